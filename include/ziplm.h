@@ -1,0 +1,132 @@
+/*
+ * ziplm.h -- C ABI of the MI355X (gfx950) structured Optimal-Brain-Surgeon pruning library.
+ *
+ * The library implements the layer-wise pruner of ZipLM (Section 3.1, Eq. 1-4, Algorithm 1):
+ *
+ *   1. ziplm_hessian_accumulate   H += scale * X X^T over batches of calibration inputs
+ *   2. ziplm_hinv                 Hinv = (H + lambda I)^-1 through a Cholesky factorisation
+ *   3. ziplm_structured_obs_prune the greedy loop: score every remaining structure (Eq. 2),
+ *                                 remove the cheapest, compensate the remaining weights (Eq. 3),
+ *                                 eliminate the structure from Hinv (Eq. 4), k times; then mask.
+ *
+ * Conventions
+ *   - Every matrix is row-major.  W is d_row x d_col; a structure is a set of COLUMNS of W
+ *     (input features).  Structure s = columns [s*group_size, (s+1)*group_size): one column for a
+ *     feed-forward neuron, d_head = 64 consecutive columns for an attention head ("Pruned
+ *     structures", Section 3.1).
+ *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns every buffer.
+ *     The library allocates no device memory: scratch space is passed in as `workspace`
+ *     (256-byte aligned, size from the matching *_workspace_bytes call) and may be reused or
+ *     freed as soon as the work enqueued by the call has finished.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     on that stream and return without waiting, except where a *_host output is requested.
+ *   - Return value: ZIPLM_OK or a negative ziplm_status.  Argument errors are detected before
+ *     anything is enqueued and leave all buffers untouched.  No exception crosses this boundary.
+ *   - Calls on different streams with disjoint buffers are independent; the library keeps no
+ *     state between calls.
+ */
+#ifndef ZIPLM_H
+#define ZIPLM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ZIPLM_OK = 0,
+    ZIPLM_ERR_INVALID_ARG = -1, /* null pointer, bad size, d_col % group_size != 0, ... */
+    ZIPLM_ERR_NOT_PD = -2,      /* a Cholesky pivot (of H + lambda I or of a block of Hinv) was <= 0 */
+    ZIPLM_ERR_WORKSPACE = -3,   /* workspace null, misaligned or smaller than *_workspace_bytes */
+    ZIPLM_ERR_DEVICE = -4,      /* a HIP call failed, or the device-side loop gave up waiting */
+    ZIPLM_ERR_UNSUPPORTED = -5  /* valid request that this build does not cover */
+} ziplm_status;
+
+typedef enum {
+    ZIPLM_X_FEATURE_MAJOR = 0, /* X[d_col][n_tok], ldx >= n_tok: the paper's X (Eq. 1)      */
+    ZIPLM_X_TOKEN_MAJOR = 1    /* X[n_tok][d_col], ldx >= d_col: how activations are captured */
+} ziplm_xlayout;
+
+/* Library version: major*10000 + minor*100 + patch. */
+int ziplm_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *ziplm_status_string(int status);
+
+/*
+ * Calibration Hessian (Section 3.1 "Saliency scores and weight update": H = X X^T; the caption
+ * of Algorithm 1 uses 2 X X^T, hence `scale`).
+ *
+ *   H (d_col x d_col, leading dimension d_col, fp32)  +=  scale * X X^T
+ *
+ * X holds n_tok calibration inputs of d_col features each, fp32, in the given layout with
+ * leading dimension ldx.  The caller zero-fills H before the first batch and may call this once
+ * per batch.  Both triangles of H are valid on return.  Products and sums are fp32 (matrix-core
+ * fp32 multiply-accumulate); no reduced-precision input format is used.
+ * n_tok == 0 is a no-op.  `workspace` may be NULL only if ziplm_hessian_workspace_bytes
+ * returns 0 for these sizes.  The result does not depend on run-to-run scheduling (partial sums
+ * are combined in a fixed order).
+ */
+int ziplm_hessian_accumulate(float *H, const float *X, int d_col, int64_t n_tok, int64_t ldx,
+                             int layout, float scale, void *workspace, size_t workspace_bytes,
+                             void *stream);
+size_t ziplm_hessian_workspace_bytes(int d_col, int64_t n_tok);
+
+/*
+ * Dampened inverse (caption of Algorithm 1: H^-1 = (2 X X^T + lambda I)^-1).
+ *
+ *   lambda = damp_rel * mean(diag H);   Hinv = (H + lambda I)^-1
+ *
+ * computed as H + lambda I = L L^T (blocked Cholesky), T = L^-1, Hinv = T^T T.  H and Hinv are
+ * d_col x d_col fp32 with leading dimension d_col; H is only read, and Hinv may alias H.  Both
+ * triangles of Hinv are written.
+ * lambda_out_host / info_host (host pointers, each may be NULL): if either is given the call
+ * waits for the stream and stores lambda and, in *info_host, 0 or 1 + the index of the first
+ * non-positive pivot.  Returns ZIPLM_ERR_NOT_PD in that case when info was requested; without
+ * info_host a failed factorisation is not reported and Hinv is meaningless.
+ */
+int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel, float *lambda_out_host,
+               int *info_host, void *workspace, size_t workspace_bytes, void *stream);
+size_t ziplm_hinv_workspace_bytes(int d_col);
+
+/*
+ * Greedy structured OBS pruning (Algorithm 1).
+ *
+ *   W        d_row x d_col fp32, in/out.  On return the removed columns are exactly zero and
+ *            the remaining ones carry the accumulated updates of Eq. 3.
+ *   Hinv     d_col x d_col fp32, in/out, symmetric positive definite on the live columns.  On
+ *            return the live x live block is the inverse Hessian of the surviving columns
+ *            (Eq. 4 applied n_remove times); removed rows and columns are exactly zero.
+ *   group_size  columns per structure; d_col % group_size == 0; 1 <= group_size <= 64 in this
+ *            build (ZIPLM_ERR_UNSUPPORTED above that).
+ *   n_remove number of structures to remove, 0 <= n_remove <= number of live structures.
+ *   order_out   int32[n_remove]: index of the structure removed at each step.
+ *   err_out     double[n_remove]: its Eq. 2 score at that step (the layer-wise error the removal
+ *            adds; the factor convention follows Eq. 2, i.e. no 1/2).
+ *   alive_in    optional uint8[d_col/group_size]; 0 marks structures removed by an earlier call
+ *            (their columns of W and rows/columns of Hinv are ignored and zeroed on return).
+ *   n_snap, snapshot_steps_host, W_snap   optional per-layer database (Section 3.2): after
+ *            snapshot_steps_host[i] removals (0..n_remove, host int32 array, read before the
+ *            call returns) the masked W is copied to W_snap + i*d_row*d_col.
+ *   info_host   optional host int: when given, the call waits for the stream and stores 0, or
+ *            1 + the step at which a block of Hinv was not positive definite (-> return
+ *            ZIPLM_ERR_NOT_PD), or -1 if the device loop timed out (-> ZIPLM_ERR_DEVICE).
+ *
+ * The state is held in fp64 for Hinv and fp32 for W inside the call; scores are reduced in
+ * fp64.  Ties in the argmin go to the lowest structure index.  Eq. 3 and Eq. 4 of one step use
+ * the rows of Hinv as they were before that step.
+ */
+int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int group_size,
+                               int n_remove, int32_t *order_out, double *err_out,
+                               const uint8_t *alive_in, int n_snap,
+                               const int32_t *snapshot_steps_host, float *W_snap,
+                               int *info_host, void *workspace, size_t workspace_bytes,
+                               void *stream);
+size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ZIPLM_H */

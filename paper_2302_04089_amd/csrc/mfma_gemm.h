@@ -1,0 +1,344 @@
+// fp32 matrix-core GEMM building block for gfx950 (CDNA4), used by the Hessian accumulation and by
+// the blocked Cholesky / triangular inverse.
+//
+//   C[M x N] = alpha * opA(A) * opB(B) + beta * C
+//
+// One workgroup of 256 threads (4 wavefronts of 64 lanes, arranged 2 x 2) computes a 128 x 128 tile
+// of C; each wavefront owns a 64 x 64 sub-tile as 2 x 2 accumulators of v_mfma_f32_32x32x2_f32.
+// The K loop advances in slices of 32, staged through LDS with two buffers so that the global loads
+// of slice k+1 overlap the matrix instructions of slice k (one barrier per slice).
+//
+// Operand storage ("mode") is described from the point of view of the tile an operand contributes,
+// a (128 rows) x (32 k) slab whose rows are the M index for A and the N index for B:
+//   K_CONTIG : element (r, k) at base[r * ld + k]   (row-major operand, k fastest)
+//   R_CONTIG : element (r, k) at base[k * ld + r]   (the operand's transpose is row-major)
+// so  NT = (A K_CONTIG, B K_CONTIG)  computes A B^T for row-major A [M][K], B [N][K];
+//     NN = (A K_CONTIG, B R_CONTIG)  computes A B   for row-major B [K][N];
+//     TN = (A R_CONTIG, B R_CONTIG)  computes A^T B for row-major A [K][M], B [K][N].
+//
+// Matrix-instruction operand layout (32x32x2, wave64): lane l supplies A[row = l % 32][k = l / 32] and
+// B[k = l / 32][col = l % 32]; accumulator register v of lane l holds
+// C[row = 8 * (v / 4) + 4 * (l / 32) + (v % 4)][col = l % 32].
+// The k index inside a slice is permuted identically for A and B (lanes 0-31 take k = 8j..8j+3,
+// lanes 32-63 take k = 8j+4..8j+7, over four consecutive instructions), which leaves the
+// contraction unchanged and lets a K_CONTIG operand be fetched with one 128-bit LDS read.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ziplm {
+namespace gemm {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128;      // tile rows
+constexpr int BN = 128;      // tile cols
+constexpr int BK = 32;       // k slice
+constexpr int THREADS = 256;
+constexpr int PITCH_K = 36;  // floats per row of a K_CONTIG slab in LDS ([128][36]); 36 = 4 (mod 32)
+constexpr int PITCH_R = 128; // floats per k-row of an R_CONTIG slab in LDS ([32][128])
+constexpr int SLAB = BM * PITCH_K;  // floats reserved per operand per buffer (>= 32 * 128)
+
+enum Mode { K_CONTIG = 0, R_CONTIG = 1 };
+
+enum Flags : unsigned {
+    F_LOWER_ONLY = 1u,     // compute only tiles with tile_col <= tile_row (square output)
+    F_MIRROR = 2u,         // also write the transpose of every strictly-lower tile (symmetric output)
+    F_KSTART_N = 4u,       // k starts at tile_col * 128 (B is lower triangular: B(k, n) = 0 for k < n)
+    F_KSTART_MAXMN = 8u,   // k starts at max(tile_row, tile_col) * 128 (T^T T with T lower triangular)
+    F_KEND_M = 16u,        // k ends at (tile_row + 1) * 128 (A is lower triangular: A(m, k) = 0 for k > m)
+    F_TRI_GRID = 32u,      // blockIdx.x enumerates the lower-triangular tile list instead of a 2-D grid
+    F_PARTIAL = 64u        // split-K: write raw accumulators to `partial`, no epilogue
+};
+
+struct Args {
+    const float *A;
+    const float *B;
+    float *C;
+    int M, N;
+    int64_t K;
+    int64_t lda, ldb, ldc;
+    float alpha, beta;
+    unsigned flags;
+    // batching (blockIdx.z) -- element offsets added per batch index
+    int64_t strideA, strideB, strideC;
+    // split-K (blockIdx.y when F_PARTIAL): k range of split s is [s * k_chunk, min(K, (s+1) * k_chunk))
+    int64_t k_chunk;
+    float *partial;   // [split][tile][64 regs][256 threads]
+    int tiles_n;      // number of tile columns (2-D grid decoding)
+};
+
+// ---------------------------------------------------------------------------------------------
+// Global -> register -> LDS staging of one 128 x 32 slab.
+// ---------------------------------------------------------------------------------------------
+template <int MODE, bool VEC, bool KGUARD>
+struct Slab {
+    floatx4 r[4];
+
+    __device__ __forceinline__ void load(const float *__restrict__ base, int64_t ld, int row0,
+                                         int rows, int64_t k0, int64_t kend, int tid) {
+        if (MODE == K_CONTIG) {
+            const int c4 = tid & 7;         // which group of 4 k
+            const int rr = tid >> 3;        // 0..31
+            const int64_t k = k0 + 4 * c4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = row0 + rr + 32 * q;
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};
+                if (row < rows) {
+                    const float *p = base + (int64_t)row * ld + k;
+                    if (VEC && (!KGUARD || k + 3 < kend)) {
+                        v = *reinterpret_cast<const floatx4 *>(p);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (!KGUARD || k + e < kend) v[e] = p[e];
+                    }
+                }
+                r[q] = v;
+            }
+        } else {
+            const int i4 = tid & 31;        // which group of 4 rows
+            const int kr = tid >> 5;        // 0..7
+            const int row = row0 + 4 * i4;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int64_t k = k0 + kr + 8 * q;
+                floatx4 v = {0.f, 0.f, 0.f, 0.f};
+                if (!KGUARD || k < kend) {
+                    const float *p = base + k * ld + row;
+                    if (VEC && row + 3 < rows) {
+                        v = *reinterpret_cast<const floatx4 *>(p);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (row + e < rows) v[e] = p[e];
+                    }
+                }
+                r[q] = v;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store(float *__restrict__ s, int tid) const {
+        if (MODE == K_CONTIG) {
+            const int c4 = tid & 7, rr = tid >> 3;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<floatx4 *>(s + (rr + 32 * q) * PITCH_K + 4 * c4) = r[q];
+        } else {
+            const int i4 = tid & 31, kr = tid >> 5;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<floatx4 *>(s + (kr + 8 * q) * PITCH_R + 4 * i4) = r[q];
+        }
+    }
+};
+
+// Four k-values of one 32-row fragment for the calling lane: k = kk + 4 * half + {0,1,2,3}.
+template <int MODE>
+__device__ __forceinline__ floatx4 fragment(const float *__restrict__ s, int row, int kk, int half) {
+    if (MODE == K_CONTIG) {
+        return *reinterpret_cast<const floatx4 *>(s + row * PITCH_K + kk + 4 * half);
+    } else {
+        floatx4 v;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = s[(kk + 4 * half + q) * PITCH_R + row];
+        return v;
+    }
+}
+
+// One k slice of 32 for the calling wavefront's 64 x 64 sub-tile.
+template <int AMODE, int BMODE>
+__device__ __forceinline__ void mma_slice(const float *__restrict__ sA, const float *__restrict__ sB,
+                                          floatx16 (&acc)[2][2], int wm, int wn, int lane) {
+    const int r = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += 8) {
+        floatx4 a[2], b[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = fragment<AMODE>(sA, wm * 64 + i * 32 + r, kk, half);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) b[j] = fragment<BMODE>(sB, wn * 64 + j * 32 + r, kk, half);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i][q], b[j][q], acc[i][j], 0, 0, 0);
+    }
+}
+
+// Decodes index t of the lower-triangular tile list (0,0),(1,0),(1,1),(2,0),... into (row, col).
+__device__ __forceinline__ void tri_decode(int t, int &tm, int &tn) {
+    int m = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+    while ((m + 1) * (m + 2) / 2 <= t) ++m;
+    while (m * (m + 1) / 2 > t) --m;
+    tm = m;
+    tn = t - m * (m + 1) / 2;
+}
+
+// Epilogue for one accumulator set: C = alpha * acc + beta * C, optional mirrored copy.
+__device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__restrict__ C, int64_t ldc,
+                                         int M, int N, int tm, int tn, float alpha, float beta,
+                                         bool mirror, int wm, int wn, int lane) {
+    const int r = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int col = tn * BN + wn * 64 + j * 32 + r;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = tm * BM + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                if (row < M && col < N) {
+                    float *p = C + (int64_t)row * ldc + col;
+                    float val = alpha * acc[i][j][v];
+                    if (beta != 0.f) val += beta * (*p);
+                    *p = val;
+                    if (mirror) {
+                        // symmetric output (M == N): transposed element of a strictly-lower tile
+                        float *pt = C + (int64_t)col * ldc + row;
+                        float vt = alpha * acc[i][j][v];
+                        if (beta != 0.f) vt += beta * (*pt);
+                        *pt = vt;
+                    }
+                }
+            }
+        }
+}
+
+template <int AMODE, int BMODE, bool VEC, bool KGUARD>
+__global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
+    __shared__ __attribute__((aligned(16))) float lds[2][2][SLAB];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    int tm, tn, split = 0, tile_linear;
+    if (g.flags & F_TRI_GRID) {
+        tile_linear = blockIdx.x;
+        tri_decode(tile_linear, tm, tn);
+    } else {
+        tile_linear = blockIdx.x;
+        tm = blockIdx.x / g.tiles_n;
+        tn = blockIdx.x % g.tiles_n;
+        if ((g.flags & F_LOWER_ONLY) && tn > tm) return;
+    }
+    if (g.flags & F_PARTIAL) split = blockIdx.y;
+
+    const float *A = g.A + (int64_t)blockIdx.z * g.strideA;
+    const float *B = g.B + (int64_t)blockIdx.z * g.strideB;
+    float *C = g.C + (int64_t)blockIdx.z * g.strideC;
+
+    int64_t kb = 0, ke = g.K;
+    if (g.flags & F_KSTART_N) kb = (int64_t)tn * BN;
+    if (g.flags & F_KSTART_MAXMN) kb = (int64_t)(tm > tn ? tm : tn) * BM;
+    if (g.flags & F_KEND_M) { int64_t e = (int64_t)(tm + 1) * BM; ke = e < ke ? e : ke; }
+    if (g.flags & F_PARTIAL) {
+        kb = (int64_t)split * g.k_chunk;
+        int64_t e = kb + g.k_chunk;
+        ke = e < g.K ? e : g.K;
+    }
+
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int64_t nslices = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+    Slab<AMODE, VEC, KGUARD> ra;
+    Slab<BMODE, VEC, KGUARD> rb;
+    if (nslices > 0) {
+        ra.load(A, g.lda, tm * BM, g.M, kb, ke, tid);
+        rb.load(B, g.ldb, tn * BN, g.N, kb, ke, tid);
+        ra.store(lds[0][0], tid);
+        rb.store(lds[0][1], tid);
+    }
+    __syncthreads();
+    int cur = 0;
+    for (int64_t s = 0; s < nslices; ++s) {
+        const bool more = (s + 1 < nslices);
+        if (more) {
+            ra.load(A, g.lda, tm * BM, g.M, kb + (s + 1) * BK, ke, tid);
+            rb.load(B, g.ldb, tn * BN, g.N, kb + (s + 1) * BK, ke, tid);
+        }
+        mma_slice<AMODE, BMODE>(lds[cur][0], lds[cur][1], acc, wm, wn, lane);
+        if (more) {
+            ra.store(lds[cur ^ 1][0], tid);
+            rb.store(lds[cur ^ 1][1], tid);
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+
+    if (g.flags & F_PARTIAL) {
+        float *dst = g.partial + ((int64_t)split * gridDim.x + tile_linear) * (64 * THREADS);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) dst[((i * 2 + j) * 16 + v) * THREADS + tid] = acc[i][j][v];
+        return;
+    }
+    const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
+    epilogue(acc, C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
+}
+
+// Second pass of a split-K product: sums the raw accumulators of all splits in split order and
+// applies the epilogue.  Same thread <-> element mapping as gemm_kernel.
+static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, int nsplit, int ntiles) {
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int tile_linear = blockIdx.x;
+    int tm, tn;
+    if (g.flags & F_TRI_GRID) {
+        tri_decode(tile_linear, tm, tn);
+    } else {
+        tm = tile_linear / g.tiles_n;
+        tn = tile_linear % g.tiles_n;
+        if ((g.flags & F_LOWER_ONLY) && tn > tm) return;
+    }
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int s = 0; s < nsplit; ++s) {
+        const float *src = g.partial + ((int64_t)s * ntiles + tile_linear) * (64 * THREADS);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * 2 + j) * 16 + v) * THREADS + tid];
+    }
+    const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
+    epilogue(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
+}
+
+// Host-side launch of a full (non split-K) product.  `batch` >= 1.
+template <int AMODE, int BMODE, bool VEC, bool KGUARD>
+inline hipError_t launch(Args g, int batch, hipStream_t stream) {
+    if (g.M <= 0 || g.N <= 0 || batch <= 0) return hipSuccess;
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    g.tiles_n = tiles_n;
+    dim3 grid;
+    if (g.flags & F_TRI_GRID) grid = dim3(tiles_m * (tiles_m + 1) / 2, 1, batch);
+    else grid = dim3(tiles_m * tiles_n, 1, batch);
+    hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD>), grid, dim3(THREADS), 0, stream, g);
+    return hipGetLastError();
+}
+
+}  // namespace gemm
+}  // namespace ziplm

@@ -1,0 +1,605 @@
+// Greedy structured OBS pruning (Algorithm 1; Eq. 2 score, Eq. 3 weight update, Eq. 4 elimination
+// of the removed structure from the inverse Hessian).
+//
+// State inside a call: Hd = the inverse Hessian in fp64 (workspace copy of the caller's fp32 Hinv;
+// fp32 storage of this matrix loses the 1e-4 agreement with exact arithmetic over thousands of
+// eliminations when H is ill conditioned), W in fp32 in place, score reductions in fp64.
+//
+// Single columns (group_size == 1): one persistent cooperative kernel runs all n_remove steps; the
+// steps are separated by device-wide barriers, the host is not involved.  Per step
+//     candidates -> barrier -> argmin (every workgroup redundantly) + update -> barrier.
+// The update pass over W also produces the partial squared column norms the next step's scores need
+// and the pass over Hd refreshes a compact copy of its diagonal, so a step reads the state once.
+// Rows of Hd that belong to removed columns are skipped; removed columns are masked per lane.
+//
+// Larger structures (2 <= group_size <= 64): a short sequence of ordinary launches per step
+//     score (one workgroup per live structure: block inverse in LDS, Gram contraction)
+//     -> select -> prepare (C_H = Hd[:,S] B, C_W = W[:,S] B) -> update,
+// with the selected index handed from kernel to kernel in device memory.
+#include <hip/hip_cooperative_groups.h>
+
+#include "common.h"
+
+namespace ziplm {
+
+int device_cu_count();
+
+constexpr int PT = 512;        // threads per workgroup of the persistent kernel (= columns per tile)
+constexpr int H_ROWS = 8;      // rows of Hd per tile
+constexpr int W_ROWS = 32;     // rows of W per tile (one partial norm per tile and column)
+constexpr unsigned long long kBarrierTimeoutTicks = 400000000ull;  // 4 s of the 100 MHz wall clock
+
+struct PruneState {
+    float *W;
+    float *Hinv;
+    double *Hd;
+    int m, d, g, G, n_remove;
+    int32_t *order;
+    double *err;
+    const uint8_t *alive_in;
+    uint8_t *alive;      // per structure
+    double *Pn;          // [nrc][d] partial squared column norms (g == 1)
+    double *diag;        // [d] compact diagonal of Hd (g == 1)
+    double *cand_score;  // [ncc]
+    int *cand_idx;       // [ncc]
+    int nrc, ncc;
+    const int *snap_of_step;  // [n_remove + 1] first snapshot taken after that many removals, or -1
+    const int *snap_next;     // [n_snap] next snapshot at the same step, or -1
+    float *W_snap;
+    unsigned *bar;       // barrier arrival counter
+    int *status;         // 0 ok, >0: 1 + step with a non-positive pivot, -1: barrier timed out
+    // group path
+    double *score;       // [G]
+    double *Binv;        // [G][g*g]
+    double *CH;          // [d][g]
+    double *CW;          // [m][g]
+    int *sel;            // selected structure of the current step
+};
+
+// ---------------------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool better(double s1, int i1, double s2, int i2) {
+    // strict order: smaller score first, lower index on equal scores; index -1 = "none"
+    if (i2 < 0) return i1 >= 0;
+    if (i1 < 0) return false;
+    return (s1 < s2) || (s1 == s2 && i1 < i2);
+}
+
+template <int NT>
+__device__ __forceinline__ void block_argmin(double &s, int &i, double *sh_s, int *sh_i) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const double so = __shfl_down(s, o);
+        const int io = __shfl_down(i, o);
+        if (better(so, io, s, i)) { s = so; i = io; }
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (lane == 0) { sh_s[wave] = s; sh_i[wave] = i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double bs = sh_s[0];
+        int bi = sh_i[0];
+        for (int w = 1; w < NT / 64; ++w)
+            if (better(sh_s[w], sh_i[w], bs, bi)) { bs = sh_s[w]; bi = sh_i[w]; }
+        sh_s[0] = bs;
+        sh_i[0] = bi;
+    }
+    __syncthreads();
+    s = sh_s[0];
+    i = sh_i[0];
+    __syncthreads();
+}
+
+// Device-wide barrier for a cooperative launch (all workgroups resident).  A monotonically
+// increasing arrival counter; `epoch` counts the barriers this workgroup has passed.  Waiting is
+// bounded: after kBarrierTimeoutTicks the waiter raises status = -1, which every waiter polls, so
+// that all workgroups leave their loops and the grid drains.  Returns false on abort.
+__device__ __forceinline__ bool grid_barrier(unsigned *counter, unsigned &epoch, unsigned nblocks, int *status) {
+    __shared__ int ok_flag;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        epoch += 1;
+        __threadfence();
+        atomicAdd(counter, 1u);
+        const unsigned target = epoch * nblocks;
+        const unsigned long long t0 = wall_clock64();
+        int ok = 1;
+        unsigned spins = 0;
+        while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            __builtin_amdgcn_s_sleep(1);
+            if ((++spins & 63u) == 0u) {
+                if (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == -1) { ok = 0; break; }
+                if (wall_clock64() - t0 > kBarrierTimeoutTicks) {
+                    __hip_atomic_store(status, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ok = 0;
+                    break;
+                }
+            }
+        }
+        __threadfence();
+        ok_flag = ok;
+    }
+    __syncthreads();
+    const bool ok = ok_flag != 0;
+    __syncthreads();
+    return ok;
+}
+
+__device__ __forceinline__ void snapshot_copy(const PruneState &P, int removed, int gtid, int gthreads) {
+    int q = P.snap_of_step ? P.snap_of_step[removed] : -1;
+    while (q >= 0) {
+        float *dst = P.W_snap + (size_t)q * P.m * P.d;
+        const size_t total = (size_t)P.m * P.d;
+        for (size_t idx = gtid; idx < total; idx += gthreads) {
+            const int j = (int)(idx % P.d);
+            dst[idx] = P.alive[j / P.g] ? P.W[idx] : 0.f;
+        }
+        q = P.snap_next[q];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// group_size == 1: persistent cooperative kernel
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(PT) void prune_columns_kernel(PruneState P) {
+    __shared__ double sh_s[PT / 64];
+    __shared__ int sh_i[PT / 64];
+    const int nb = gridDim.x, b = blockIdx.x, tid = threadIdx.x;
+    const int gtid = b * PT + tid, gthreads = nb * PT;
+    const int d = P.d, m = P.m;
+    unsigned epoch = 0;
+
+    // ---- set-up: fp64 copy of the inverse Hessian, alive flags, diagonal, partial column norms ----
+    {
+        const size_t total = (size_t)d * d;
+        for (size_t idx = gtid; idx < total; idx += gthreads) P.Hd[idx] = (double)P.Hinv[idx];
+        for (int j = gtid; j < d; j += gthreads) {
+            P.alive[j] = P.alive_in ? (P.alive_in[j] != 0) : 1;
+            P.diag[j] = (double)P.Hinv[(size_t)j * d + j];
+        }
+        for (int tile = b; tile < P.nrc * P.ncc; tile += nb) {
+            const int rc = tile / P.ncc, j = (tile % P.ncc) * PT + tid;
+            if (j < d) {
+                double s = 0.0;
+                const int i1 = min(m, (rc + 1) * W_ROWS);
+                for (int i = rc * W_ROWS; i < i1; ++i) {
+                    const double w = (double)P.W[(size_t)i * d + j];
+                    s += w * w;
+                }
+                P.Pn[(size_t)rc * d + j] = s;
+            }
+        }
+    }
+    bool ok = grid_barrier(P.bar, epoch, nb, P.status);
+
+    const int n_h_tiles = ((d + H_ROWS - 1) / H_ROWS) * P.ncc;
+    const int n_w_tiles = P.nrc * P.ncc;
+    int t = 0;
+    for (; ok && t < P.n_remove; ++t) {
+        snapshot_copy(P, t, gtid, gthreads);
+
+        // ---- candidates: Eq. 2 for single columns, ||W[:,j]||^2 / Hd[j][j], per chunk of PT columns
+        for (int cc = b; cc < P.ncc; cc += nb) {
+            const int j = cc * PT + tid;
+            double s = 0.0;
+            int idx = -1;
+            if (j < d && P.alive[j]) {
+                double nrm = 0.0;
+                for (int rc = 0; rc < P.nrc; ++rc) nrm += P.Pn[(size_t)rc * d + j];
+                const double dj = P.diag[j];
+                if (dj > 0.0) { s = nrm / dj; idx = j; }
+                else __hip_atomic_store(P.status, 1 + t, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            block_argmin<PT>(s, idx, sh_s, sh_i);
+            if (tid == 0) { P.cand_score[cc] = s; P.cand_idx[cc] = idx; }
+        }
+        ok = grid_barrier(P.bar, epoch, nb, P.status);
+        if (!ok) break;
+
+        // ---- argmin over the candidates, redundantly in every workgroup (same inputs, same result)
+        double best = 0.0;
+        int p = -1;
+        for (int cc = 0; cc < P.ncc; ++cc) {
+            const double s = P.cand_score[cc];
+            const int i = P.cand_idx[cc];
+            if (better(s, i, best, p)) { best = s; p = i; }
+        }
+        const int st = __hip_atomic_load(P.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (p < 0 || st != 0) {     // uniform over the grid: status was written before the barrier
+            if (gtid == 0 && st == 0) *P.status = 1 + t;
+            break;
+        }
+        if (gtid == 0) {
+            P.order[t] = p;
+            P.err[t] = best;
+            P.alive[p] = 0;   // readers of this step treat p as removed either way
+        }
+
+        // ---- Eq. 3 and Eq. 4 with the pre-step row p of Hd (row and column p are not written) ----
+        const double *R = P.Hd + (size_t)p * d;
+        const double inv = 1.0 / R[p];
+        for (int tile = b; tile < n_h_tiles + n_w_tiles; tile += nb) {
+            if (tile < n_h_tiles) {
+                const int rt = tile / P.ncc, j = (tile % P.ncc) * PT + tid;
+                const bool live = (j < d) && (j != p) && P.alive[j];
+                const double rj = live ? R[j] : 0.0;
+                const int i1 = min(d, (rt + 1) * H_ROWS);
+                for (int i = rt * H_ROWS; i < i1; ++i) {
+                    if (i == p || !P.alive[i]) continue;
+                    const double ci = R[i] * inv;
+                    if (live) {
+                        double *h = P.Hd + (size_t)i * d + j;
+                        const double v = *h - ci * rj;
+                        *h = v;
+                        if (i == j) P.diag[j] = v;
+                    }
+                }
+            } else {
+                const int wt = tile - n_h_tiles;
+                const int rc = wt / P.ncc, j = (wt % P.ncc) * PT + tid;
+                const bool live = (j < d) && (j != p) && P.alive[j];
+                const double rj = live ? R[j] : 0.0;
+                const int i1 = min(m, (rc + 1) * W_ROWS);
+                double s = 0.0;
+                for (int i = rc * W_ROWS; i < i1; ++i) {
+                    const double cw = (double)P.W[(size_t)i * d + p] * inv;
+                    if (live) {
+                        float *w = P.W + (size_t)i * d + j;
+                        const float v = (float)((double)(*w) - cw * rj);
+                        *w = v;
+                        s += (double)v * (double)v;
+                    }
+                }
+                if (live) P.Pn[(size_t)rc * d + j] = s;
+            }
+        }
+        ok = grid_barrier(P.bar, epoch, nb, P.status);
+    }
+
+    // ---- final masking (last line of Algorithm 1) and write-back of the surviving inverse -------
+    if (ok && t == P.n_remove) snapshot_copy(P, P.n_remove, gtid, gthreads);
+    {
+        const size_t totalw = (size_t)m * d;
+        for (size_t idx = gtid; idx < totalw; idx += gthreads)
+            if (!P.alive[idx % d]) P.W[idx] = 0.f;
+        const size_t total = (size_t)d * d;
+        for (size_t idx = gtid; idx < total; idx += gthreads) {
+            const int i = (int)(idx / d), j = (int)(idx % d);
+            P.Hinv[idx] = (P.alive[i] && P.alive[j]) ? (float)P.Hd[idx] : 0.f;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// group_size > 1: per-step launches
+// ---------------------------------------------------------------------------------------------
+constexpr int GMAX = 64;
+
+__global__ __launch_bounds__(256) void group_init_kernel(PruneState P) {
+    const int gtid = blockIdx.x * 256 + threadIdx.x, gthreads = gridDim.x * 256;
+    const size_t total = (size_t)P.d * P.d;
+    for (size_t idx = gtid; idx < total; idx += gthreads) P.Hd[idx] = (double)P.Hinv[idx];
+    for (int s = gtid; s < P.G; s += gthreads) P.alive[s] = P.alive_in ? (P.alive_in[s] != 0) : 1;
+    if (gtid == 0) *P.sel = -1;
+}
+
+// One workgroup per structure s: B = (Hd[S,S])^-1 by in-place Gauss-Jordan elimination in LDS (the
+// pivots of a positive definite block are its successive Schur complements, all > 0; no pivoting),
+// then score_s = sum_i w_i B w_i^T = <B, W[:,S]^T W[:,S]> with the Gram matrix accumulated in fp64.
+__global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step) {
+    __shared__ double Bm[GMAX][GMAX + 1];
+    __shared__ double rowk[GMAX], colk[GMAX];
+    __shared__ float Wt[64][GMAX + 1];
+    __shared__ double red[256];
+    __shared__ int bad;
+    const int s = blockIdx.x, tid = threadIdx.x, g = P.g, d = P.d;
+    if (*P.status != 0) return;
+    if (!P.alive[s]) {
+        if (tid == 0) P.score[s] = 0.0;
+        return;
+    }
+    const int c0 = s * g;
+    for (int e = tid; e < g * g; e += 256) Bm[e / g][e % g] = P.Hd[(size_t)(c0 + e / g) * d + c0 + e % g];
+    if (tid == 0) bad = 0;
+    __syncthreads();
+    for (int k = 0; k < g; ++k) {
+        const double piv = Bm[k][k];
+        if (tid < g) { rowk[tid] = Bm[k][tid]; colk[tid] = Bm[tid][k]; }
+        __syncthreads();
+        if (!(piv > 0.0)) {          // uniform: every thread read the same pivot
+            if (tid == 0) bad = 1;
+            break;
+        }
+        const double ip = 1.0 / piv;
+        for (int e = tid; e < g * g; e += 256) {
+            const int i = e / g, j = e % g;
+            double v;
+            if (i == k && j == k) v = ip;
+            else if (i == k) v = rowk[j] * ip;
+            else if (j == k) v = -colk[i] * ip;
+            else v = Bm[i][j] - colk[i] * rowk[j] * ip;
+            Bm[i][j] = v;
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    if (bad) {
+        if (tid == 0) atomicCAS(P.status, 0, 1 + step);
+        return;
+    }
+    double *Bout = P.Binv + (size_t)s * g * g;
+    for (int e = tid; e < g * g; e += 256) Bout[e] = Bm[e / g][e % g];
+
+    // Gram contraction: thread owns pairs e = tid + 256 q
+    double acc[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) acc[q] = 0.0;
+    for (int i0 = 0; i0 < P.m; i0 += 64) {
+        for (int e = tid; e < 64 * g; e += 256) {
+            const int r = e / g, c = e % g;
+            Wt[r][c] = (i0 + r < P.m) ? P.W[(size_t)(i0 + r) * d + c0 + c] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < 16; ++q) {
+            const int e = tid + 256 * q;
+            if (e < g * g) {
+                const int a = e / g, c = e % g;
+                double sacc = acc[q];
+                for (int r = 0; r < 64; ++r) sacc += (double)Wt[r][a] * (double)Wt[r][c];
+                acc[q] = sacc;
+            }
+        }
+        __syncthreads();
+    }
+    double part = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) {
+        const int e = tid + 256 * q;
+        if (e < g * g) part += Bm[e / g][e % g] * acc[q];
+    }
+    red[tid] = part;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    if (tid == 0) P.score[s] = red[0];
+}
+
+__global__ __launch_bounds__(256) void group_select_kernel(PruneState P, int step) {
+    __shared__ double sh_s[4];
+    __shared__ int sh_i[4];
+    if (*P.status != 0) return;
+    double s = 0.0;
+    int idx = -1;
+    for (int q = threadIdx.x; q < P.G; q += 256) {
+        if (!P.alive[q]) continue;
+        const double v = P.score[q];
+        if (better(v, q, s, idx)) { s = v; idx = q; }
+    }
+    block_argmin<256>(s, idx, sh_s, sh_i);
+    if (threadIdx.x == 0) {
+        if (idx < 0) { *P.status = 1 + step; return; }
+        *P.sel = idx;
+        P.order[step] = idx;
+        P.err[step] = s;
+        P.alive[idx] = 0;
+    }
+}
+
+// C_H[i][b] = sum_a Hd[i][S_a] B[a][b] for every row i of Hd; C_W[i][b] likewise for W.
+__global__ __launch_bounds__(256) void group_prepare_kernel(PruneState P) {
+    if (*P.status != 0) return;
+    const int g = P.g, d = P.d, p = *P.sel, c0 = p * g;
+    const double *B = P.Binv + (size_t)p * g * g;
+    const int total = (d + P.m) * g;
+    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
+        const int i = e / g, b = e % g;
+        double s = 0.0;
+        if (i < d) {
+            for (int a = 0; a < g; ++a) s += P.Hd[(size_t)i * d + c0 + a] * B[a * g + b];
+            P.CH[(size_t)i * g + b] = s;
+        } else {
+            const int iw = i - d;
+            for (int a = 0; a < g; ++a) s += (double)P.W[(size_t)iw * d + c0 + a] * B[a * g + b];
+            P.CW[(size_t)iw * g + b] = s;
+        }
+    }
+}
+
+// Hd[i][j] -= sum_b C_H[i][b] Hd[S_b][j]   and   W[i][j] -= sum_b C_W[i][b] Hd[S_b][j]
+// Rows and columns of the selected structure and of earlier removed ones are left alone (they are
+// zeroed at the end); the rows Hd[S,:] read here are therefore the pre-step ones.
+constexpr int G_ROWS = 16;
+__global__ __launch_bounds__(256) void group_update_kernel(PruneState P) {
+    if (*P.status != 0) return;
+    const int g = P.g, d = P.d, m = P.m, p = *P.sel, c0 = p * g;
+    const int ncc = (d + 255) / 256;
+    const int n_h_tiles = ((d + G_ROWS - 1) / G_ROWS) * ncc;
+    const int n_w_tiles = ((m + G_ROWS - 1) / G_ROWS) * ncc;
+    for (int tile = blockIdx.x; tile < n_h_tiles + n_w_tiles; tile += gridDim.x) {
+        const bool is_h = tile < n_h_tiles;
+        const int tt = is_h ? tile : tile - n_h_tiles;
+        const int i0 = (tt / ncc) * G_ROWS, j = (tt % ncc) * 256 + threadIdx.x;
+        const int rows = is_h ? d : m;
+        const bool live = (j < d) && P.alive[j / g];   // the selected structure is already marked removed
+        const double *C = is_h ? P.CH : P.CW;
+        double acc[G_ROWS];
+#pragma unroll
+        for (int ii = 0; ii < G_ROWS; ++ii) acc[ii] = 0.0;
+        if (live) {
+            for (int b = 0; b < g; ++b) {
+                const double r = P.Hd[(size_t)(c0 + b) * d + j];
+#pragma unroll
+                for (int ii = 0; ii < G_ROWS; ++ii) {
+                    const int i = i0 + ii;
+                    if (i < rows) acc[ii] += C[(size_t)i * g + b] * r;
+                }
+            }
+#pragma unroll
+            for (int ii = 0; ii < G_ROWS; ++ii) {
+                const int i = i0 + ii;
+                if (i >= rows) continue;
+                if (is_h) {
+                    if (!P.alive[i / g]) continue;
+                    P.Hd[(size_t)i * d + j] -= acc[ii];
+                } else {
+                    float *w = P.W + (size_t)i * d + j;
+                    *w = (float)((double)(*w) - acc[ii]);
+                }
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void group_snapshot_kernel(PruneState P, int removed) {
+    snapshot_copy(P, removed, blockIdx.x * 256 + threadIdx.x, gridDim.x * 256);
+}
+
+__global__ __launch_bounds__(256) void group_final_kernel(PruneState P) {
+    const int gtid = blockIdx.x * 256 + threadIdx.x, gthreads = gridDim.x * 256;
+    const int d = P.d, g = P.g;
+    const size_t totalw = (size_t)P.m * d;
+    for (size_t idx = gtid; idx < totalw; idx += gthreads)
+        if (!P.alive[(idx % d) / g]) P.W[idx] = 0.f;
+    const size_t total = (size_t)d * d;
+    for (size_t idx = gtid; idx < total; idx += gthreads) {
+        const int i = (int)(idx / d), j = (int)(idx % d);
+        P.Hinv[idx] = (P.alive[i / g] && P.alive[j / g]) ? (float)P.Hd[idx] : 0.f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------------------
+struct PruneLayout {
+    PruneState st;
+    int *snap_of_step;
+    int *snap_next;
+    size_t bytes;
+};
+
+static PruneLayout prune_layout(int d_row, int d_col, int g, int n_snap, void *ws) {
+    PruneLayout l = {};
+    PruneState &s = l.st;
+    s.m = d_row; s.d = d_col; s.g = g; s.G = d_col / g;
+    s.nrc = (d_row + W_ROWS - 1) / W_ROWS;
+    s.ncc = (d_col + PT - 1) / PT;
+    Carver c(ws);
+    s.Hd = c.take<double>((size_t)d_col * d_col);
+    s.alive = c.take<uint8_t>((size_t)s.G);
+    s.bar = c.take<unsigned>(1);
+    s.status = c.take<int>(1);
+    s.sel = c.take<int>(1);
+    l.snap_of_step = c.take<int>((size_t)s.G + 1);
+    l.snap_next = c.take<int>((size_t)(n_snap > 0 ? n_snap : 1));
+    if (g == 1) {
+        s.Pn = c.take<double>((size_t)s.nrc * d_col);
+        s.diag = c.take<double>((size_t)d_col);
+        s.cand_score = c.take<double>((size_t)s.ncc);
+        s.cand_idx = c.take<int>((size_t)s.ncc);
+    } else {
+        s.score = c.take<double>((size_t)s.G);
+        s.Binv = c.take<double>((size_t)s.G * g * g);
+        s.CH = c.take<double>((size_t)d_col * g);
+        s.CW = c.take<double>((size_t)d_row * g);
+    }
+    l.bytes = c.off;
+    return l;
+}
+
+}  // namespace ziplm
+
+extern "C" size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap) {
+    if (d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size) return 0;
+    return ziplm::prune_layout(d_row, d_col, group_size, n_snap, nullptr).bytes;
+}
+
+extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int group_size,
+                                          int n_remove, int32_t *order_out, double *err_out,
+                                          const uint8_t *alive_in, int n_snap,
+                                          const int32_t *snapshot_steps_host, float *W_snap, int *info_host,
+                                          void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace ziplm;
+    if (!W || !Hinv || d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size) return ZIPLM_ERR_INVALID_ARG;
+    const int G = d_col / group_size;
+    if (n_remove < 0 || n_remove > G) return ZIPLM_ERR_INVALID_ARG;
+    if (n_remove > 0 && (!order_out || !err_out)) return ZIPLM_ERR_INVALID_ARG;
+    if (n_snap < 0 || (n_snap > 0 && (!snapshot_steps_host || !W_snap))) return ZIPLM_ERR_INVALID_ARG;
+    for (int q = 0; q < n_snap; ++q)
+        if (snapshot_steps_host[q] < 0 || snapshot_steps_host[q] > n_remove) return ZIPLM_ERR_INVALID_ARG;
+    if (group_size > GMAX) return ZIPLM_ERR_UNSUPPORTED;
+    const size_t need = ziplm_prune_workspace_bytes(d_row, d_col, group_size, n_snap);
+    if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    PruneLayout l = prune_layout(d_row, d_col, group_size, n_snap, workspace);
+    PruneState &P = l.st;
+    P.W = W; P.Hinv = Hinv; P.n_remove = n_remove;
+    P.order = order_out; P.err = err_out; P.alive_in = alive_in; P.W_snap = W_snap;
+
+    // snapshot schedule: first snapshot per step + chain of further ones at the same step
+    if (n_snap > 0) {
+        int *of_step = new int[(size_t)G + 1];
+        int *next = new int[(size_t)n_snap];
+        for (int t = 0; t <= G; ++t) of_step[t] = -1;
+        for (int q = n_snap - 1; q >= 0; --q) {
+            next[q] = of_step[snapshot_steps_host[q]];
+            of_step[snapshot_steps_host[q]] = q;
+        }
+        hipError_t e1 = hipMemcpyAsync(l.snap_of_step, of_step, sizeof(int) * ((size_t)G + 1), hipMemcpyHostToDevice, st);
+        hipError_t e2 = hipMemcpyAsync(l.snap_next, next, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st);
+        // pageable source: the copies above have staged the data when they return
+        hipError_t e3 = hipStreamSynchronize(st);
+        delete[] of_step;
+        delete[] next;
+        if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return ZIPLM_ERR_DEVICE;
+        P.snap_of_step = l.snap_of_step;
+        P.snap_next = l.snap_next;
+    } else {
+        P.snap_of_step = nullptr;
+        P.snap_next = nullptr;
+    }
+    // bar, status, sel are adjacent 256-byte slots
+    ZIPLM_HIP_TRY(hipMemsetAsync(P.bar, 0, 3 * kAlign, st));
+
+    // the device counts removals against the structures that are alive; an impossible request
+    // (n_remove above the live count) shows up as "no candidate" -> status = 1 + step
+    if (group_size == 1) {
+        int per_cu = 0;
+        ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_columns_kernel, PT, 0));
+        if (per_cu < 1) return ZIPLM_ERR_DEVICE;
+        const int nblocks = device_cu_count() * (per_cu < 2 ? per_cu : 2);
+        void *args[] = {&P};
+        ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<void *>(prune_columns_kernel), dim3(nblocks),
+                                                 dim3(PT), args, 0, st));
+    } else {
+        const int fill = 1024;
+        hipLaunchKernelGGL(group_init_kernel, dim3(fill), dim3(256), 0, st, P);
+        const int ncc = (d_col + 255) / 256;
+        const int tiles = ((d_col + G_ROWS - 1) / G_ROWS + (d_row + G_ROWS - 1) / G_ROWS) * ncc;
+        const int prep_blocks = ((d_col + d_row) * group_size + 255) / 256;
+        for (int t = 0; t < n_remove; ++t) {
+            if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill), dim3(256), 0, st, P, t);
+            hipLaunchKernelGGL(group_score_kernel, dim3(G), dim3(256), 0, st, P, t);
+            hipLaunchKernelGGL(group_select_kernel, dim3(1), dim3(256), 0, st, P, t);
+            hipLaunchKernelGGL(group_prepare_kernel, dim3(prep_blocks), dim3(256), 0, st, P);
+            hipLaunchKernelGGL(group_update_kernel, dim3(tiles), dim3(256), 0, st, P);
+        }
+        if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill), dim3(256), 0, st, P, n_remove);
+        hipLaunchKernelGGL(group_final_kernel, dim3(fill), dim3(256), 0, st, P);
+        ZIPLM_HIP_TRY(hipGetLastError());
+    }
+
+    if (info_host) {
+        int status = 0;
+        ZIPLM_HIP_TRY(hipStreamSynchronize(st));
+        ZIPLM_HIP_TRY(hipMemcpy(&status, P.status, sizeof(int), hipMemcpyDeviceToHost));
+        *info_host = status;
+        if (status > 0) return ZIPLM_ERR_NOT_PD;
+        if (status < 0) return ZIPLM_ERR_DEVICE;
+    }
+    return ZIPLM_OK;
+}

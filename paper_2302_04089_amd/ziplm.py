@@ -1,0 +1,164 @@
+"""Thin ctypes binding of libziplm.so (argument marshalling only).
+
+Same names as the C ABI in include/ziplm.h.  Tensors are torch CUDA tensors (PyTorch provides
+device memory and the stream, nothing else); every computation runs inside the library's HIP
+kernels.  There is no CPU fallback: if the library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libziplm.so")
+
+OK = 0
+ERR_INVALID_ARG = -1
+ERR_NOT_PD = -2
+ERR_WORKSPACE = -3
+ERR_DEVICE = -4
+ERR_UNSUPPORTED = -5
+X_FEATURE_MAJOR = 0
+X_TOKEN_MAJOR = 1
+
+EXPORTS = (
+    "ziplm_version", "ziplm_status_string",
+    "ziplm_hessian_accumulate", "ziplm_hessian_workspace_bytes",
+    "ziplm_hinv", "ziplm_hinv_workspace_bytes",
+    "ziplm_structured_obs_prune", "ziplm_prune_workspace_bytes",
+)
+
+_lib = None
+
+
+class ZiplmError(RuntimeError):
+    def __init__(self, status, info=None):
+        msg = lib().ziplm_status_string(int(status)).decode()
+        super().__init__("libziplm: %s (status %d, info %s)" % (msg, status, info))
+        self.status = int(status)
+        self.info = info
+
+
+def lib():
+    """Loads libziplm.so (built in-tree by paper_2302_04089_amd/build.py).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libziplm.so is not built: run `python paper_2302_04089_amd/build.py`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32, i64, f32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_int64, ctypes.c_float
+    L.ziplm_version.restype = i32
+    L.ziplm_version.argtypes = []
+    L.ziplm_status_string.restype = ctypes.c_char_p
+    L.ziplm_status_string.argtypes = [i32]
+    L.ziplm_hessian_accumulate.restype = i32
+    L.ziplm_hessian_accumulate.argtypes = [vp, vp, i32, i64, i64, i32, f32, vp, sz, vp]
+    L.ziplm_hessian_workspace_bytes.restype = sz
+    L.ziplm_hessian_workspace_bytes.argtypes = [i32, i64]
+    L.ziplm_hinv.restype = i32
+    L.ziplm_hinv.argtypes = [vp, vp, i32, f32, ctypes.POINTER(f32), ctypes.POINTER(i32), vp, sz, vp]
+    L.ziplm_hinv_workspace_bytes.restype = sz
+    L.ziplm_hinv_workspace_bytes.argtypes = [i32]
+    L.ziplm_structured_obs_prune.restype = i32
+    L.ziplm_structured_obs_prune.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32,
+                                             ctypes.POINTER(ctypes.c_int32), vp, ctypes.POINTER(i32),
+                                             vp, sz, vp]
+    L.ziplm_prune_workspace_bytes.restype = sz
+    L.ziplm_prune_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    _lib = L
+    return L
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous CUDA tensor of dtype %s" % (name, dtype))
+
+
+def _workspace(nbytes, device):
+    # torch's caching allocator returns 512-byte aligned blocks
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def ziplm_hessian_workspace_bytes(d_col, n_tok):
+    return int(lib().ziplm_hessian_workspace_bytes(int(d_col), int(n_tok)))
+
+
+def ziplm_hinv_workspace_bytes(d_col):
+    return int(lib().ziplm_hinv_workspace_bytes(int(d_col)))
+
+
+def ziplm_prune_workspace_bytes(d_row, d_col, group_size, n_snap=0):
+    return int(lib().ziplm_prune_workspace_bytes(int(d_row), int(d_col), int(group_size), int(n_snap)))
+
+
+def ziplm_hessian_accumulate(H, X, scale=2.0, layout=X_FEATURE_MAJOR, workspace=None, stream=None):
+    """H += scale * X X^T.  X: (d_col, n_tok) feature-major or (n_tok, d_col) token-major."""
+    _check(H, torch.float32, "H")
+    _check(X, torch.float32, "X")
+    d = H.shape[0]
+    if layout == X_FEATURE_MAJOR:
+        n_tok, ldx = X.shape[1], X.stride(0)
+        assert X.shape[0] == d
+    else:
+        n_tok, ldx = X.shape[0], X.stride(0)
+        assert X.shape[1] == d
+    need = ziplm_hessian_workspace_bytes(d, n_tok)
+    ws = workspace if workspace is not None else _workspace(need, H.device)
+    rc = lib().ziplm_hessian_accumulate(H.data_ptr(), X.data_ptr(), d, n_tok, ldx, int(layout), float(scale),
+                                        ws.data_ptr(), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return H
+
+
+def ziplm_hinv(H, damp_rel=0.01, out=None, workspace=None, stream=None, check=True):
+    """Returns (Hinv, lambda).  With check=False nothing is copied back and lambda is None."""
+    _check(H, torch.float32, "H")
+    d = H.shape[0]
+    out = torch.empty_like(H) if out is None else out
+    _check(out, torch.float32, "out")
+    need = ziplm_hinv_workspace_bytes(d)
+    ws = workspace if workspace is not None else _workspace(need, H.device)
+    lam = ctypes.c_float(0.0)
+    info = ctypes.c_int(0)
+    rc = lib().ziplm_hinv(H.data_ptr(), out.data_ptr(), d, float(damp_rel),
+                          ctypes.byref(lam) if check else None, ctypes.byref(info) if check else None,
+                          ws.data_ptr(), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc, info.value)
+    return out, (lam.value if check else None)
+
+
+def ziplm_structured_obs_prune(W, Hinv, group_size, n_remove, alive=None, snapshot_steps=None,
+                               workspace=None, stream=None, check=True):
+    """Algorithm 1 in place on W and Hinv.  Returns (order int32[n_remove], err float64[n_remove],
+    W_snap or None), all on the device."""
+    _check(W, torch.float32, "W")
+    _check(Hinv, torch.float32, "Hinv")
+    m, d = W.shape
+    dev = W.device
+    order = torch.empty(max(n_remove, 1), dtype=torch.int32, device=dev)
+    err = torch.empty(max(n_remove, 1), dtype=torch.float64, device=dev)
+    steps = [] if snapshot_steps is None else [int(s) for s in snapshot_steps]
+    n_snap = len(steps)
+    W_snap = torch.empty((n_snap, m, d), dtype=torch.float32, device=dev) if n_snap else None
+    steps_c = (ctypes.c_int32 * n_snap)(*steps) if n_snap else None
+    if alive is not None:
+        _check(alive, torch.uint8, "alive")
+    need = ziplm_prune_workspace_bytes(m, d, group_size, n_snap)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    info = ctypes.c_int(0)
+    rc = lib().ziplm_structured_obs_prune(
+        W.data_ptr(), Hinv.data_ptr(), m, d, int(group_size), int(n_remove), order.data_ptr(), err.data_ptr(),
+        alive.data_ptr() if alive is not None else None, n_snap, steps_c,
+        W_snap.data_ptr() if n_snap else None, ctypes.byref(info) if check else None,
+        ws.data_ptr(), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc, info.value)
+    return order[:n_remove], err[:n_remove], W_snap

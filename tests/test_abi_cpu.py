@@ -1,0 +1,80 @@
+"""CPU-only checks of the C ABI: the shared library loads, exports every function that
+include/ziplm.h declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    from paper_2302_04089_amd import ziplm
+    return ziplm.lib()
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ziplm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ziplm_[a-z_]+)\s*\(", text)))
+
+
+def test_header_functions_are_exported(L):
+    from paper_2302_04089_amd import ziplm
+    names = _declared_functions()
+    assert len(names) == 8
+    assert sorted(ziplm.EXPORTS) == names
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_version_and_status_strings(L):
+    assert L.ziplm_version() >= 100
+    seen = set()
+    for code in (0, -1, -2, -3, -4, -5):
+        s = L.ziplm_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert L.ziplm_status_string(12345) == b"unknown status"
+
+
+def test_workspace_sizes_are_aligned_and_monotone(L):
+    assert L.ziplm_hinv_workspace_bytes(0) == 0
+    a, b = L.ziplm_hinv_workspace_bytes(768), L.ziplm_hinv_workspace_bytes(3072)
+    assert 0 < a < b and a % 256 == 0 and b % 256 == 0
+    # three padded fp32 squares
+    assert b >= 3 * 3072 * 3072 * 4
+    p1 = L.ziplm_prune_workspace_bytes(768, 3072, 1, 0)
+    assert p1 >= 3072 * 3072 * 8 and p1 % 256 == 0
+    assert L.ziplm_prune_workspace_bytes(768, 768, 64, 0) >= 768 * 768 * 8
+    assert L.ziplm_prune_workspace_bytes(768, 770, 64, 0) == 0      # not divisible
+    assert L.ziplm_hessian_workspace_bytes(3072, 0) == 0
+    assert L.ziplm_hessian_workspace_bytes(3072, 16384) % 256 == 0
+
+
+def test_argument_errors_return_before_any_device_work(L):
+    one = ctypes.c_void_p(256)       # never dereferenced: validation fails first
+    assert L.ziplm_hessian_accumulate(None, one, 4, 4, 4, 0, 2.0, None, 0, None) == -1
+    assert L.ziplm_hessian_accumulate(one, None, 4, 4, 4, 0, 2.0, None, 0, None) == -1
+    assert L.ziplm_hessian_accumulate(one, one, 4, 8, 4, 0, 2.0, None, 0, None) == -1      # ldx < n_tok
+    assert L.ziplm_hessian_accumulate(one, one, 4, 8, 8, 7, 2.0, None, 0, None) == -1      # layout
+    assert L.ziplm_hessian_accumulate(one, one, 0, 8, 8, 0, 2.0, None, 0, None) == -1
+    assert L.ziplm_hessian_accumulate(one, None, 4, 0, 0, 0, 2.0, None, 0, None) == 0      # empty batch
+    assert L.ziplm_hinv(None, one, 4, 0.01, None, None, one, 1 << 30, None) == -1
+    assert L.ziplm_hinv(one, one, 4, -1.0, None, None, one, 1 << 30, None) == -1
+    assert L.ziplm_hinv(one, one, 4, 0.01, None, None, None, 0, None) == -3
+    assert L.ziplm_hinv(one, one, 4, 0.01, None, None, ctypes.c_void_p(8), 1 << 30, None) == -3   # misaligned
+    assert L.ziplm_hinv(one, one, 4, 0.01, None, None, one, 16, None) == -3                        # too small
+    pr = L.ziplm_structured_obs_prune
+    big = 1 << 40
+    assert pr(None, one, 2, 8, 1, 1, one, one, None, 0, None, None, None, one, big, None) == -1
+    assert pr(one, one, 2, 8, 3, 1, one, one, None, 0, None, None, None, one, big, None) == -1     # 8 % 3
+    assert pr(one, one, 2, 8, 1, 9, one, one, None, 0, None, None, None, one, big, None) == -1     # n_remove > G
+    assert pr(one, one, 2, 8, 1, 1, None, one, None, 0, None, None, None, one, big, None) == -1    # no order_out
+    assert pr(one, one, 2, 8, 1, 1, one, one, None, 1, None, None, None, one, big, None) == -1     # snapshots w/o arrays
+    steps = (ctypes.c_int32 * 1)(5)
+    assert pr(one, one, 2, 8, 1, 1, one, one, None, 1, steps, one, None, one, big, None) == -1     # step > n_remove
+    assert pr(one, one, 2, 256, 128, 1, one, one, None, 0, None, None, None, one, big, None) == -5 # group too large
+    assert pr(one, one, 2, 8, 1, 1, one, one, None, 0, None, None, None, None, 0, None) == -3

@@ -1,0 +1,257 @@
+"""GPU parity: every C-ABI entry point against the fp64 CPU oracle on the same seeded inputs.
+
+Tolerances (spec bar, fp32 device arithmetic vs fp64 oracle):
+  * removal order: identical wherever the oracle's relative score gap exceeds 1e-6
+    (tests/parity_protocol.py spells out the resync rule);
+  * per-step errors, W snapshots and the final inverse Hessian: 1e-4 relative;
+  * Hessian entries: 1e-5 of sqrt(H_ii H_jj) (fp32 products accumulated in fp32 over n_tok
+    terms: rounding grows like sqrt(n_tok) * 2^-24, about 8e-6 at 16384 tokens);
+  * inverse: 1e-4 relative Frobenius and on the diagonal (observed ~1e-6 at cond ~ 1e3).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2302_04089_amd import workloads
+
+from parity_protocol import REL_TOL, compare_run, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def z():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2302_04089_amd import ziplm
+    ziplm.lib()           # raises if the HIP library is not built: there is no fallback
+    return ziplm
+
+
+def dev(a, dtype=torch.float32):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dtype).cuda()
+
+
+# ------------------------------------------------------------------------------------------ Hessian
+
+def _check_hessian(H_gpu, H_ref, tol=1e-5):
+    dg = np.sqrt(np.diag(H_ref))
+    err = np.abs(H_gpu.astype(np.float64) - H_ref) / np.outer(dg, dg)
+    assert err.max() <= tol, "Hessian entry off by %.3e of sqrt(HiiHjj)" % err.max()
+    assert np.array_equal(H_gpu, H_gpu.T), "Hessian not exactly symmetric"
+
+
+@pytest.mark.parametrize("d,n,kind", [
+    (256, 1024, "normal"),        # whole tiles, one split
+    (200, 1000, "gelu"),          # ragged rows, ragged tokens
+    (130, 77, "scaled_normal"),   # n_tok not a multiple of 4: scalar tail loads
+    (384, 6144, "gelu"),          # several token splits
+    (1, 5, "normal"),
+])
+def test_hessian_feature_major(z, oracle, d, n, kind):
+    spec = workloads.small(4, d, 1, n, x_kind=kind, seed=d + n)
+    X = workloads.make_X(spec)
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, dev(X), scale=2.0)
+    torch.cuda.synchronize()
+    _check_hessian(H.cpu().numpy(), oracle.hessian(X, 2.0))
+
+
+def test_hessian_unaligned_leading_dimension(z, oracle):
+    spec = workloads.small(4, 70, 1, 333, x_kind="gelu", seed=5)
+    X = workloads.make_X(spec)
+    buf = torch.zeros((70, 335), dtype=torch.float32, device="cuda")
+    buf[:, :333] = dev(X)
+    H = torch.zeros((70, 70), dtype=torch.float32, device="cuda")
+    rc = z.lib().ziplm_hessian_accumulate(H.data_ptr(), buf.data_ptr(), 70, 333, 335, 0, 2.0, None, 0, None)
+    assert rc == 0
+    torch.cuda.synchronize()
+    _check_hessian(H.cpu().numpy(), oracle.hessian(X, 2.0))
+
+
+def test_hessian_token_major_and_batches(z, oracle):
+    spec = workloads.small(4, 192, 1, 2048, x_kind="gelu", seed=9)
+    X = workloads.make_X(spec)
+    H = torch.zeros((192, 192), dtype=torch.float32, device="cuda")
+    # three batches, token-major as an activation hook would deliver them
+    for lo, hi in ((0, 700), (700, 701), (701, 2048)):
+        z.ziplm_hessian_accumulate(H, dev(X[:, lo:hi].T.copy()), scale=2.0, layout=z.X_TOKEN_MAJOR)
+    torch.cuda.synchronize()
+    _check_hessian(H.cpu().numpy(), oracle.hessian(X, 2.0))
+    # empty batch is a no-op
+    before = H.clone()
+    assert z.lib().ziplm_hessian_accumulate(H.data_ptr(), None, 192, 0, 0, 0, 2.0, None, 0, None) == 0
+    assert torch.equal(H, before)
+
+
+def test_hessian_is_deterministic(z):
+    spec = workloads.small(4, 384, 1, 6144, x_kind="gelu", seed=3)
+    X = dev(workloads.make_X(spec))
+    outs = []
+    for _ in range(2):
+        H = torch.zeros((384, 384), dtype=torch.float32, device="cuda")
+        z.ziplm_hessian_accumulate(H, X)
+        outs.append(H.cpu())
+    assert torch.equal(outs[0], outs[1])
+
+
+# ------------------------------------------------------------------------------------------ inverse
+
+@pytest.mark.parametrize("d,n,kind", [(64, 256, "gelu"), (200, 1000, "gelu"), (384, 2048, "scaled_normal"),
+                                      (640, 4096, "gelu"), (1, 8, "normal"), (129, 600, "normal")])
+def test_hinv_matches_oracle(z, oracle, d, n, kind):
+    spec = workloads.small(4, d, 1, n, x_kind=kind, seed=d)
+    H32 = oracle.hessian(workloads.make_X(spec), 2.0).astype(np.float32)
+    ref, lam_ref = oracle.hinv(H32, 0.01)
+    out, lam = z.ziplm_hinv(dev(H32), 0.01)
+    got = out.cpu().numpy()
+    assert lam == pytest.approx(lam_ref, rel=1e-6)
+    assert rel_fro(got, ref) <= REL_TOL
+    assert np.abs(np.diag(got) / np.diag(ref) - 1).max() <= REL_TOL
+    assert np.array_equal(got, got.T)
+    # in place
+    Hd = dev(H32)
+    out2, _ = z.ziplm_hinv(Hd, 0.01, out=Hd)
+    assert torch.equal(out2, out)
+
+
+def test_hinv_reports_non_positive_definite(z):
+    A = np.eye(200, dtype=np.float32)
+    A[137, 137] = -1.0
+    with pytest.raises(z.ZiplmError) as e:
+        z.ziplm_hinv(dev(A), 0.0)
+    assert e.value.status == z.ERR_NOT_PD and e.value.info == 138
+
+
+# ------------------------------------------------------------------------------------------ pruning
+
+def _oracle_inputs(oracle, spec):
+    X = workloads.make_X(spec)
+    W32 = workloads.make_W(spec)
+    H = oracle.hessian(X, 2.0)
+    Hi, lam = oracle.hinv(H, spec.damp_rel)
+    return X, W32, H, Hi.astype(np.float32)
+
+
+def _run_prune_case(z, oracle, spec, n_remove, snaps):
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    Wd, Hd = dev(W32), dev(Hi32)
+    order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hd, spec.group_size, n_remove, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    ref = compare_run(oracle, W32, Hi32, spec.group_size, n_remove, order.cpu().numpy(), err.cpu().numpy(),
+                      snap_steps=snaps)
+    g = spec.group_size
+    gone = np.zeros(spec.d_col, bool)
+    for s in ref["order"]:
+        gone[s * g:(s + 1) * g] = True
+    Wg = Wd.cpu().numpy()
+    Hg = Hd.cpu().numpy()
+    assert np.all(Wg[:, gone] == 0.0)
+    assert np.all(Hg[gone, :] == 0.0) and np.all(Hg[:, gone] == 0.0)
+    if (~gone).any():
+        assert rel_fro(Wg, ref["W"]) <= REL_TOL
+        assert rel_fro(Hg, ref["Hinv"]) <= REL_TOL
+    for q, k in enumerate(snaps or []):
+        sg = W_snap[q].cpu().numpy()
+        so = ref["W_snap"][q]
+        if np.any(so != 0):
+            assert rel_fro(sg, so) <= REL_TOL, "snapshot after %d removals" % k
+        assert np.all(sg[:, so[0] == 0] == 0.0) or np.all(so == 0)
+    return ref
+
+
+@pytest.mark.parametrize("m,d,n,kind,seed", [
+    (48, 160, 640, "gelu", 1),          # ragged: not a multiple of any tile size
+    (256, 1024, 2048, "normal", 2),     # config-1 shape
+    (33, 700, 3000, "gelu", 3),         # two column chunks, ragged rows
+    (1, 40, 200, "normal", 4),          # single output row: classic OBS
+])
+def test_prune_single_columns_remove_all(z, oracle, m, d, n, kind, seed):
+    spec = workloads.small(m, d, 1, n, x_kind=kind, seed=seed)
+    snaps = sorted({0, d // 4, d // 2, (9 * d) // 10, max(d - 8, 0), d})
+    _run_prune_case(z, oracle, spec, d, snaps)
+
+
+def test_prune_single_columns_partial(z, oracle):
+    spec = workloads.small(64, 512, 1, 2048, x_kind="gelu", seed=7)
+    _run_prune_case(z, oracle, spec, 200, [200])
+
+
+@pytest.mark.parametrize("m,d,g,n,kind,seed", [
+    (96, 256, 64, 1024, "scaled_normal", 1),    # 4 heads
+    (40, 96, 8, 400, "gelu", 2),
+    (17, 60, 2, 300, "normal", 3),
+    (24, 64, 4, 256, "gelu", 4),
+    (8, 64, 64, 256, "normal", 5),              # one structure = the whole layer
+])
+def test_prune_groups_remove_all(z, oracle, m, d, g, n, kind, seed):
+    spec = workloads.small(m, d, g, n, x_kind=kind, seed=seed)
+    G = d // g
+    snaps = sorted({0, G // 2, G - 1, G})
+    _run_prune_case(z, oracle, spec, G, snaps)
+
+
+def test_prune_resume_with_alive_mask(z, oracle):
+    spec = workloads.small(32, 256, 1, 1024, x_kind="gelu", seed=11)
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    Wd, Hd = dev(W32), dev(Hi32)
+    o1, e1, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, 100)
+    alive = torch.ones(256, dtype=torch.uint8, device="cuda")
+    alive[o1.long()] = 0
+    o2, e2, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, 100, alive=alive)
+    order = torch.cat([o1, o2]).cpu().numpy()
+    err = torch.cat([e1, e2]).cpu().numpy()
+    ref = compare_run(oracle, W32, Hi32, 1, 200, order, err)
+    assert rel_fro(Wd.cpu().numpy(), ref["W"]) <= REL_TOL
+
+
+def test_prune_zero_removals_is_identity(z):
+    W = torch.randn(8, 32, device="cuda")
+    Hi = torch.eye(32, device="cuda")
+    W0, H0 = W.clone(), Hi.clone()
+    order, err, _ = z.ziplm_structured_obs_prune(W, Hi, 1, 0)
+    torch.cuda.synchronize()
+    assert order.numel() == 0 and torch.equal(W, W0) and torch.equal(Hi, H0)
+
+
+def test_prune_reports_non_positive_definite_block(z):
+    W = torch.ones(4, 16, device="cuda")
+    Hi = -torch.eye(16, device="cuda")
+    for g in (1, 4):
+        with pytest.raises(z.ZiplmError) as e:
+            z.ziplm_structured_obs_prune(W.clone(), Hi.clone(), g, 2)
+        assert e.value.status == z.ERR_NOT_PD and e.value.info == 1
+
+
+def test_prune_is_deterministic(z, oracle):
+    spec = workloads.small(48, 320, 1, 1280, x_kind="gelu", seed=13)
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    outs = []
+    for _ in range(2):
+        Wd, Hd = dev(W32), dev(Hi32)
+        o, e, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, 300)
+        outs.append((o.cpu(), e.cpu(), Wd.cpu(), Hd.cpu()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+# ------------------------------------------------------------------------------------------ end to end
+
+@pytest.mark.parametrize("m,d,g,n,kind", [(64, 384, 1, 2048, "gelu"), (96, 256, 64, 2048, "scaled_normal")])
+def test_end_to_end_pipeline(z, oracle, m, d, g, n, kind):
+    """X -> H -> Hinv -> prune entirely on the device, against the oracle's own fp64 chain."""
+    spec = workloads.small(m, d, g, n, x_kind=kind, seed=21)
+    X = workloads.make_X(spec)
+    W32 = workloads.make_W(spec)
+    G = d // g
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, dev(X), 2.0)
+    Hi, lam = z.ziplm_hinv(H, spec.damp_rel)
+    Wd = dev(W32)
+    snaps = [G // 2]
+    order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hi, g, G, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    Hi_or, lam_or = oracle.hinv(oracle.hessian(X, 2.0), spec.damp_rel)
+    assert lam == pytest.approx(lam_or, rel=1e-5)
+    ref = compare_run(oracle, W32, Hi_or, g, G, order.cpu().numpy(), err.cpu().numpy(), snap_steps=snaps)
+    assert rel_fro(W_snap[0].cpu().numpy(), ref["W_snap"][0]) <= REL_TOL
