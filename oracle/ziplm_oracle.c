@@ -31,9 +31,23 @@
 #include <string.h>
 #include <stdint.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 #define ORACLE_OK 0
 #define ORACLE_ERR_INVALID_ARG (-1)
 #define ORACLE_ERR_NOT_PD (-2)
+
+/* Number of threads the OpenMP loops below will use (for reporting timings). */
+int ziplm_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------------ */
 /* H <- H + scale * X X^T                                                    */

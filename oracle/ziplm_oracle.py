@@ -45,8 +45,15 @@ def _load():
     lib.ziplm_oracle_prune.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                        ctypes.c_int, bp, ip, ip, dp, dp, dp,
                                        ctypes.c_int, ip, dp]
+    lib.ziplm_oracle_threads.restype = ctypes.c_int
+    lib.ziplm_oracle_threads.argtypes = []
     _lib = lib
     return lib
+
+
+def threads():
+    """OpenMP threads the oracle's loops use."""
+    return int(_load().ziplm_oracle_threads())
 
 
 class OracleError(RuntimeError):

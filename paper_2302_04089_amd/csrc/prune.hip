@@ -18,11 +18,26 @@
 // with the selected index handed from kernel to kernel in device memory.
 #include <hip/hip_cooperative_groups.h>
 
+#include <stdlib.h>
+
 #include "common.h"
 
 namespace ziplm {
 
 int device_cu_count();
+bool lazy_columns_feasible(int d_row, int d_col);
+size_t lazy_columns_workspace_bytes(int d_row, int d_col, int n_snap);
+int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remove, int32_t *order_out,
+                        double *err_out, const uint8_t *alive_in, int n_snap, const int32_t *snap_steps_host,
+                        float *W_snap, void *workspace, hipStream_t st, int **status_dev_out);
+
+// The eager single-column kernel is kept as the fallback for shapes the deferred-update kernel
+// cannot hold in LDS, and can be forced with ZIPLM_PRUNE_EAGER=1 for cross-checking.
+static bool use_lazy_columns(int d_row, int d_col) {
+    const char *e = getenv("ZIPLM_PRUNE_EAGER");
+    if (e && e[0] == '1') return false;
+    return lazy_columns_feasible(d_row, d_col);
+}
 
 constexpr int PT = 512;        // threads per workgroup of the persistent kernel (= columns per tile)
 constexpr int H_ROWS = 8;      // rows of Hd per tile
@@ -514,6 +529,8 @@ static PruneLayout prune_layout(int d_row, int d_col, int g, int n_snap, void *w
 
 extern "C" size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap) {
     if (d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size) return 0;
+    if (group_size == 1 && ziplm::use_lazy_columns(d_row, d_col))
+        return ziplm::lazy_columns_workspace_bytes(d_row, d_col, n_snap);
     return ziplm::prune_layout(d_row, d_col, group_size, n_snap, nullptr).bytes;
 }
 
@@ -534,6 +551,22 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
     const size_t need = ziplm_prune_workspace_bytes(d_row, d_col, group_size, n_snap);
     if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (group_size == 1 && use_lazy_columns(d_row, d_col)) {
+        int *status_dev = nullptr;
+        const int rc = lazy_columns_launch(W, Hinv, d_row, d_col, n_remove, order_out, err_out, alive_in, n_snap,
+                                           snapshot_steps_host, W_snap, workspace, st, &status_dev);
+        if (rc != ZIPLM_OK) return rc;
+        if (info_host) {
+            int status = 0;
+            ZIPLM_HIP_TRY(hipStreamSynchronize(st));
+            ZIPLM_HIP_TRY(hipMemcpy(&status, status_dev, sizeof(int), hipMemcpyDeviceToHost));
+            *info_host = status;
+            if (status > 0) return ZIPLM_ERR_NOT_PD;
+            if (status < 0) return ZIPLM_ERR_DEVICE;
+        }
+        return ZIPLM_OK;
+    }
 
     PruneLayout l = prune_layout(d_row, d_col, group_size, n_snap, workspace);
     PruneState &P = l.st;
@@ -571,7 +604,7 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
         int per_cu = 0;
         ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_columns_kernel, PT, 0));
         if (per_cu < 1) return ZIPLM_ERR_DEVICE;
-        const int nblocks = device_cu_count() * (per_cu < 2 ? per_cu : 2);
+        const int nblocks = device_cu_count();   // one workgroup per compute unit keeps the barrier short
         void *args[] = {&P};
         ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<void *>(prune_columns_kernel), dim3(nblocks),
                                                  dim3(PT), args, 0, st));
