@@ -9,19 +9,23 @@
 //     only needs (a) the current diagonal, which each owner keeps up to date from u alone, and (b) the
 //     current row of the next pivot, which is  stale_row - sum_k u_k[p'] u_k / piv_k  over the
 //     downdates not yet applied.  So the downdates of up to 64 consecutive steps are kept as a list
-//     of pivot rows and applied to the stored matrix in one pass ("flush").  The stored fp64 matrix
-//     is then read and written once per 64 steps instead of once per step.
+//     of pivot rows and applied to the stored matrix in one pass ("flush"), a 16 x 64 x d
+//     contraction per workgroup on the fp64 matrix cores.  The stored fp64 matrix is then read and
+//     written once per 64 steps instead of once per step.
 //   * W is compensated at every step (Eq. 3 needs no deferral: the scores need the current W).
 //
 // Work is divided by columns: workgroup b owns `cpb` consecutive columns j, i.e. column j of W (kept
 // transposed as a row of `wt`, in LDS when it fits), row j of the fp64 inverse Hessian, its diagonal
-// entry, squared norm and score.  One wavefront works on one owned column at a time.  Per step:
+// entry, squared norm and score.  The owned rows of the inverse Hessian are stored as a panel
+// P[c][r] (column index outer, owned row inner, padded to 16 rows), so that "column p of my rows"
+// -- by symmetry my slice of row p -- is one contiguous 128-byte read.  One wavefront works on one
+// owned column at a time.  Per step:
 //
 //   1. every workgroup publishes its best owned column (score, index) and, speculatively, what the
 //      others would need if it wins: that column of W, the entries u_k[p] of the pending pivot rows
-//      and the current diagonal entry.  All of it is written as 64-bit words carrying 32 bits of
-//      data and a 32-bit step tag, so readers can tell a fresh word from an old one without any
-//      ordering between stores ("flag in data"); buffers alternate with the step parity.
+//      and the current diagonal entry.  All of it is written as 64-bit words that carry their step
+//      tag next to the data, so readers can tell a fresh word from an old one without any ordering
+//      between stores ("flag in data"); buffers alternate with the step parity.
 //   2. every workgroup reads all candidates, takes the argmin (lowest index on ties), reads the
 //      winner's payload, forms its slice of the current pivot row, updates its diagonal entries,
 //      compensates its columns of W and refreshes their norms and scores.
@@ -29,6 +33,8 @@
 // One exchange per step is the only device-wide synchronisation; every 64 steps one barrier
 // precedes the flush.  All waits are bounded: on a time-out the waiter raises status = -1 and
 // leaves; the others then time out or see the flag, and the grid drains.
+#include <stdio.h>
+
 #include "common.h"
 
 namespace ziplm {
@@ -37,14 +43,18 @@ int device_cu_count();
 
 namespace lazy {
 
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
 constexpr int LT = 1024;                 // threads per workgroup (16 wavefronts)
 constexpr int NW = LT / 64;
 constexpr int BMAX = 64;                 // pending pivot rows between flushes (one lane per row)
-constexpr int ROWS_PER_PASS = 16;        // owned rows updated per sweep over the pending rows in a flush
+constexpr int RG = 16;                   // owned rows per matrix-core pass (panel rows are padded to this)
+constexpr int NTI = 2;                  // column tiles a wavefront interleaves in a flush
 constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int IDX_NONE = -1;             // workgroup has no live column
-constexpr int IDX_ERROR = 0x7ffffff0;    // workgroup met a non-positive diagonal entry
-constexpr int SLOT_WORDS = 4;
+constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
+constexpr unsigned ENC_NONE = 0xFFFFu, ENC_ERROR = 0xFFFEu;
+constexpr int MAX_D = 65000;             // column index travels in 16 bits
 
 struct State {
     // caller's buffers
@@ -59,31 +69,33 @@ struct State {
     const int *snap_steps;   // device copy of the caller's list
     float *W_snap;
     // workspace
-    double *Hd;                   // [d][d]   stored (stale between flushes) inverse Hessian
-    float *Wt;                    // [d][m]   transposed W when it does not fit LDS, else unused
-    double *U;                    // [2][BMAX][d] pending pivot rows of the current / previous block
-    unsigned long long *slots;    // [2][nb][SLOT_WORDS]
+    double *P;                    // [nb][d][cp]  panels of the stored (stale between flushes) inverse Hessian
+    float *Wt;                    // [d][m]       transposed W when it does not fit LDS, else unused
+    double *U;                    // [2][BMAX][d] pending pivot rows of the current / previous block of steps
+    unsigned long long *slots;    // [2][nb][2]
     unsigned long long *pay;      // [2][nb][pay_words]
     unsigned long long *bar;      // [nb] flush-barrier epochs
     int *status;
     int cpb;                      // columns per workgroup
-    int w_in_lds;
+    int cp;                       // cpb rounded up to a multiple of RG
     int pay_words;                // m + 2*BMAX + 2
+#ifdef ZIPLM_LAZY_TIMING
+    unsigned long long *timing;   // [8] accumulated 100 MHz ticks per phase (workgroup 0), then [nb] local ticks
+#endif
 };
 
-__device__ __forceinline__ unsigned long long ll_pack(unsigned data, unsigned tag) {
-    return ((unsigned long long)data << 32) | tag;
-}
+// ------------------------------------------------------------------------------------------------
+// tagged words
+// ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ void ll_store(unsigned long long *p, unsigned data, unsigned tag) {
-    __hip_atomic_store(p, ll_pack(data, tag), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p, ((unsigned long long)data << 32) | tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Spins until the word carries `tag`; returns false on time-out or when another waiter gave up.
-__device__ __forceinline__ bool ll_wait(const unsigned long long *p, unsigned tag, unsigned &data, int *status) {
+
+struct Waiter {
     unsigned spins = 0;
     unsigned long long t0 = 0;
-    for (;;) {
-        const unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((unsigned)(v & 0xffffffffu) == tag) { data = (unsigned)(v >> 32); return true; }
+    // call after an unsuccessful poll; returns false when the wait must be abandoned
+    __device__ __forceinline__ bool again(int *status) {
         if ((++spins & 255u) == 0u) {
             if (t0 == 0) t0 = wall_clock64();
             if (__hip_atomic_load(status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == -1) return false;
@@ -92,19 +104,53 @@ __device__ __forceinline__ bool ll_wait(const unsigned long long *p, unsigned ta
                 return false;
             }
         }
+        return true;
+    }
+};
+
+// One word: 32 bits of data, 32-bit tag.
+__device__ __forceinline__ bool ll_wait(const unsigned long long *p, unsigned tag, unsigned &data, int *status) {
+    Waiter w;
+    for (;;) {
+        const unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((unsigned)(v & 0xffffffffu) == tag) { data = (unsigned)(v >> 32); return true; }
+        if (!w.again(status)) return false;
     }
 }
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    return v;
+// Two adjacent words, each 32 bits of data and a 32-bit tag: both loads are issued before either is tested.
+__device__ __forceinline__ bool ll_wait2(const unsigned long long *p, unsigned tag, unsigned &d0, unsigned &d1, int *status) {
+    Waiter w;
+    for (;;) {
+        const unsigned long long v0 = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long v1 = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((unsigned)(v0 & 0xffffffffu) == tag && (unsigned)(v1 & 0xffffffffu) == tag) {
+            d0 = (unsigned)(v0 >> 32);
+            d1 = (unsigned)(v1 >> 32);
+            return true;
+        }
+        if (!w.again(status)) return false;
+    }
 }
-
-__device__ __forceinline__ bool better(double s1, int i1, double s2, int i2) {
-    if (i2 < 0) return i1 >= 0;
-    if (i1 < 0) return false;
-    return (s1 < s2) || (s1 == s2 && i1 < i2);
+// Candidate slot: word0 = [score bits 63..32 | index:16 | tag:16], word1 = [score bits 31..0 | 0:16 | tag:16].
+__device__ __forceinline__ void slot_store(unsigned long long *p, double score, unsigned enc_idx, unsigned tag16) {
+    const unsigned long long b = (unsigned long long)__double_as_longlong(score);
+    __hip_atomic_store(p, ((b >> 32) << 32) | ((unsigned long long)enc_idx << 16) | tag16, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, ((b & 0xffffffffull) << 32) | tag16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool slot_wait(const unsigned long long *p, unsigned tag16, double &score, int &idx, int *status) {
+    Waiter w;
+    for (;;) {
+        const unsigned long long v0 = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long v1 = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((unsigned)(v0 & 0xffffu) == tag16 && (unsigned)(v1 & 0xffffu) == tag16) {
+            score = __longlong_as_double((long long)(((v0 >> 32) << 32) | (v1 >> 32)));
+            const unsigned e = (unsigned)((v0 >> 16) & 0xffffu);
+            idx = (e == ENC_NONE) ? IDX_NONE : (e == ENC_ERROR) ? IDX_ERROR : (int)e;
+            return true;
+        }
+        if (!w.again(status)) return false;
+    }
 }
 
 __device__ __forceinline__ unsigned dhi(double x) { return (unsigned)((unsigned long long)__double_as_longlong(x) >> 32); }
@@ -113,24 +159,82 @@ __device__ __forceinline__ double dmake(unsigned hi, unsigned lo) {
     return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
 }
 
-// LDS carve-up (byte offsets), identical on host and device.
+// ------------------------------------------------------------------------------------------------
+// wavefront reductions on the data-parallel-primitive lane permutes (no LDS traffic)
+// ------------------------------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) { return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_d(double v) { return dmake((unsigned)dpp_i<CTRL>((int)dhi(v)), (unsigned)dpp_i<CTRL>((int)dlo(v))); }
+__device__ __forceinline__ double readlane_d(double v, int lane) {
+    return dmake((unsigned)__builtin_amdgcn_readlane((int)dhi(v), lane), (unsigned)__builtin_amdgcn_readlane((int)dlo(v), lane));
+}
+constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
+
+// Sum over the 64 lanes, returned in every lane.
+__device__ __forceinline__ double wave_sum(double v) {
+    v += dpp_d<DPP_XOR1>(v);
+    v += dpp_d<DPP_XOR2>(v);
+    v += dpp_d<DPP_HALF_MIRROR>(v);
+    v += dpp_d<DPP_MIRROR>(v);          // every lane of a 16-lane row holds the row's sum
+    return (readlane_d(v, 0) + readlane_d(v, 16)) + (readlane_d(v, 32) + readlane_d(v, 48));
+}
+
+// strict order: smaller score first, lower index on equal scores; negative index = "none"
+__device__ __forceinline__ bool better(double s1, int i1, double s2, int i2) {
+    if (i2 < 0) return i1 >= 0;
+    if (i1 < 0) return false;
+    return (s1 < s2) || (s1 == s2 && i1 < i2);
+}
+template <int CTRL>
+__device__ __forceinline__ void argmin_step(double &s, int &i) {
+    const double so = dpp_d<CTRL>(s);
+    const int io = dpp_i<CTRL>(i);
+    if (better(so, io, s, i)) { s = so; i = io; }
+}
+// Argmin within each 16-lane row, result in every lane of the row.
+__device__ __forceinline__ void row_argmin(double &s, int &i) {
+    argmin_step<DPP_XOR1>(s, i);
+    argmin_step<DPP_XOR2>(s, i);
+    argmin_step<DPP_HALF_MIRROR>(s, i);
+    argmin_step<DPP_MIRROR>(s, i);
+}
+// Argmin over the 64 lanes, result in every lane.
+__device__ __forceinline__ void wave_argmin(double &s, int &i) {
+    row_argmin(s, i);
+    double bs = readlane_d(s, 0);
+    int bi = __builtin_amdgcn_readlane(i, 0);
+#pragma unroll
+    for (int r = 1; r < 4; ++r) {
+        const double so = readlane_d(s, 16 * r);
+        const int io = __builtin_amdgcn_readlane(i, 16 * r);
+        if (better(so, io, bs, bi)) { bs = so; bi = io; }
+    }
+    s = bs;
+    i = bi;
+}
+
+// ------------------------------------------------------------------------------------------------
+// LDS carve-up (byte offsets), identical on host and device
+// ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, coef, hist, pivs, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, red_i, misc, wt, total;
+    size_t uloc, cvec, pivs, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, red_i, misc, wt, total;
 };
-__host__ __device__ inline Lds lds_layout(int m, int d, int cpb, bool w_in_lds) {
+__host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
     Lds l;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 15) / 16 * 16; return r; };
-    l.uloc = take(sizeof(double) * BMAX * cpb);          // pending pivot rows, owned slice: [k][jl]
-    l.coef = take(sizeof(double) * BMAX * ROWS_PER_PASS);// flush coefficients of one pass: [k][row]
-    l.hist = take(sizeof(double) * BMAX);                // u_k[p] of the current pivot
+    l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [k][row]
+    l.cvec = take(sizeof(double) * BMAX);                // u_k[p] / piv_k for the current pivot
     l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
-    l.wcol = take(sizeof(float) * m);                    // column p of W
-    l.norm = take(sizeof(double) * cpb);
-    l.diag = take(sizeof(double) * cpb);
-    l.score = take(sizeof(double) * cpb);
-    l.hstale = take(sizeof(double) * cpb);
-    l.alive_own = take(sizeof(int) * cpb);
+    l.wcol = take(m * sizeof(float) > LT * sizeof(double) ? m * sizeof(float) : LT * sizeof(double));
+                                                         // column p of W (fp32) during a step; matrix-core A
+                                                         // fragments [k/4][lane] (fp64) during a flush
+    l.norm = take(sizeof(double) * cp);
+    l.diag = take(sizeof(double) * cp);
+    l.score = take(sizeof(double) * cp);
+    l.hstale = take(sizeof(double) * cp);
+    l.alive_own = take(sizeof(int) * cp);
     l.alive_bits = take(sizeof(unsigned) * ((d + 31) / 32));
     l.snap_bits = take(sizeof(unsigned) * ((d + 32) / 32 + 1));
     l.red_s = take(sizeof(double) * NW);
@@ -141,32 +245,117 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cpb, bool w_in_lds) 
     return l;
 }
 
+
+// Applies the k pending downdates to one workgroup's panel:
+//   P[c][g0 + r] -= sum_kk (uloc[kk][g0 + r] / piv_kk) * U[kk][c]   on v_mfma_f64_16x16x4_f64.
+// Lane l supplies A[row l%16][k l/16] and B[k l/16][col l%16]; its accumulator v holds
+// D[row 4v + l/16][col l%16].  Matrix row i = 4v + q is mapped to owned row g0 + 4q + v, so a lane ends
+// up with four consecutive rows of one column: 32 contiguous bytes of the panel.
+__device__ __forceinline__ void flush_panel(double *__restrict__ P, const double *__restrict__ Ub,
+                                                      const double *uloc, const double *pivs, double *coefa,
+                                                      const int *alive_own, const unsigned *alive_bits,
+                                                      int k, int d, int cp) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q4 = lane >> 4, cl16 = lane & 15;
+    const int nks = (k + 3) / 4;
+    for (int g0 = 0; g0 < cp; g0 += RG) {
+        {   // one A fragment entry per thread: k-group tid/64, lane tid%64
+            const int kk = 4 * wave + q4;
+            const int arow = g0 + 4 * (cl16 & 3) + (cl16 >> 2);
+            coefa[tid] = (kk < k && alive_own[arow]) ? uloc[kk * cp + arow] / pivs[kk] : 0.0;
+        }
+        __syncthreads();
+        // a wavefront works on NTI adjacent 16-column tiles at a time, so that 4 * NTI loads of
+        // pending-row entries are in flight before the matrix instructions that consume them
+        const int ntiles = (d + 15) / 16;
+        for (int ct0 = wave * NTI; ct0 < ntiles; ct0 += NW * NTI) {
+            int c[NTI];
+            bool col_ok[NTI];
+            bool any_ok = false;
+#pragma unroll
+            for (int x = 0; x < NTI; ++x) {
+                c[x] = (ct0 + x) * 16 + cl16;
+                col_ok[x] = (c[x] < d) && ((alive_bits[c[x] >> 5] >> (c[x] & 31)) & 1u);
+                any_ok = any_ok || col_ok[x];
+            }
+            if (!__any(any_ok)) continue;
+            doublex4 acc[NTI];
+#pragma unroll
+            for (int x = 0; x < NTI; ++x) acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
+            const double *ub = Ub + (size_t)q4 * d;
+            for (int h = 0; h < nks; h += 4) {
+                double bv[NTI][4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int kk = 4 * (h + e) + q4;
+#pragma unroll
+                    for (int x = 0; x < NTI; ++x)
+                        bv[x][e] = (kk < k && col_ok[x]) ? ub[(size_t)(h + e) * 4 * d + c[x]] : 0.0;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (h + e < nks) {
+                        const double a = coefa[(h + e) * 64 + lane];
+#pragma unroll
+                        for (int x = 0; x < NTI; ++x)
+                            acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bv[x][e], acc[x], 0, 0, 0);
+                    }
+                }
+            }
+#pragma unroll
+            for (int x = 0; x < NTI; ++x) {
+                if (col_ok[x]) {
+                    doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c[x] * cp + g0 + 4 * q4);
+                    doublex4 cur = *dst;
+                    cur -= acc[x];
+                    *dst = cur;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+#ifdef ZIPLM_LAZY_TIMING
+#define TICK(slot) do { if (b == 0 && tid == 0) { const unsigned long long now_ = wall_clock64(); tacc[slot] += now_ - tlast; tlast = now_; } } while (0)
+#else
+#define TICK(slot) do { } while (0)
+#endif
+
+template <bool W_IN_LDS>
 __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+#ifdef ZIPLM_LAZY_TIMING
+    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long tlast = wall_clock64();
+    unsigned long long tlocal = 0, texch = wall_clock64();
+#endif
     const int b = blockIdx.x, nb = gridDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int m = S.m, d = S.d, cpb = S.cpb;
-    const Lds L = lds_layout(m, d, cpb, S.w_in_lds != 0);
+    const int m = S.m, d = S.d, cpb = S.cpb, cp = S.cp;
+    const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb);
     double *uloc = reinterpret_cast<double *>(smem + L.uloc);
-    double *coef = reinterpret_cast<double *>(smem + L.coef);
-    double *hist = reinterpret_cast<double *>(smem + L.hist);
+    double *cvec = reinterpret_cast<double *>(smem + L.cvec);
     double *pivs = reinterpret_cast<double *>(smem + L.pivs);
     float *wcol = reinterpret_cast<float *>(smem + L.wcol);
+    double *coefa = reinterpret_cast<double *>(smem + L.wcol);
     double *norm = reinterpret_cast<double *>(smem + L.norm);
     double *diag = reinterpret_cast<double *>(smem + L.diag);
     double *score = reinterpret_cast<double *>(smem + L.score);
     double *hstale = reinterpret_cast<double *>(smem + L.hstale);
     int *alive_own = reinterpret_cast<int *>(smem + L.alive_own);
     unsigned *alive_bits = reinterpret_cast<unsigned *>(smem + L.alive_bits);
+    unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
     double *red_s = reinterpret_cast<double *>(smem + L.red_s);
     int *red_i = reinterpret_cast<int *>(smem + L.red_i);
-    unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
-    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [1] winner, [2] error seen, [3] local candidate
-    double *misc_d = reinterpret_cast<double *>(smem + L.misc + 32);  // [0] best score, [1] pivot
+    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen
+    double *misc_d = reinterpret_cast<double *>(smem + L.misc + 32);  // [1] pivot, [2] 1 / pivot
 
     const int j0 = b * cpb;
     const int nown = max(0, min(cpb, d - j0));
-    // generic pointer: LDS or this workgroup's private rows of the transposed copy in global memory
-    float *wt = S.w_in_lds ? reinterpret_cast<float *>(smem + L.wt) : (S.Wt + (size_t)j0 * m);
+    double *P = S.P + (size_t)b * d * cp;       // this workgroup's panel: P[c * cp + r] = Hinv[j0 + r][c]
+    float *wt_lds = reinterpret_cast<float *>(smem + L.wt);
+    float *wt_glb = S.Wt + (size_t)j0 * m;
+#define WT(jl, i) (*(W_IN_LDS ? &wt_lds[(size_t)(jl) * m + (i)] : &wt_glb[(size_t)(jl) * m + (i)]))
 
     // ------------------------------------------------------------------ set-up (own data only)
     for (int w = tid; w < (d + 31) / 32; w += LT) {
@@ -179,30 +368,29 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     }
     if (tid == 0) { misc[0] = 0; misc[2] = 0; }
     for (int w = tid; w < (d + 32) / 32 + 1; w += LT) snap_bits[w] = 0;
+    for (int r = tid; r < cp; r += LT) { alive_own[r] = 0; norm[r] = 0.0; diag[r] = 1.0; score[r] = 0.0; hstale[r] = 0.0; }
+    for (int e = tid; e < BMAX * cp; e += LT) uloc[e] = 0.0;
     __syncthreads();
     for (int q = tid; q < S.n_snap; q += LT) {
         const int sstep = S.snap_steps[q];
         atomicOr(&snap_bits[sstep >> 5], 1u << (sstep & 31));
     }
-    for (int jl = 0; jl < nown; ++jl) {
-        const size_t row = (size_t)(j0 + jl) * d;
-        for (int c = tid; c < d; c += LT) S.Hd[row + c] = (double)S.Hinv[row + c];
-    }
+    for (int c = tid; c < d; c += LT)
+        for (int r = 0; r < cp; ++r) P[(size_t)c * cp + r] = (r < nown) ? (double)S.Hinv[(size_t)(j0 + r) * d + c] : 0.0;
     for (int jl = wave; jl < nown; jl += NW) {
         const int j = j0 + jl;
         double s = 0.0;
         for (int i = lane; i < m; i += 64) {
             const float w = S.W[(size_t)i * d + j];
-            wt[(size_t)jl * m + i] = w;
+            WT(jl, i) = w;
             s += (double)w * (double)w;
         }
         s = wave_sum(s);
         if (lane == 0) {
             const double dj = (double)S.Hinv[(size_t)j * d + j];
-            const int alive = S.alive_in ? (S.alive_in[j] != 0) : 1;
             norm[jl] = s;
             diag[jl] = dj;
-            alive_own[jl] = alive;
+            alive_own[jl] = S.alive_in ? (S.alive_in[j] != 0) : 1;
             score[jl] = s / dj;
         }
     }
@@ -214,6 +402,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     int t = 0;
     bool ok = true;
     int error_step = 0;
+    double tau = 1.0e300;   // publish the payload ahead of the exchange only if my best score is <= tau
 
     for (; t <= S.n_remove; ++t) {
         // -------------------------------------------------------------- snapshots after t removals
@@ -222,16 +411,21 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             float *dst = S.W_snap + (size_t)q * m * d;
             for (int jl = wave; jl < nown; jl += NW) {
                 const bool a = alive_own[jl] != 0;
-                for (int i = lane; i < m; i += 64) dst[(size_t)i * d + j0 + jl] = a ? wt[(size_t)jl * m + i] : 0.f;
+                for (int i = lane; i < m; i += 64) dst[(size_t)i * d + j0 + jl] = a ? WT(jl, i) : 0.f;
             }
         }
         if (t == S.n_remove) break;
 
         const unsigned tag = (unsigned)(t + 1);
+        const unsigned tag16 = tag & 0xffffu;
         const int par = t & 1;
+        TICK(0);
 
         // ---------------------------------------------------------- 1. local candidate + publish
-        if (wave == 0) {
+        // every wavefront evaluates the (few) owned columns itself: no broadcast, no barrier
+        int cand;
+        double cand_score;
+        {
             double bs = 0.0;
             int bi = IDX_NONE;
             bool bad = false;
@@ -240,110 +434,117 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 if (!(diag[jl] > 0.0)) { bad = true; continue; }
                 if (better(score[jl], j0 + jl, bs, bi)) { bs = score[jl]; bi = j0 + jl; }
             }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const double so = __shfl_xor(bs, o);
-                const int io = __shfl_xor(bi, o);
-                if (better(so, io, bs, bi)) { bs = so; bi = io; }
-            }
-            bad = __any(bad);
-            if (lane == 0) {
-                if (bad) bi = IDX_ERROR;
-                misc[3] = bi;
-                unsigned long long *slot = S.slots + ((size_t)par * nb + b) * SLOT_WORDS;
-                ll_store(slot + 0, dhi(bs), tag);
-                ll_store(slot + 1, dlo(bs), tag);
-                ll_store(slot + 2, (unsigned)bi, tag);
-            }
-        }
-        __syncthreads();
-        {
-            const int cand = misc[3];
-            if (cand >= 0 && cand != IDX_ERROR) {
-                const int cl = cand - j0;
-                unsigned long long *pw = S.pay + ((size_t)par * nb + b) * S.pay_words;
-                for (int i = tid; i < m; i += LT) ll_store(pw + i, __float_as_uint(wt[(size_t)cl * m + i]), tag);
-                if (tid < k) {
-                    const double u = uloc[tid * cpb + cl];
-                    ll_store(pw + m + 2 * tid, dhi(u), tag);
-                    ll_store(pw + m + 2 * tid + 1, dlo(u), tag);
-                }
-                if (tid == BMAX) {
-                    const double dv = diag[cl];
-                    ll_store(pw + m + 2 * BMAX, dhi(dv), tag);
-                    ll_store(pw + m + 2 * BMAX + 1, dlo(dv), tag);
-                }
+            if (cpb <= 16) row_argmin(bs, bi);      // all candidates sit in lanes 0..15
+            else wave_argmin(bs, bi);
+            bi = __builtin_amdgcn_readfirstlane(bi);
+            bs = readlane_d(bs, 0);
+            if (__any(bad)) bi = IDX_ERROR;
+            cand = bi;
+            cand_score = bs;
+            if (tid == 0) {
+                slot_store(S.slots + ((size_t)par * nb + b) * 2, bs,
+                           bi == IDX_NONE ? ENC_NONE : bi == IDX_ERROR ? ENC_ERROR : (unsigned)bi, tag16);
+#ifdef ZIPLM_LAZY_TIMING
+                tlocal += wall_clock64() - texch;
+#endif
             }
         }
+        // The payload travels ahead of the exchange only from workgroups that are likely to win (score
+        // within the range of the previous step's leaders); any other winner publishes after the
+        // exchange.  Readers wait on the tags either way, so this is a matter of traffic, not of
+        // correctness.
+        const bool published = (cand >= 0) && (cand_score <= tau);
+        auto publish_payload = [&](int col) {
+            const int cl = col - j0;
+            unsigned long long *pw = S.pay + ((size_t)par * nb + b) * S.pay_words;
+            for (int i = tid; i < m; i += LT) ll_store(pw + i, __float_as_uint(WT(cl, i)), tag);
+            if (tid >= LT - BMAX && tid - (LT - BMAX) < k) {     // last wavefront: rarely busy in step 4
+                const int kk = tid - (LT - BMAX);
+                const double u = uloc[kk * cp + cl];
+                ll_store(pw + m + 2 * kk, dhi(u), tag);
+                ll_store(pw + m + 2 * kk + 1, dlo(u), tag);
+            }
+            if (tid == LT - BMAX - 1) {
+                const double dv = diag[cl];
+                ll_store(pw + m + 2 * BMAX, dhi(dv), tag);
+                ll_store(pw + m + 2 * BMAX + 1, dlo(dv), tag);
+            }
+        };
+        if (published) publish_payload(cand);
+        TICK(1);
 
         // ---------------------------------------------------------- 2. all candidates -> argmin
+        int p;
+        double best;
         {
             double s = 0.0;
             int idx = IDX_NONE;
             bool fail = false, err = false;
             for (int sb = tid; sb < nb; sb += LT) {
-                const unsigned long long *slot = S.slots + ((size_t)par * nb + sb) * SLOT_WORDS;
-                unsigned hi, lo, ix;
-                if (!ll_wait(slot + 0, tag, hi, S.status) || !ll_wait(slot + 1, tag, lo, S.status) ||
-                    !ll_wait(slot + 2, tag, ix, S.status)) { fail = true; break; }
-                if ((int)ix == IDX_ERROR) { err = true; continue; }
-                const double sv = dmake(hi, lo);
-                if (better(sv, (int)ix, s, idx)) { s = sv; idx = (int)ix; }
+                double sv;
+                int iv;
+                if (!slot_wait(S.slots + ((size_t)par * nb + sb) * 2, tag16, sv, iv, S.status)) { fail = true; break; }
+                if (iv == IDX_ERROR) { err = true; continue; }
+                if (better(sv, iv, s, idx)) { s = sv; idx = iv; }
             }
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const double so = __shfl_xor(s, o);
-                const int io = __shfl_xor(idx, o);
-                if (better(so, io, s, idx)) { s = so; idx = io; }
+            const int nwaves_used = min(NW, (nb + 63) / 64);
+            if (wave < nwaves_used) {
+                wave_argmin(s, idx);
+                if (lane == 0) { red_s[wave] = s; red_i[wave] = idx; }
             }
-            if (lane == 0) { red_s[wave] = s; red_i[wave] = idx; }
             if (fail) misc[0] = 1;
             if (err) misc[2] = 1;
             __syncthreads();
-            if (tid == 0) {
-                double bs = red_s[0];
-                int bi = red_i[0];
-                for (int w = 1; w < NW; ++w)
-                    if (better(red_s[w], red_i[w], bs, bi)) { bs = red_s[w]; bi = red_i[w]; }
-                misc[1] = bi;
-                misc_d[0] = bs;
+            best = red_s[0];
+            p = red_i[0];
+            double worst = (red_i[0] >= 0) ? red_s[0] : 0.0;
+            for (int w = 1; w < nwaves_used; ++w) {
+                if (better(red_s[w], red_i[w], best, p)) { best = red_s[w]; p = red_i[w]; }
+                if (red_i[w] >= 0 && red_s[w] > worst) worst = red_s[w];
             }
-            __syncthreads();
+            // next step's publication threshold: the largest of the per-wavefront minima (each over 64
+            // workgroups); with a single wavefront of candidates everybody keeps publishing
+            tau = (nwaves_used >= 2) ? worst : 1.0e300;
         }
+        TICK(2);
+#ifdef ZIPLM_LAZY_TIMING
+        if (tid == 0) texch = wall_clock64();
+#endif
         if (misc[0]) { ok = false; break; }
-        const int p = misc[1];
         if (misc[2] || p < 0) { error_step = 1 + t; break; }   // same inputs in every workgroup: uniform
-        const double best = misc_d[0];
         const int owner = p / cpb;
+        if (owner == b && !published) publish_payload(p);
 
         // ---------------------------------------------------------- 3. winner's payload + stale column p
         {
             const unsigned long long *pw = S.pay + ((size_t)par * nb + owner) * S.pay_words;
             bool fail = false;
-            // own rows, column p of the stored matrix (symmetric: equals row p, columns owned here)
-            if (tid < nown && alive_own[tid]) hstale[tid] = S.Hd[(size_t)(j0 + tid) * d + p];
+            // column p of the stored matrix restricted to my rows (= my slice of row p, by symmetry)
+            if (tid < cp) hstale[tid] = P[(size_t)p * cp + tid];
             for (int i = tid; i < m; i += LT) {
                 unsigned v;
                 if (!ll_wait(pw + i, tag, v, S.status)) { fail = true; break; }
                 wcol[i] = __uint_as_float(v);
             }
-            if (tid < k) {
+            if (tid >= LT - BMAX && tid - (LT - BMAX) < k) {
+                const int kk = tid - (LT - BMAX);
                 unsigned hi, lo;
-                if (!ll_wait(pw + m + 2 * tid, tag, hi, S.status) || !ll_wait(pw + m + 2 * tid + 1, tag, lo, S.status)) fail = true;
-                else hist[tid] = dmake(hi, lo);
+                if (!ll_wait2(pw + m + 2 * kk, tag, hi, lo, S.status)) fail = true;
+                else cvec[kk] = dmake(hi, lo) / pivs[kk];
             }
-            if (tid == BMAX) {
+            if (tid == LT - BMAX - 1) {
                 unsigned hi, lo;
-                if (!ll_wait(pw + m + 2 * BMAX, tag, hi, S.status) || !ll_wait(pw + m + 2 * BMAX + 1, tag, lo, S.status)) fail = true;
-                else { misc_d[1] = dmake(hi, lo); pivs[k] = dmake(hi, lo); }
+                if (!ll_wait2(pw + m + 2 * BMAX, tag, hi, lo, S.status)) fail = true;
+                else { const double pv = dmake(hi, lo); misc_d[1] = pv; misc_d[2] = 1.0 / pv; }
             }
             if (fail) misc[0] = 1;
             __syncthreads();
         }
+        TICK(3);
         if (misc[0]) { ok = false; break; }
-        const double piv = misc_d[1];
+        const double piv = misc_d[1], rpiv = misc_d[2];
         if (b == 0 && tid == 0) { S.order[t] = p; S.err[t] = best; }
-        if (tid == 0) alive_bits[p >> 5] &= ~(1u << (p & 31));
+        if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; }
 
         // ---------------------------------------------------------- 4. own slice of the pivot row, Eq. 3
         for (int jl = wave; jl < nown; jl += NW) {
@@ -353,20 +554,29 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 if (lane == 0) alive_own[jl] = 0;
                 continue;
             }
-            double term = 0.0;
-            if (lane < k) term = (hist[lane] / pivs[lane]) * uloc[lane * cpb + jl];
+            const double term = (lane < k) ? cvec[lane] * uloc[lane * cp + jl] : 0.0;
             const double u = hstale[jl] - wave_sum(term);
-            const double f = u / piv;
+            const double f = u * rpiv;
             double s = 0.0;
-            for (int i = lane; i < m; i += 64) {
-                float *w = wt + (size_t)jl * m + i;
-                const float v = (float)((double)(*w) - (double)wcol[i] * f);
-                *w = v;
-                s += (double)v * (double)v;
+            for (int i0 = 0; i0 < m; i0 += 256) {
+                float w[4], c[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = i0 + lane + 64 * e;
+                    w[e] = (i < m) ? WT(jl, i) : 0.f;
+                    c[e] = (i < m) ? wcol[i] : 0.f;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = i0 + lane + 64 * e;
+                    const float v = (float)((double)w[e] - (double)c[e] * f);
+                    if (i < m) WT(jl, i) = v;
+                    s += (double)v * (double)v;
+                }
             }
             s = wave_sum(s);
             if (lane == 0) {
-                uloc[k * cpb + jl] = u;
+                uloc[k * cp + jl] = u;
                 __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const double dj = diag[jl] - u * f;
                 diag[jl] = dj;
@@ -376,6 +586,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         }
         ++k;
         __syncthreads();
+        TICK(4);
 
         // ---------------------------------------------------------- 5. flush the pending downdates
         if (k == BMAX || t + 1 == S.n_remove) {
@@ -387,80 +598,48 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             {
                 bool fail = false;
                 for (int sb = tid; sb < nb; sb += LT) {
-                    unsigned spins = 0;
-                    unsigned long long t0 = 0;
-                    while (__hip_atomic_load(S.bar + sb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bar_epoch) {
-                        if ((++spins & 255u) == 0u) {
-                            if (t0 == 0) t0 = wall_clock64();
-                            if (__hip_atomic_load(S.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == -1 ||
-                                wall_clock64() - t0 > kTimeoutTicks) {
-                                __hip_atomic_store(S.status, -1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                                fail = true;
-                                break;
-                            }
-                        }
-                    }
+                    Waiter w;
+                    while (__hip_atomic_load(S.bar + sb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < bar_epoch)
+                        if (!w.again(S.status)) { fail = true; break; }
                     if (fail) break;
                 }
                 if (fail) misc[0] = 1;
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
             __syncthreads();
+            TICK(5);
             if (misc[0]) { ok = false; break; }
 
-            const double *Ub = S.U + (size_t)ublk * BMAX * d;
-            for (int g0 = 0; g0 < nown; g0 += ROWS_PER_PASS) {
-                const int nrow = min(ROWS_PER_PASS, nown - g0);
-                for (int e = tid; e < BMAX * ROWS_PER_PASS; e += LT) {
-                    const int kk = e / ROWS_PER_PASS, r = e % ROWS_PER_PASS;
-                    double c = 0.0;
-                    if (kk < k && r < nrow && alive_own[g0 + r]) c = uloc[kk * cpb + g0 + r] / pivs[kk];
-                    coef[e] = c;
-                }
-                __syncthreads();
-                for (int c = tid; c < d; c += LT) {
-                    if (!((alive_bits[c >> 5] >> (c & 31)) & 1u)) continue;
-                    double acc[ROWS_PER_PASS];
-#pragma unroll
-                    for (int r = 0; r < ROWS_PER_PASS; ++r) acc[r] = 0.0;
-                    for (int kk = 0; kk < k; ++kk) {
-                        const double u = Ub[(size_t)kk * d + c];
-#pragma unroll
-                        for (int r = 0; r < ROWS_PER_PASS; ++r) acc[r] += coef[kk * ROWS_PER_PASS + r] * u;
-                    }
-#pragma unroll
-                    for (int r = 0; r < ROWS_PER_PASS; ++r)
-                        if (r < nrow && alive_own[g0 + r]) S.Hd[(size_t)(j0 + g0 + r) * d + c] -= acc[r];
-                }
-                __syncthreads();
-            }
+            flush_panel(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits, k, d, cp);
             k = 0;
             ublk ^= 1;
+            TICK(6);
         }
     }
 
     // ------------------------------------------------------------------ final masking + write-back
     __syncthreads();
-    if (b == 0 && tid == 0 && error_step != 0)
-        atomicCAS(S.status, 0, error_step);
+#ifdef ZIPLM_LAZY_TIMING
+    if (b == 0 && tid == 0) for (int q = 0; q < 8; ++q) S.timing[q] = tacc[q];
+    if (tid == 0) S.timing[8 + b] = tlocal;
+#endif
+    if (b == 0 && tid == 0 && error_step != 0) atomicCAS(S.status, 0, error_step);
     if (ok && error_step == 0) {
-        for (int jl = 0; jl < nown; ++jl) {
-            const size_t row = (size_t)(j0 + jl) * d;
-            const bool a = alive_own[jl] != 0;
-            for (int c = tid; c < d; c += LT) {
-                const bool live = a && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
-                S.Hinv[row + c] = live ? (float)S.Hd[row + c] : 0.f;
-            }
+        for (int c = tid; c < d; c += LT) {
+            const bool col_live = (alive_bits[c >> 5] >> (c & 31)) & 1u;
+            for (int r = 0; r < nown; ++r)
+                S.Hinv[(size_t)(j0 + r) * d + c] = (col_live && alive_own[r]) ? (float)P[(size_t)c * cp + r] : 0.f;
         }
         for (int jl = wave; jl < nown; jl += NW) {
             const bool a = alive_own[jl] != 0;
-            for (int i = lane; i < m; i += 64) S.W[(size_t)i * d + j0 + jl] = a ? wt[(size_t)jl * m + i] : 0.f;
+            for (int i = lane; i < m; i += 64) S.W[(size_t)i * d + j0 + jl] = a ? WT(jl, i) : 0.f;
         }
     }
+#undef WT
 }
 
 struct Plan {
-    int nb, cpb, w_in_lds, pay_words;
+    int nb, cpb, cp, w_in_lds, pay_words;
     size_t lds_bytes;
     bool feasible;
 };
@@ -469,12 +648,13 @@ static Plan make_plan(int d_row, int d_col) {
     Plan p = {};
     const int cus = device_cu_count();
     p.cpb = (d_col + cus - 1) / cus;
+    p.cp = (p.cpb + RG - 1) / RG * RG;
     p.nb = (d_col + p.cpb - 1) / p.cpb;
     p.pay_words = d_row + 2 * BMAX + 2;
-    const size_t lds_cap = 150 * 1024;
-    p.w_in_lds = lds_layout(d_row, d_col, p.cpb, true).total <= lds_cap ? 1 : 0;
-    p.lds_bytes = lds_layout(d_row, d_col, p.cpb, p.w_in_lds != 0).total;
-    p.feasible = p.lds_bytes <= lds_cap;
+    const size_t lds_cap = 158 * 1024;
+    p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb).total <= lds_cap ? 1 : 0;
+    p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb).total;
+    p.feasible = p.lds_bytes <= lds_cap && d_col <= MAX_D;
     return p;
 }
 
@@ -488,15 +668,18 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     Layout l = {};
     State &s = l.st;
     Carver c(ws);
-    s.Hd = c.take<double>((size_t)d_col * d_col);
+    s.P = c.take<double>((size_t)p.nb * d_col * p.cp);
     s.Wt = c.take<float>(p.w_in_lds ? 1 : (size_t)d_col * d_row);
     s.U = c.take<double>((size_t)2 * BMAX * d_col);
     // zero-initialised region: slots, payload, barrier epochs, status
-    s.slots = c.take<unsigned long long>((size_t)2 * p.nb * SLOT_WORDS);
+    s.slots = c.take<unsigned long long>((size_t)2 * p.nb * 2);
     s.pay = c.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
     s.bar = c.take<unsigned long long>((size_t)p.nb);
     s.status = c.take<int>(1);
     l.snap_steps = c.take<int>((size_t)(n_snap > 0 ? n_snap : 1));
+#ifdef ZIPLM_LAZY_TIMING
+    s.timing = c.take<unsigned long long>(8 + 1024);
+#endif
     l.bytes = c.off;
     return l;
 }
@@ -522,7 +705,7 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
     S.W = W; S.Hinv = Hinv; S.m = d_row; S.d = d_col; S.n_remove = n_remove;
     S.order = order_out; S.err = err_out; S.alive_in = alive_in;
     S.n_snap = n_snap; S.snap_steps = l.snap_steps; S.W_snap = W_snap;
-    S.cpb = p.cpb; S.w_in_lds = p.w_in_lds; S.pay_words = p.pay_words;
+    S.cpb = p.cpb; S.cp = p.cp; S.pay_words = p.pay_words;
     if (n_snap > 0) {
         // pageable source: staged before the call returns
         ZIPLM_HIP_TRY(hipMemcpyAsync(l.snap_steps, snap_steps_host, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st));
@@ -530,18 +713,36 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
     }
     const size_t zero_bytes = reinterpret_cast<char *>(l.snap_steps) - reinterpret_cast<char *>(S.slots);
     ZIPLM_HIP_TRY(hipMemsetAsync(S.slots, 0, zero_bytes, st));
-    static bool attr_set = false;
-    if (!attr_set) {
-        ZIPLM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(prune_lazy_kernel),
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set = true;
+    const void *fn = p.w_in_lds ? reinterpret_cast<const void *>(prune_lazy_kernel<true>)
+                                : reinterpret_cast<const void *>(prune_lazy_kernel<false>);
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[p.w_in_lds]) {
+        ZIPLM_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_set[p.w_in_lds] = true;
     }
     int per_cu = 0;
-    ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_lazy_kernel, LT, p.lds_bytes));
+    if (p.w_in_lds) ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_lazy_kernel<true>, LT, p.lds_bytes));
+    else ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_lazy_kernel<false>, LT, p.lds_bytes));
     if (per_cu < 1 || p.nb > per_cu * device_cu_count()) return ZIPLM_ERR_DEVICE;
     void *args[] = {&S};
-    ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<void *>(prune_lazy_kernel), dim3(p.nb), dim3(LT), args,
-                                             (unsigned)p.lds_bytes, st));
+    ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(const_cast<void *>(fn), dim3(p.nb), dim3(LT), args, (unsigned)p.lds_bytes, st));
+#ifdef ZIPLM_LAZY_TIMING
+    {
+        unsigned long long tm[8];
+        hipStreamSynchronize(st);
+        hipMemcpy(tm, S.timing, sizeof(tm), hipMemcpyDeviceToHost);
+        const char *names[8] = {"snapshot+loop top", "candidate+publish", "exchange+argmin", "payload+gather", "row slice + Eq.3",
+                                "flush barrier", "flush update", "-"};
+        for (int q = 0; q < 7; ++q)
+            fprintf(stderr, "[lazy timing] %-20s %9.3f ms total  %7.3f us/step\n", names[q], tm[q] * 1e-5,
+                    tm[q] * 1e-2 / (n_remove > 0 ? n_remove : 1));
+        unsigned long long loc[1024];
+        hipMemcpy(loc, S.timing + 8, sizeof(unsigned long long) * p.nb, hipMemcpyDeviceToHost);
+        double mn = 1e30, mx = 0, sum = 0; int imx = 0;
+        for (int q = 0; q < p.nb; ++q) { double v = loc[q] * 1e-2 / (n_remove > 0 ? n_remove : 1); sum += v; if (v < mn) mn = v; if (v > mx) { mx = v; imx = q; } }
+        fprintf(stderr, "[lazy timing] local us/step (exchange done -> slot published): min %.3f avg %.3f max %.3f (block %d)\n", mn, sum / p.nb, mx, imx);
+    }
+#endif
     *status_dev_out = S.status;
     return ZIPLM_OK;
 }

@@ -10,7 +10,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libziplm.so")
+# ZIPLM_LIBRARY selects another build of the same ABI (for instance an instrumented one)
+LIB_PATH = os.environ.get("ZIPLM_LIBRARY") or os.path.join(_HERE, "libziplm.so")
 
 OK = 0
 ERR_INVALID_ARG = -1
