@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="also run one plain device-to-device copy of this many MiB before the timed steps, so a "
+                         "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic to scale counters by")
     ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
                     help="per-launch HBM KiB of the loop kernel from rocprofv3 --pmc runs (for the record)")
     args = ap.parse_args()
@@ -96,6 +99,14 @@ def main():
             result["events"].append(e)
         return order, err
 
+    if args.calibration_copy_mib > 0:
+        n = args.calibration_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)          # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()

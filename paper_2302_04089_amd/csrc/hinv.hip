@@ -4,7 +4,7 @@
 //   A  = H + lambda I, embedded in a dp x dp matrix (dp = d_col rounded up to 128) whose padding is
 //        the identity, so that every internal product runs on whole tiles;
 //   A  = L L^T     right-looking blocked Cholesky, 64-column panels:
-//                  diagonal block factored and inverted inside LDS by one workgroup,
+//                  diagonal block factored and inverted in the registers of one wavefront,
 //                  panel  L21 = A21 inv(L11)^T  and trailing update  A22 -= L21 L21^T  on the
 //                  fp32 matrix cores;
 //   T  = L^-1      bottom-up pairwise merges  T21 = -T22 (L21 T11), all pairs of a level in one
@@ -51,56 +51,53 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ H,
 
 // Factor the 64 x 64 diagonal block at (k0, k0) of A in place (lower triangle) and store the
 // inverse of the factor, a dense 64 x 64 lower-triangular matrix, in dinv.
-// Right-looking column Cholesky in LDS; the triangular inverse by forward substitution, one
-// column per thread.  A non-positive pivot records 1 + its global column in *info (first one wins)
-// and is replaced by 1 so that the remaining arithmetic stays finite.
-__global__ __launch_bounds__(256) void potrf_diag_kernel(float *__restrict__ A, int ld, int k0,
-                                                         float *__restrict__ dinv, int *__restrict__ info) {
-    __shared__ float L[NB][NB + 1];
-    __shared__ float T[NB][NB + 1];
-    const int tid = threadIdx.x;
+// One wavefront, everything in registers: lane i holds row i of the block (64 VGPRs) and, for the
+// inverse, lane c holds column c of T = L^-1.  An entry another lane needs is always "register j
+// of lane c" with both known at compile time after full unrolling, i.e. one v_readlane.
+//   factorisation, right-looking:  L[i][j] = A[i][j] / l_jj ;  A[i][c] -= L[i][j] L[c][j]  (j < c <= i)
+//   inverse, forward substitution: T[i][c] = (delta_ic - sum_{k<i} L[i][k] T[k][c]) / L[i][i]
+// A non-positive pivot records 1 + its global column in *info (first one wins) and is replaced by 1
+// so that the remaining arithmetic stays finite.
+__device__ __forceinline__ float lane_bcast(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+__global__ __launch_bounds__(64) void potrf_diag_kernel(float *__restrict__ A, int ld, int k0,
+                                                        float *__restrict__ dinv, int *__restrict__ info) {
+    const int lane = threadIdx.x;
     float *Ab = A + (int64_t)k0 * ld + k0;
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int i = e / NB, j = e % NB;
-        L[i][j] = (j <= i) ? Ab[(int64_t)i * ld + j] : 0.f;
-        T[i][j] = 0.f;
-    }
-    __syncthreads();
+    float a[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c) a[c] = Ab[(int64_t)lane * ld + c];   // upper entries are never used
+    float rdiag[NB];                                                  // 1 / l_jj, uniform
+#pragma unroll
     for (int j = 0; j < NB; ++j) {
-        if (tid == 0) {
-            float s = L[j][j];
-            if (!(s > 0.f)) {
-                if (*info == 0) *info = 1 + k0 + j;
-                s = 1.f;
-            }
-            L[j][j] = sqrtf(s);
+        float piv = lane_bcast(a[j], j);
+        if (!(piv > 0.f)) {                  // uniform
+            if (lane == 0 && *info == 0) *info = 1 + k0 + j;
+            piv = 1.f;
         }
-        __syncthreads();
-        const float inv = 1.0f / L[j][j];
-        if (tid > j && tid < NB) L[tid][j] *= inv;
-        __syncthreads();
-        const int n = NB - 1 - j;
-        for (int e = tid; e < n * n; e += 256) {
-            const int i = j + 1 + e / n, c = j + 1 + e % n;
-            if (c <= i) L[i][c] -= L[i][j] * L[c][j];
-        }
-        __syncthreads();
+        const float ljj = sqrtf(piv);
+        const float r = 1.0f / ljj;
+        rdiag[j] = r;
+        a[j] = (lane == j) ? ljj : a[j] * r;              // column j of L (rows above j: unused)
+#pragma unroll
+        for (int c = j + 1; c < NB; ++c) a[c] -= a[j] * lane_bcast(a[j], c);
     }
-    // T = L^-1: thread c owns column c (entries of its own column only: no barrier needed)
-    if (tid < NB) {
-        const int c = tid;
-        for (int i = c; i < NB; ++i) {
-            float s = (i == c) ? 1.f : 0.f;
-            for (int k = c; k < i; ++k) s -= L[i][k] * T[k][c];
-            T[i][c] = s / L[i][i];
-        }
+    // T = L^-1, lane = column
+    float t[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+        float s = (lane == i) ? 1.f : 0.f;
+#pragma unroll
+        for (int k = 0; k < i; ++k) s -= lane_bcast(a[k], i) * t[k];
+        t[i] = s * rdiag[i];
     }
-    __syncthreads();
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int i = e / NB, j = e % NB;
-        if (j <= i) Ab[(int64_t)i * ld + j] = L[i][j];
-        dinv[e] = T[i][j];
-    }
+#pragma unroll
+    for (int c = 0; c < NB; ++c)
+        if (c <= lane) Ab[(int64_t)lane * ld + c] = a[c];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) dinv[i * NB + lane] = t[i];          // t[i] = T[i][lane], zero above the diagonal
 }
 
 // T (dp x dp) = block diagonal of the inverted 64 x 64 factors, zero elsewhere.
@@ -163,7 +160,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     // ---- A = L L^T, right-looking over 64-column panels --------------------------------------
     for (int k0 = 0; k0 < dp; k0 += NB) {
         float *dinv = l.dinv + (size_t)(k0 / NB) * NB * NB;
-        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(256), 0, st, l.A, dp, k0, dinv, l.info);
+        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(64), 0, st, l.A, dp, k0, dinv, l.info);
         const int rest = dp - k0 - NB;
         if (rest <= 0) break;
         float *A21 = l.A + (int64_t)(k0 + NB) * dp + k0;

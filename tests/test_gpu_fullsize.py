@@ -1,0 +1,141 @@
+"""GPU parity at the benchmark's full size (configuration 3: BERT-base feed-forward down-projection,
+W 768 x 3072, 16384 post-GELU calibration tokens, every column removed), in the launch configuration
+bench.py times, plus property checks at configuration 4 (1024 x 4096, 65536 tokens) where the oracle
+would take minutes.
+
+  * Hessian: sampled entries against fp64 dot products of the same fp32 inputs; exact symmetry.
+  * inverse: (H + lambda I) Hinv = I checked in fp64 on the host.
+  * greedy loop: the complete protocol of tests/parity_protocol.py against the oracle run on the very
+    same fp32 inverse, W snapshots at several sparsities, and the telescoping identity
+    sum_t err_t = tr(W0 inv(Hinv0) W0^T)  (removing everything costs the whole layer energy).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2302_04089_amd import workloads
+
+from parity_protocol import REL_TOL, compare_run, rel_fro
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def z():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    from paper_2302_04089_amd import ziplm
+    ziplm.lib()
+    return ziplm
+
+
+def _sampled_hessian_check(H_gpu, X, scale, n_samples=1500, seed=0, tol=1e-5):
+    d = X.shape[0]
+    rng = np.random.default_rng(seed)
+    ii = rng.integers(0, d, n_samples)
+    jj = rng.integers(0, d, n_samples)
+    ii[:50] = jj[:50]                      # some diagonal entries
+    diag = np.array([scale * np.dot(X[i].astype(np.float64), X[i].astype(np.float64)) for i in range(0, d, max(1, d // 64))])
+    dref = diag.mean()
+    worst = 0.0
+    for i, j in zip(ii, jj):
+        ref = scale * np.dot(X[i].astype(np.float64), X[j].astype(np.float64))
+        worst = max(worst, abs(float(H_gpu[i, j]) - ref) / dref)
+    assert worst <= tol, "sampled Hessian entries off by %.3e of the mean diagonal" % worst
+
+
+def test_config3_full_pipeline_matches_oracle(z, oracle):
+    spec = workloads.config(3)
+    d, m = spec.d_col, spec.d_row
+    X = workloads.make_X(spec)
+    W32 = workloads.make_W(spec)
+    Xd = torch.from_numpy(X).cuda()
+
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, Xd, 2.0)
+    Hh = H.cpu().numpy()
+    assert np.array_equal(Hh, Hh.T)
+    _sampled_hessian_check(Hh, X, 2.0)
+
+    Hi, lam = z.ziplm_hinv(H, spec.damp_rel)
+    Hi32 = Hi.cpu().numpy()
+    assert np.array_equal(Hi32, Hi32.T)
+    A = Hh.astype(np.float64) + float(lam) * np.eye(d)
+    resid = np.abs(A @ Hi32.astype(np.float64) - np.eye(d)).max()
+    assert resid <= 1e-3, "||(H + lambda I) Hinv - I||_max = %.3e" % resid     # cond ~ 2e3, fp32 factorisation
+    assert lam == pytest.approx(0.01 * np.trace(Hh.astype(np.float64)) / d, rel=1e-5)
+
+    snaps = [d // 4, d // 2, (3 * d) // 4, (9 * d) // 10, d - 8]
+    Wd = torch.from_numpy(W32).cuda()
+    order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hi, 1, d, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    order_h, err_h = order.cpu().numpy(), err.cpu().numpy()
+    assert sorted(order_h.tolist()) == list(range(d))
+    assert np.all(err_h >= 0.0)
+    assert float(Wd.abs().max()) == 0.0 and float(Hi.abs().max()) == 0.0
+
+    ref = compare_run(oracle, W32, Hi32, 1, d, order_h, err_h, snap_steps=snaps)
+    for q, k in enumerate(snaps):
+        got = W_snap[q].cpu().numpy()
+        want = ref["W_snap"][q]
+        assert rel_fro(got, want) <= REL_TOL, "W after %d removals" % k
+        dead = np.all(want == 0.0, axis=0)
+        assert np.all(got[:, dead] == 0.0)
+
+    # telescoping: removing every column costs tr(W0 inv(Hinv0) W0^T)
+    total = np.trace(W32.astype(np.float64) @ np.linalg.solve(Hi32.astype(np.float64), W32.astype(np.float64).T))
+    assert err_h.sum() == pytest.approx(total, rel=1e-6)
+
+
+def test_config4_properties(z):
+    spec = workloads.config(4)
+    d, m = spec.d_col, spec.d_row
+    X = workloads.make_X(spec)
+    W32 = workloads.make_W(spec)
+    Xd = torch.from_numpy(X).cuda()
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    # two batches of tokens, as a calibration loop would deliver them
+    half = spec.n_tok // 2
+    z.ziplm_hessian_accumulate(H, Xd[:, :half].contiguous(), 2.0)
+    z.ziplm_hessian_accumulate(H, Xd[:, half:].contiguous(), 2.0)
+    Hh = H.cpu().numpy()
+    assert np.array_equal(Hh, Hh.T)
+    _sampled_hessian_check(Hh, X, 2.0, n_samples=400, tol=2e-5)
+    del Xd
+
+    Hi, lam = z.ziplm_hinv(H, spec.damp_rel)
+    Hi32 = Hi.cpu().numpy()
+    # (H + lambda I) Hinv = I on a sample of columns
+    cols = np.random.default_rng(1).integers(0, d, 64)
+    A = Hh.astype(np.float64)
+    A[np.diag_indices(d)] += float(lam)
+    R = A @ Hi32[:, cols].astype(np.float64)
+    R[cols, np.arange(len(cols))] -= 1.0
+    assert np.abs(R).max() <= 2e-3
+
+    k_snap = d // 2
+    Wd = torch.from_numpy(W32).cuda()
+    order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hi, 1, d, snapshot_steps=[k_snap])
+    torch.cuda.synchronize()
+    order_h, err_h = order.cpu().numpy(), err.cpu().numpy()
+    assert sorted(order_h.tolist()) == list(range(d))
+    assert np.all(err_h >= 0.0)
+    assert float(Wd.abs().max()) == 0.0
+    W64 = W32.astype(np.float64)
+    Hi64 = Hi32.astype(np.float64)
+    total = np.trace(W64 @ np.linalg.solve(Hi64, W64.T))
+    assert err_h.sum() == pytest.approx(total, rel=1e-6)
+    # weights after k removals depend only on the removed set: W[:, R] = W0 Hinv0^-1[:, R] (Hinv0^-1[R, R])^-1
+    # is checked through its defining property instead: the update leaves W Hinv0^-1 unchanged on the
+    # surviving columns' normal equations, i.e. (W_k - W0) inv(Hinv0) has no component on survivors.
+    gone = np.zeros(d, bool)
+    gone[order_h[:k_snap]] = True
+    Wk = W_snap[0].cpu().numpy().astype(np.float64)
+    assert np.all(Wk[:, gone] == 0.0)
+    G = np.linalg.solve(Hi64, (Wk - W64).T).T          # (W_k - W0) H
+    live_part = np.abs(G[:, ~gone]).max()
+    scale = np.abs(np.linalg.solve(Hi64, W64.T)).max()
+    assert live_part <= 1e-4 * scale, "stationarity on the surviving columns violated: %.3e vs %.3e" % (live_part, scale)
+    # and the first k errors add up to the error of that joint removal: tr((W_k - W0) H (W_k - W0)^T)
+    joint = np.sum(G * (Wk - W64))
+    assert err_h[:k_snap].sum() == pytest.approx(joint, rel=1e-4)
