@@ -21,6 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the greedy-loop kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
+# in profiles/greedy_loop_and_hessian_config3_hbm_counters.md (KiB, already scaled by the copy-kernel factors);
+# --traffic-kib overrides them after a new counter run.
+MEASURED_TRAFFIC_KIB = {3: (3809593.0, 3169652.0)}
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
@@ -133,8 +137,9 @@ def main():
     hess_tflops = syrk_flops / (mean["hessian"] * 1e-3) / 1e12
 
     traffic = None
-    if args.traffic_kib is not None:
-        traffic = (args.traffic_kib[0] + args.traffic_kib[1]) * 1024.0
+    kib = args.traffic_kib if args.traffic_kib is not None else MEASURED_TRAFFIC_KIB.get(args.config)
+    if kib is not None:
+        traffic = (kib[0] + kib[1]) * 1024.0
 
     out = {
         "metric": "structured-OBS prune time per layer (Hessian + inverse + greedy loop)",

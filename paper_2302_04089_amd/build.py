@@ -15,12 +15,21 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, 
 
 
 def build(verbose=False):
+    """Compiles csrc/*.hip and links libziplm.so next to this file.
+
+    Environment (optional): HIPCC; ZIPLM_EXTRA_HIPCC_FLAGS, e.g. "-DZIPLM_LAZY_TIMING" for the build that
+    prints the greedy loop's per-phase times; ZIPLM_BUILD_LIB, another output path for such a build (its
+    objects then go to a directory beside it, so the regular build is left alone)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = os.environ.get("ZIPLM_EXTRA_HIPCC_FLAGS", "").split()
+    lib = os.environ.get("ZIPLM_BUILD_LIB") or LIB
+    objdir = CSRC if lib == LIB else lib + ".objs"
+    os.makedirs(objdir, exist_ok=True)
     objs = []
     procs = []
     for s in SOURCES:
-        obj = os.path.join(CSRC, s.replace(".hip", ".o"))
-        cmd = [hipcc] + FLAGS + ["-c", os.path.join(CSRC, s), "-o", obj]
+        obj = os.path.join(objdir, s.replace(".hip", ".o"))
+        cmd = [hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, s), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
@@ -32,8 +41,8 @@ def build(verbose=False):
             raise RuntimeError("hipcc failed on %s:\n%s" % (s, out))
         if verbose and out.strip():
             print(out)
-    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs)
-    return LIB
+    subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib] + objs)
+    return lib
 
 
 if __name__ == "__main__":
