@@ -53,8 +53,7 @@ constexpr int NTI = 2;                  // column tiles a wavefront interleaves 
 constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
-constexpr unsigned ENC_NONE = 0xFFFFu, ENC_ERROR = 0xFFFEu;
-constexpr int MAX_D = 65000;             // column index travels in 16 bits
+constexpr int MAX_CPB = 250;             // the local column index travels in 8 bits
 
 struct State {
     // caller's buffers
@@ -72,7 +71,7 @@ struct State {
     double *P;                    // [nb][d][cp]  panels of the stored (stale between flushes) inverse Hessian
     float *Wt;                    // [d][m]       transposed W when it does not fit LDS, else unused
     double *U;                    // [2][BMAX][d] pending pivot rows of the current / previous block of steps
-    unsigned long long *slots;    // [2][nb][2]
+    unsigned long long *slots;    // [2][nb]
     unsigned long long *pay;      // [2][nb][pay_words]
     unsigned long long *bar;      // [nb] flush-barrier epochs
     int *status;
@@ -131,22 +130,26 @@ __device__ __forceinline__ bool ll_wait2(const unsigned long long *p, unsigned t
         if (!w.again(status)) return false;
     }
 }
-// Candidate slot: word0 = [score bits 63..32 | index:16 | tag:16], word1 = [score bits 31..0 | 0:16 | tag:16].
-__device__ __forceinline__ void slot_store(unsigned long long *p, double score, unsigned enc_idx, unsigned tag16) {
+// Candidate slot, one 64-bit word: [score bits 63..12 | local column index : 8 | tag : 4].
+// Scores are positive doubles, whose order is the order of their bit patterns; dropping the 12 lowest
+// mantissa bits keeps that order and merges only scores closer than 2^-40 relative, which then go to the
+// lower column index like any tie.  The exact score of the winner is reported by its owner.
+constexpr unsigned ENC_NONE = 0xFFu, ENC_ERROR = 0xFEu;
+__device__ __forceinline__ void slot_store(unsigned long long *p, double score, unsigned enc_idx, unsigned tag4) {
     const unsigned long long b = (unsigned long long)__double_as_longlong(score);
-    __hip_atomic_store(p, ((b >> 32) << 32) | ((unsigned long long)enc_idx << 16) | tag16, __ATOMIC_RELAXED,
+    __hip_atomic_store(p, (b & ~0xfffull) | ((unsigned long long)enc_idx << 4) | tag4, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 1, ((b & 0xffffffffull) << 32) | tag16, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ bool slot_wait(const unsigned long long *p, unsigned tag16, double &score, int &idx, int *status) {
+// Waits for slot `sb`; idx becomes the global column (cpb * sb + local index), IDX_NONE or IDX_ERROR.
+__device__ __forceinline__ bool slot_wait(const unsigned long long *p, unsigned tag4, int sb, int cpb, double &score,
+                                          int &idx, int *status) {
     Waiter w;
     for (;;) {
-        const unsigned long long v0 = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned long long v1 = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if ((unsigned)(v0 & 0xffffu) == tag16 && (unsigned)(v1 & 0xffffu) == tag16) {
-            score = __longlong_as_double((long long)(((v0 >> 32) << 32) | (v1 >> 32)));
-            const unsigned e = (unsigned)((v0 >> 16) & 0xffffu);
-            idx = (e == ENC_NONE) ? IDX_NONE : (e == ENC_ERROR) ? IDX_ERROR : (int)e;
+        const unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if ((unsigned)(v & 0xfu) == tag4) {
+            score = __longlong_as_double((long long)(v & ~0xfffull));
+            const unsigned e = (unsigned)((v >> 4) & 0xffu);
+            idx = (e == ENC_NONE) ? IDX_NONE : (e == ENC_ERROR) ? IDX_ERROR : sb * cpb + (int)e;
             return true;
         }
         if (!w.again(status)) return false;
@@ -224,7 +227,7 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     Lds l;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 15) / 16 * 16; return r; };
-    l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [k][row]
+    l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [row][k]
     l.cvec = take(sizeof(double) * BMAX);                // u_k[p] / piv_k for the current pivot
     l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
     l.wcol = take(m * sizeof(float) > LT * sizeof(double) ? m * sizeof(float) : LT * sizeof(double));
@@ -262,7 +265,7 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
         {   // one A fragment entry per thread: k-group tid/64, lane tid%64
             const int kk = 4 * wave + q4;
             const int arow = g0 + 4 * (cl16 & 3) + (cl16 >> 2);
-            coefa[tid] = (kk < k && alive_own[arow]) ? uloc[kk * cp + arow] / pivs[kk] : 0.0;
+            coefa[tid] = (kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
         }
         __syncthreads();
         // a wavefront works on NTI adjacent 16-column tiles at a time, so that 4 * NTI loads of
@@ -402,6 +405,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     int t = 0;
     bool ok = true;
     int error_step = 0;
+    unsigned tag4 = 0;
     double tau = 1.0e300;   // publish the payload ahead of the exchange only if my best score is <= tau
 
     for (; t <= S.n_remove; ++t) {
@@ -417,7 +421,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         if (t == S.n_remove) break;
 
         const unsigned tag = (unsigned)(t + 1);
-        const unsigned tag16 = tag & 0xffffu;
+        tag4 = (tag4 == 15u) ? 1u : tag4 + 1u;              // 1..15: never 0 (the initial fill), differs from step t - 2
         const int par = t & 1;
         TICK(0);
 
@@ -442,8 +446,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             cand = bi;
             cand_score = bs;
             if (tid == 0) {
-                slot_store(S.slots + ((size_t)par * nb + b) * 2, bs,
-                           bi == IDX_NONE ? ENC_NONE : bi == IDX_ERROR ? ENC_ERROR : (unsigned)bi, tag16);
+                slot_store(S.slots + (size_t)par * nb + b, bs,
+                           bi == IDX_NONE ? ENC_NONE : bi == IDX_ERROR ? ENC_ERROR : (unsigned)(bi - j0), tag4);
 #ifdef ZIPLM_LAZY_TIMING
                 tlocal += wall_clock64() - texch;
 #endif
@@ -460,7 +464,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             for (int i = tid; i < m; i += LT) ll_store(pw + i, __float_as_uint(WT(cl, i)), tag);
             if (tid >= LT - BMAX && tid - (LT - BMAX) < k) {     // last wavefront: rarely busy in step 4
                 const int kk = tid - (LT - BMAX);
-                const double u = uloc[kk * cp + cl];
+                const double u = uloc[cl * BMAX + kk];
                 ll_store(pw + m + 2 * kk, dhi(u), tag);
                 ll_store(pw + m + 2 * kk + 1, dlo(u), tag);
             }
@@ -483,7 +487,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             for (int sb = tid; sb < nb; sb += LT) {
                 double sv;
                 int iv;
-                if (!slot_wait(S.slots + ((size_t)par * nb + sb) * 2, tag16, sv, iv, S.status)) { fail = true; break; }
+                if (!slot_wait(S.slots + (size_t)par * nb + sb, tag4, sb, cpb, sv, iv, S.status)) { fail = true; break; }
+#ifdef ZIPLM_LAZY_TIMING
+                if (b == 0 && tid == 0) tacc[7] += wall_clock64() - tlast;     // own slot seen again: store -> load round trip
+#endif
                 if (iv == IDX_ERROR) { err = true; continue; }
                 if (better(sv, iv, s, idx)) { s = sv; idx = iv; }
             }
@@ -543,7 +550,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         TICK(3);
         if (misc[0]) { ok = false; break; }
         const double piv = misc_d[1], rpiv = misc_d[2];
-        if (b == 0 && tid == 0) { S.order[t] = p; S.err[t] = best; }
+        if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = cand_score; }   // exact score: the winner is my candidate
         if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; }
 
         // ---------------------------------------------------------- 4. own slice of the pivot row, Eq. 3
@@ -554,7 +561,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 if (lane == 0) alive_own[jl] = 0;
                 continue;
             }
-            const double term = (lane < k) ? cvec[lane] * uloc[lane * cp + jl] : 0.0;
+            const double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
             const double u = hstale[jl] - wave_sum(term);
             const double f = u * rpiv;
             double s = 0.0;
@@ -576,7 +583,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             }
             s = wave_sum(s);
             if (lane == 0) {
-                uloc[k * cp + jl] = u;
+                uloc[jl * BMAX + k] = u;
                 __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const double dj = diag[jl] - u * f;
                 diag[jl] = dj;
@@ -654,7 +661,7 @@ static Plan make_plan(int d_row, int d_col) {
     const size_t lds_cap = 158 * 1024;
     p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb).total <= lds_cap ? 1 : 0;
     p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb).total;
-    p.feasible = p.lds_bytes <= lds_cap && d_col <= MAX_D;
+    p.feasible = p.lds_bytes <= lds_cap && p.cpb <= MAX_CPB;
     return p;
 }
 
@@ -672,7 +679,7 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     s.Wt = c.take<float>(p.w_in_lds ? 1 : (size_t)d_col * d_row);
     s.U = c.take<double>((size_t)2 * BMAX * d_col);
     // zero-initialised region: slots, payload, barrier epochs, status
-    s.slots = c.take<unsigned long long>((size_t)2 * p.nb * 2);
+    s.slots = c.take<unsigned long long>((size_t)2 * p.nb);
     s.pay = c.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
     s.bar = c.take<unsigned long long>((size_t)p.nb);
     s.status = c.take<int>(1);
@@ -732,8 +739,8 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
         hipStreamSynchronize(st);
         hipMemcpy(tm, S.timing, sizeof(tm), hipMemcpyDeviceToHost);
         const char *names[8] = {"snapshot+loop top", "candidate+publish", "exchange+argmin", "payload+gather", "row slice + Eq.3",
-                                "flush barrier", "flush update", "-"};
-        for (int q = 0; q < 7; ++q)
+                                "flush barrier", "flush update", "(own slot round trip)"};
+        for (int q = 0; q < 8; ++q)
             fprintf(stderr, "[lazy timing] %-20s %9.3f ms total  %7.3f us/step\n", names[q], tm[q] * 1e-5,
                     tm[q] * 1e-2 / (n_remove > 0 ? n_remove : 1));
         unsigned long long loc[1024];
