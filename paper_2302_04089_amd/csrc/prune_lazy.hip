@@ -30,8 +30,12 @@
 //      winner's payload, forms its slice of the current pivot row, updates its diagonal entries,
 //      compensates its columns of W and refreshes their norms and scores.
 //
-// One exchange per step is the only device-wide synchronisation; every 64 steps one barrier
-// precedes the flush.  All waits are bounded: on a time-out the waiter raises status = -1 and
+// One exchange per step is the only device-wide synchronisation; every 64 steps one barrier makes the
+// finished block of pending rows visible.  When a workgroup owns at most 16 columns the flush of that
+// block is then not done at once but in the background: while four wavefronts wait for the next steps'
+// candidates, the other twelve each apply half a column tile of the previous block per step.  A pivot
+// whose column tile has not been reached yet gets the previous block's downdates applied on the fly,
+// exactly like the pending ones of the current block.  All waits are bounded: on a time-out the waiter raises status = -1 and
 // leaves; the others then time out or see the flag, and the grid drains.
 #include <stdio.h>
 
@@ -49,7 +53,11 @@ constexpr int LT = 1024;                 // threads per workgroup (16 wavefronts
 constexpr int NW = LT / 64;
 constexpr int BMAX = 64;                 // pending pivot rows between flushes (one lane per row)
 constexpr int RG = 16;                   // owned rows per matrix-core pass (panel rows are padded to this)
-constexpr int NTI = 2;                  // column tiles a wavefront interleaves in a flush
+constexpr int NTI = 1;                  // column tiles a wavefront interleaves in a flush
+constexpr int AFRAG = (BMAX / 4) * 64;  // entries of one set of matrix-core A fragments: [k-group][lane]
+constexpr int NPOLL = 4;                // wavefronts that poll the candidate slots (up to 256 workgroups)
+constexpr int NBG = NW - NPOLL;         // wavefronts that apply the previous block's downdates meanwhile
+constexpr int BG_KS = 4;                // k-groups (of 4 pending rows) a background unit covers: a quarter tile
 constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
@@ -77,7 +85,7 @@ struct State {
     int *status;
     int cpb;                      // columns per workgroup
     int cp;                       // cpb rounded up to a multiple of RG
-    int pay_words;                // m + 2*BMAX + 2
+    int pay_words;                // m + 4*BMAX + 2
 #ifdef ZIPLM_LAZY_TIMING
     unsigned long long *timing;   // [8] accumulated 100 MHz ticks per phase (workgroup 0), then [nb] local ticks
 #endif
@@ -221,16 +229,23 @@ __device__ __forceinline__ void wave_argmin(double &s, int &i) {
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, cvec, pivs, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, red_i, misc, wt, total;
+    size_t uloc, uprev, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, red_i, misc, wt, total;
 };
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
     Lds l;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 15) / 16 * 16; return r; };
     l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [row][k]
+    l.uprev = take(sizeof(double) * BMAX * cp);          // the same for the previous block (background flush)
+    l.coefbg = take(sizeof(double) * AFRAG);              // matrix-core A fragments of the background flush
+    l.bgacc = take(sizeof(double) * 4 * 64 * NBG);       // its accumulators between steps: [wavefront][4][lane]
+    l.bgpart = take(sizeof(int) * NW);                   // k-group quarter each background wavefront is at
     l.cvec = take(sizeof(double) * BMAX);                // u_k[p] / piv_k for the current pivot
+    l.cprev = take(sizeof(double) * BMAX);               // the same over the previous block's rows
+    l.pivprev = take(sizeof(double) * BMAX);
+    l.seq_done = take(sizeof(int) * NW);                 // column tiles each background wavefront has finished
     l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
-    l.wcol = take(m * sizeof(float) > LT * sizeof(double) ? m * sizeof(float) : LT * sizeof(double));
+    l.wcol = take(m * sizeof(float) > AFRAG * sizeof(double) ? m * sizeof(float) : AFRAG * sizeof(double));
                                                          // column p of W (fp32) during a step; matrix-core A
                                                          // fragments [k/4][lane] (fp64) during a flush
     l.norm = take(sizeof(double) * cp);
@@ -262,10 +277,10 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
     const int q4 = lane >> 4, cl16 = lane & 15;
     const int nks = (k + 3) / 4;
     for (int g0 = 0; g0 < cp; g0 += RG) {
-        {   // one A fragment entry per thread: k-group tid/64, lane tid%64
-            const int kk = 4 * wave + q4;
-            const int arow = g0 + 4 * (cl16 & 3) + (cl16 >> 2);
-            coefa[tid] = (kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
+        for (int e = tid; e < AFRAG; e += LT) {   // A fragment entry e: k-group e/64, lane e%64
+            const int l = e & 63, kk = 4 * (e >> 6) + (l >> 4);
+            const int arow = g0 + 4 * (l & 3) + ((l & 15) >> 2);
+            coefa[e] = (kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
         }
         __syncthreads();
         // a wavefront works on NTI adjacent 16-column tiles at a time, so that 4 * NTI loads of
@@ -337,7 +352,14 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     const int m = S.m, d = S.d, cpb = S.cpb, cp = S.cp;
     const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb);
     double *uloc = reinterpret_cast<double *>(smem + L.uloc);
+    double *uprev = reinterpret_cast<double *>(smem + L.uprev);
+    double *coefbg = reinterpret_cast<double *>(smem + L.coefbg);
+    double *bgacc = reinterpret_cast<double *>(smem + L.bgacc);
+    int *bgpart = reinterpret_cast<int *>(smem + L.bgpart);
     double *cvec = reinterpret_cast<double *>(smem + L.cvec);
+    double *cprev = reinterpret_cast<double *>(smem + L.cprev);
+    double *pivprev = reinterpret_cast<double *>(smem + L.pivprev);
+    int *seq_done = reinterpret_cast<int *>(smem + L.seq_done);
     double *pivs = reinterpret_cast<double *>(smem + L.pivs);
     float *wcol = reinterpret_cast<float *>(smem + L.wcol);
     double *coefa = reinterpret_cast<double *>(smem + L.wcol);
@@ -350,7 +372,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
     double *red_s = reinterpret_cast<double *>(smem + L.red_s);
     int *red_i = reinterpret_cast<int *>(smem + L.red_i);
-    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen
+    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet
     double *misc_d = reinterpret_cast<double *>(smem + L.misc + 32);  // [1] pivot, [2] 1 / pivot
 
     const int j0 = b * cpb;
@@ -406,6 +428,50 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     bool ok = true;
     int error_step = 0;
     unsigned tag4 = 0;
+    // background flush of the previous block of pending rows
+    const bool bg_enabled = (cp == RG) && (nb <= 64 * NPOLL);
+    const int ntiles = (d + 15) / 16;
+    const int q4 = lane >> 4, cl16 = lane & 15;
+    bool bg_active = false;
+    const double *Uprev = S.U;
+    // one unit: BG_KS k-groups of one 16-column tile; tiles of wavefront w: (w - NPOLL) + NBG * seq.
+    // Progress (seq, part) is passed in and out by the caller, identically in every lane; between steps it
+    // lives in LDS (seq_done, bgpart), like the partial accumulators.
+    auto bg_unit = [&](int &seq, int &part) {
+        const int ct = (wave - NPOLL) + NBG * seq;
+        if (ct >= ntiles) return false;
+        const int c = ct * 16 + cl16;
+        const bool col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
+        const double *ub = Uprev + (size_t)q4 * d + c;
+        double *accp = bgacc + (size_t)(wave - NPOLL) * 256 + lane;
+        // the accumulator starts as the panel tile and the A fragments are negated, so the last unit of a
+        // tile ends with a plain store instead of a dependent read-modify-write
+        doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c * cp + 4 * q4);
+        doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+        if (part > 0) {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) acc[v] = accp[64 * v];
+        } else if (col_ok) {
+            acc = *dst;
+        }
+        double bv[BG_KS];
+#pragma unroll
+        for (int e = 0; e < BG_KS; ++e) bv[e] = col_ok ? ub[(size_t)(part * BG_KS + e) * 4 * d] : 0.0;
+#pragma unroll
+        for (int e = 0; e < BG_KS; ++e)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(coefbg[(part * BG_KS + e) * 64 + lane], bv[e], acc, 0, 0, 0);
+        if (part == BMAX / 4 / BG_KS - 1) {
+            if (col_ok) *dst = acc;
+            ++seq;
+            part = 0;
+        } else {
+#pragma unroll
+            for (int v = 0; v < 4; ++v) accp[64 * v] = acc[v];
+            ++part;
+        }
+        return true;
+    };
+
     double tau = 1.0e300;   // publish the payload ahead of the exchange only if my best score is <= tau
 
     for (; t <= S.n_remove; ++t) {
@@ -473,6 +539,12 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 ll_store(pw + m + 2 * BMAX, dhi(dv), tag);
                 ll_store(pw + m + 2 * BMAX + 1, dlo(dv), tag);
             }
+            if (bg_active && tid >= LT - 3 * BMAX && tid < LT - 2 * BMAX) {   // entries of the previous block's rows
+                const int kk = tid - (LT - 3 * BMAX);
+                const double u = uprev[cl * BMAX + kk];
+                ll_store(pw + m + 2 * BMAX + 2 + 2 * kk, dhi(u), tag);
+                ll_store(pw + m + 2 * BMAX + 2 + 2 * kk + 1, dlo(u), tag);
+            }
         };
         if (published) publish_payload(cand);
         TICK(1);
@@ -493,6 +565,11 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
 #endif
                 if (iv == IDX_ERROR) { err = true; continue; }
                 if (better(sv, iv, s, idx)) { s = sv; idx = iv; }
+            }
+            if (bg_active && wave >= NPOLL) {
+                int seq = seq_done[wave], part = bgpart[wave];     // written before the previous barrier
+                bg_unit(seq, part);
+                if (lane == 0) { seq_done[wave] = seq; bgpart[wave] = part; }
             }
             const int nwaves_used = min(NW, (nb + 63) / 64);
             if (wave < nwaves_used) {
@@ -528,6 +605,16 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             bool fail = false;
             // column p of the stored matrix restricted to my rows (= my slice of row p, by symmetry)
             if (tid < cp) hstale[tid] = P[(size_t)p * cp + tid];
+            if (tid == 0) {
+                const int ct = p >> 4;
+                misc[4] = (bg_active && (ct / NBG) >= seq_done[NPOLL + ct % NBG]) ? 1 : 0;
+            }
+            if (bg_active && tid >= LT - 3 * BMAX && tid < LT - 2 * BMAX) {
+                const int kk = tid - (LT - 3 * BMAX);
+                unsigned hi, lo;
+                if (!ll_wait2(pw + m + 2 * BMAX + 2 + 2 * kk, tag, hi, lo, S.status)) fail = true;
+                else cprev[kk] = dmake(hi, lo) / pivprev[kk];
+            }
             for (int i = tid; i < m; i += LT) {
                 unsigned v;
                 if (!ll_wait(pw + i, tag, v, S.status)) { fail = true; break; }
@@ -550,6 +637,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         TICK(3);
         if (misc[0]) { ok = false; break; }
         const double piv = misc_d[1], rpiv = misc_d[2];
+        const bool unflushed = misc[4] != 0;
         if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = cand_score; }   // exact score: the winner is my candidate
         if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; }
 
@@ -561,7 +649,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 if (lane == 0) alive_own[jl] = 0;
                 continue;
             }
-            const double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
+            double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
+            if (unflushed) term += cprev[lane] * uprev[jl * BMAX + lane];
             const double u = hstale[jl] - wave_sum(term);
             const double f = u * rpiv;
             double s = 0.0;
@@ -597,6 +686,16 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
 
         // ---------------------------------------------------------- 5. flush the pending downdates
         if (k == BMAX || t + 1 == S.n_remove) {
+            // whatever is left of the previous block's background flush is finished first
+            if (bg_active) {
+                if (wave >= NPOLL) {
+                    int seq = seq_done[wave], part = bgpart[wave];
+                    // at most (BMAX / 4 / BG_KS) units per tile remain: the bound only guards against a stuck loop
+                    for (int guard = 0; guard < (BMAX / 4 / BG_KS) * (ntiles / NBG + 1) && bg_unit(seq, part); ++guard) {}
+                }
+                __syncthreads();
+                bg_active = false;
+            }
             // all slices of the pending rows must be in memory before anyone reads them
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
@@ -617,7 +716,22 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             TICK(5);
             if (misc[0]) { ok = false; break; }
 
-            flush_panel(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits, k, d, cp);
+            if (bg_enabled && k == BMAX && t + 1 < S.n_remove) {
+                // hand this block to the background: keep its owned slices, pivots and A fragments
+                for (int e = tid; e < BMAX * cp; e += LT) uprev[e] = uloc[e];
+                if (tid < BMAX) pivprev[tid] = pivs[tid];
+                for (int e = tid; e < AFRAG; e += LT) {
+                    const int l = e & 63, kk = 4 * (e >> 6) + (l >> 4);
+                    const int arow = 4 * (l & 3) + ((l & 15) >> 2);
+                    coefbg[e] = alive_own[arow] ? -(uloc[arow * BMAX + kk] / pivs[kk]) : 0.0;
+                }
+                if (tid < NW) { seq_done[tid] = 0; bgpart[tid] = 0; }
+                Uprev = S.U + (size_t)ublk * BMAX * d;
+                bg_active = true;
+                __syncthreads();
+            } else {
+                flush_panel(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits, k, d, cp);
+            }
             k = 0;
             ublk ^= 1;
             TICK(6);
@@ -657,7 +771,7 @@ static Plan make_plan(int d_row, int d_col) {
     p.cpb = (d_col + cus - 1) / cus;
     p.cp = (p.cpb + RG - 1) / RG * RG;
     p.nb = (d_col + p.cpb - 1) / p.cpb;
-    p.pay_words = d_row + 2 * BMAX + 2;
+    p.pay_words = d_row + 4 * BMAX + 2;
     const size_t lds_cap = 158 * 1024;
     p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb).total <= lds_cap ? 1 : 0;
     p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb).total;
