@@ -48,6 +48,7 @@ int device_cu_count();
 namespace lazy {
 
 typedef double doublex4 __attribute__((ext_vector_type(4)));
+constexpr unsigned long long KEY_EMPTY_ = ~0ull;
 
 constexpr int LT = 1024;                 // threads per workgroup (16 wavefronts)
 constexpr int NW = LT / 64;
@@ -62,6 +63,7 @@ constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 M
 constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
 constexpr int MAX_CPB = 250;             // the local column index travels in 8 bits
+constexpr int MAX_D = 65535;             // the global column index travels in 16 bits of the comparison key
 
 struct State {
     // caller's buffers
@@ -148,16 +150,27 @@ __device__ __forceinline__ void slot_store(unsigned long long *p, double score, 
     __hip_atomic_store(p, (b & ~0xfffull) | ((unsigned long long)enc_idx << 4) | tag4, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
-// Waits for slot `sb`; idx becomes the global column (cpb * sb + local index), IDX_NONE or IDX_ERROR.
-__device__ __forceinline__ bool slot_wait(const unsigned long long *p, unsigned tag4, int sb, int cpb, double &score,
-                                          int &idx, int *status) {
+// The same word without the tag, as kept in LDS for the workgroup's own columns: the smallest key is the
+// best candidate (lower local index on equal truncated scores).
+__device__ __forceinline__ unsigned long long cand_key_of(double score, unsigned enc_idx) {
+    return ((unsigned long long)__double_as_longlong(score) & ~0xfffull) | ((unsigned long long)enc_idx << 4);
+}
+constexpr unsigned long long KEY_NONE = ~0ull & ~0xfull;     // index field reads ENC_NONE
+
+// Waits for slot `sb` and turns it into a comparison key [score bits 63..16 | global column : 16]: the
+// smallest key over all slots is the step's pivot (scores closer than 2^-36 relative count as tied and go
+// to the lower column).  KEY_EMPTY for a workgroup without live columns; *err is set if it reported a
+// non-positive diagonal entry.
+constexpr unsigned long long KEY_EMPTY = ~0ull;
+__device__ __forceinline__ bool slot_wait(const unsigned long long *p, unsigned tag4, int sb, int cpb,
+                                          unsigned long long &key, bool &err, int *status) {
     Waiter w;
     for (;;) {
         const unsigned long long v = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if ((unsigned)(v & 0xfu) == tag4) {
-            score = __longlong_as_double((long long)(v & ~0xfffull));
             const unsigned e = (unsigned)((v >> 4) & 0xffu);
-            idx = (e == ENC_NONE) ? IDX_NONE : (e == ENC_ERROR) ? IDX_ERROR : sb * cpb + (int)e;
+            if (e == ENC_ERROR) err = true;
+            key = (e >= ENC_ERROR) ? KEY_EMPTY : ((v & ~0xffffull) | (unsigned long long)(sb * cpb + (int)e));
             return true;
         }
         if (!w.again(status)) return false;
@@ -191,45 +204,32 @@ __device__ __forceinline__ double wave_sum(double v) {
     return (readlane_d(v, 0) + readlane_d(v, 16)) + (readlane_d(v, 32) + readlane_d(v, 48));
 }
 
-// strict order: smaller score first, lower index on equal scores; negative index = "none"
-__device__ __forceinline__ bool better(double s1, int i1, double s2, int i2) {
-    if (i2 < 0) return i1 >= 0;
-    if (i1 < 0) return false;
-    return (s1 < s2) || (s1 == s2 && i1 < i2);
-}
 template <int CTRL>
-__device__ __forceinline__ void argmin_step(double &s, int &i) {
-    const double so = dpp_d<CTRL>(s);
-    const int io = dpp_i<CTRL>(i);
-    if (better(so, io, s, i)) { s = so; i = io; }
+__device__ __forceinline__ unsigned long long dpp_u64(unsigned long long v) {
+    return ((unsigned long long)(unsigned)dpp_i<CTRL>((int)(v >> 32)) << 32) | (unsigned)dpp_i<CTRL>((int)(v & 0xffffffffu));
 }
-// Argmin within each 16-lane row, result in every lane of the row.
-__device__ __forceinline__ void row_argmin(double &s, int &i) {
-    argmin_step<DPP_XOR1>(s, i);
-    argmin_step<DPP_XOR2>(s, i);
-    argmin_step<DPP_HALF_MIRROR>(s, i);
-    argmin_step<DPP_MIRROR>(s, i);
-}
-// Argmin over the 64 lanes, result in every lane.
-__device__ __forceinline__ void wave_argmin(double &s, int &i) {
-    row_argmin(s, i);
-    double bs = readlane_d(s, 0);
-    int bi = __builtin_amdgcn_readlane(i, 0);
+__device__ __forceinline__ unsigned long long umin64(unsigned long long a, unsigned long long b) { return a < b ? a : b; }
+// Minimum of a 64-bit key over the 64 lanes, returned in every lane.
+__device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v) {
+    v = umin64(v, dpp_u64<DPP_XOR1>(v));
+    v = umin64(v, dpp_u64<DPP_XOR2>(v));
+    v = umin64(v, dpp_u64<DPP_HALF_MIRROR>(v));
+    v = umin64(v, dpp_u64<DPP_MIRROR>(v));
+    unsigned long long r = KEY_EMPTY_;
 #pragma unroll
-    for (int r = 1; r < 4; ++r) {
-        const double so = readlane_d(s, 16 * r);
-        const int io = __builtin_amdgcn_readlane(i, 16 * r);
-        if (better(so, io, bs, bi)) { bs = so; bi = io; }
+    for (int q = 0; q < 4; ++q) {
+        const unsigned long long x = ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(v >> 32), 16 * q) << 32) |
+                                     (unsigned)__builtin_amdgcn_readlane((int)(v & 0xffffffffu), 16 * q);
+        r = umin64(r, x);
     }
-    s = bs;
-    i = bi;
+    return r;
 }
 
 // ------------------------------------------------------------------------------------------------
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, uprev, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, red_i, misc, wt, total;
+    size_t uloc, uprev, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, misc, wt, total;
 };
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
     Lds l;
@@ -255,8 +255,7 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.alive_own = take(sizeof(int) * cp);
     l.alive_bits = take(sizeof(unsigned) * ((d + 31) / 32));
     l.snap_bits = take(sizeof(unsigned) * ((d + 32) / 32 + 1));
-    l.red_s = take(sizeof(double) * NW);
-    l.red_i = take(sizeof(int) * NW);
+    l.red_s = take(sizeof(unsigned long long) * NW);     // per-wavefront minima of the candidate keys
     l.misc = take(96);
     l.wt = take(w_in_lds ? sizeof(float) * (size_t)cpb * m : 0);
     l.total = o;
@@ -370,9 +369,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     int *alive_own = reinterpret_cast<int *>(smem + L.alive_own);
     unsigned *alive_bits = reinterpret_cast<unsigned *>(smem + L.alive_bits);
     unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
-    double *red_s = reinterpret_cast<double *>(smem + L.red_s);
-    int *red_i = reinterpret_cast<int *>(smem + L.red_i);
+    unsigned long long *red_key = reinterpret_cast<unsigned long long *>(smem + L.red_s);
     int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet
+    unsigned long long *cand_key = reinterpret_cast<unsigned long long *>(smem + L.misc + 64);   // best owned column
     double *misc_d = reinterpret_cast<double *>(smem + L.misc + 32);  // [1] pivot, [2] 1 / pivot
 
     const int j0 = b * cpb;
@@ -391,7 +390,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         }
         alive_bits[w] = bits;
     }
-    if (tid == 0) { misc[0] = 0; misc[2] = 0; }
+    if (tid == 0) { misc[0] = 0; misc[2] = 0; *cand_key = KEY_NONE; }
     for (int w = tid; w < (d + 32) / 32 + 1; w += LT) snap_bits[w] = 0;
     for (int r = tid; r < cp; r += LT) { alive_own[r] = 0; norm[r] = 0.0; diag[r] = 1.0; score[r] = 0.0; hstale[r] = 0.0; }
     for (int e = tid; e < BMAX * cp; e += LT) uloc[e] = 0.0;
@@ -413,10 +412,12 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         s = wave_sum(s);
         if (lane == 0) {
             const double dj = (double)S.Hinv[(size_t)j * d + j];
+            const int alive = S.alive_in ? (S.alive_in[j] != 0) : 1;
             norm[jl] = s;
             diag[jl] = dj;
-            alive_own[jl] = S.alive_in ? (S.alive_in[j] != 0) : 1;
+            alive_own[jl] = alive;
             score[jl] = s / dj;
+            if (alive) atomicMin(cand_key, (dj > 0.0) ? cand_key_of(s / dj, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
         }
     }
     __syncthreads();
@@ -473,10 +474,11 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     };
 
     double tau = 1.0e300;   // publish the payload ahead of the exchange only if my best score is <= tau
+    const unsigned long long cpb_magic = (0x100000000ull + (unsigned)cpb - 1) / (unsigned)cpb;
 
     for (; t <= S.n_remove; ++t) {
         // -------------------------------------------------------------- snapshots after t removals
-        for (int q = 0; ((snap_bits[t >> 5] >> (t & 31)) & 1u) && q < S.n_snap; ++q) {
+        for (int q = 0; S.n_snap > 0 && ((snap_bits[t >> 5] >> (t & 31)) & 1u) && q < S.n_snap; ++q) {
             if (S.snap_steps[q] != t) continue;      // uniform
             float *dst = S.W_snap + (size_t)q * m * d;
             for (int jl = wave; jl < nown; jl += NW) {
@@ -492,38 +494,22 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         TICK(0);
 
         // ---------------------------------------------------------- 1. local candidate + publish
-        // every wavefront evaluates the (few) owned columns itself: no broadcast, no barrier
-        int cand;
-        double cand_score;
-        {
-            double bs = 0.0;
-            int bi = IDX_NONE;
-            bool bad = false;
-            for (int jl = lane; jl < nown; jl += 64) {
-                if (!alive_own[jl]) continue;
-                if (!(diag[jl] > 0.0)) { bad = true; continue; }
-                if (better(score[jl], j0 + jl, bs, bi)) { bs = score[jl]; bi = j0 + jl; }
-            }
-            if (cpb <= 16) row_argmin(bs, bi);      // all candidates sit in lanes 0..15
-            else wave_argmin(bs, bi);
-            bi = __builtin_amdgcn_readfirstlane(bi);
-            bs = readlane_d(bs, 0);
-            if (__any(bad)) bi = IDX_ERROR;
-            cand = bi;
-            cand_score = bs;
-            if (tid == 0) {
-                slot_store(S.slots + (size_t)par * nb + b, bs,
-                           bi == IDX_NONE ? ENC_NONE : bi == IDX_ERROR ? ENC_ERROR : (unsigned)(bi - j0), tag4);
+        // the owned columns' wavefronts have reduced their (score, index) keys into one LDS word
+        const unsigned long long key = *cand_key;
+        const unsigned key_idx = (unsigned)((key >> 4) & 0xffu);
+        const int cand = (key_idx == ENC_NONE) ? IDX_NONE : (key_idx == ENC_ERROR) ? IDX_ERROR : j0 + (int)key_idx;
+        const double cand_score_trunc = __longlong_as_double((long long)(key & ~0xfffull));
+        if (tid == 0) {
+            __hip_atomic_store(S.slots + (size_t)par * nb + b, key | tag4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #ifdef ZIPLM_LAZY_TIMING
-                tlocal += wall_clock64() - texch;
+            tlocal += wall_clock64() - texch;
 #endif
-            }
         }
         // The payload travels ahead of the exchange only from workgroups that are likely to win (score
         // within the range of the previous step's leaders); any other winner publishes after the
         // exchange.  Readers wait on the tags either way, so this is a matter of traffic, not of
         // correctness.
-        const bool published = (cand >= 0) && (cand_score <= tau);
+        const bool published = (cand >= 0) && (cand_score_trunc <= tau);
         auto publish_payload = [&](int col) {
             const int cl = col - j0;
             unsigned long long *pw = S.pay + ((size_t)par * nb + b) * S.pay_words;
@@ -551,20 +537,16 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
 
         // ---------------------------------------------------------- 2. all candidates -> argmin
         int p;
-        double best;
         {
-            double s = 0.0;
-            int idx = IDX_NONE;
+            unsigned long long mykey = KEY_EMPTY;
             bool fail = false, err = false;
             for (int sb = tid; sb < nb; sb += LT) {
-                double sv;
-                int iv;
-                if (!slot_wait(S.slots + (size_t)par * nb + sb, tag4, sb, cpb, sv, iv, S.status)) { fail = true; break; }
+                unsigned long long kv;
+                if (!slot_wait(S.slots + (size_t)par * nb + sb, tag4, sb, cpb, kv, err, S.status)) { fail = true; break; }
 #ifdef ZIPLM_LAZY_TIMING
                 if (b == 0 && tid == 0) tacc[7] += wall_clock64() - tlast;     // own slot seen again: store -> load round trip
 #endif
-                if (iv == IDX_ERROR) { err = true; continue; }
-                if (better(sv, iv, s, idx)) { s = sv; idx = iv; }
+                mykey = umin64(mykey, kv);
             }
             if (bg_active && wave >= NPOLL) {
                 int seq = seq_done[wave], part = bgpart[wave];     // written before the previous barrier
@@ -573,22 +555,22 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             }
             const int nwaves_used = min(NW, (nb + 63) / 64);
             if (wave < nwaves_used) {
-                wave_argmin(s, idx);
-                if (lane == 0) { red_s[wave] = s; red_i[wave] = idx; }
+                mykey = wave_min_u64(mykey);
+                if (lane == 0) red_key[wave] = mykey;
             }
             if (fail) misc[0] = 1;
             if (err) misc[2] = 1;
             __syncthreads();
-            best = red_s[0];
-            p = red_i[0];
-            double worst = (red_i[0] >= 0) ? red_s[0] : 0.0;
+            unsigned long long kmin = red_key[0], kmax = (red_key[0] == KEY_EMPTY) ? 0ull : red_key[0];
             for (int w = 1; w < nwaves_used; ++w) {
-                if (better(red_s[w], red_i[w], best, p)) { best = red_s[w]; p = red_i[w]; }
-                if (red_i[w] >= 0 && red_s[w] > worst) worst = red_s[w];
+                const unsigned long long kw = red_key[w];
+                kmin = umin64(kmin, kw);
+                if (kw != KEY_EMPTY && kw > kmax) kmax = kw;
             }
+            p = (kmin == KEY_EMPTY) ? IDX_NONE : (int)(kmin & 0xffffu);
             // next step's publication threshold: the largest of the per-wavefront minima (each over 64
             // workgroups); with a single wavefront of candidates everybody keeps publishing
-            tau = (nwaves_used >= 2) ? worst : 1.0e300;
+            tau = (nwaves_used >= 2) ? __longlong_as_double((long long)(kmax | 0xffffull)) : 1.0e300;
         }
         TICK(2);
 #ifdef ZIPLM_LAZY_TIMING
@@ -596,7 +578,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
 #endif
         if (misc[0]) { ok = false; break; }
         if (misc[2] || p < 0) { error_step = 1 + t; break; }   // same inputs in every workgroup: uniform
-        const int owner = p / cpb;
+        const int owner = (int)(((unsigned long long)(unsigned)p * cpb_magic) >> 32);      // p / cpb
+        if (tid == 0) *cand_key = KEY_NONE;       // every thread read it before the barrier of the exchange
         if (owner == b && !published) publish_payload(p);
 
         // ---------------------------------------------------------- 3. winner's payload + stale column p
@@ -638,7 +621,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         if (misc[0]) { ok = false; break; }
         const double piv = misc_d[1], rpiv = misc_d[2];
         const bool unflushed = misc[4] != 0;
-        if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = cand_score; }   // exact score: the winner is my candidate
+        if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = score[p - j0]; }   // exact score, not the truncated one
         if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; }
 
         // ---------------------------------------------------------- 4. own slice of the pivot row, Eq. 3
@@ -653,6 +636,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             if (unflushed) term += cprev[lane] * uprev[jl * BMAX + lane];
             const double u = hstale[jl] - wave_sum(term);
             const double f = u * rpiv;
+            const float nf = -(float)f;
             double s = 0.0;
             for (int i0 = 0; i0 < m; i0 += 256) {
                 float w[4], c[4];
@@ -665,7 +649,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int i = i0 + lane + 64 * e;
-                    const float v = (float)((double)w[e] - (double)c[e] * f);
+                    const float v = __builtin_fmaf(c[e], nf, w[e]);       // Eq. 3 on the fp32 state, one rounding
                     if (i < m) WT(jl, i) = v;
                     s += (double)v * (double)v;
                 }
@@ -675,9 +659,11 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 uloc[jl * BMAX + k] = u;
                 __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const double dj = diag[jl] - u * f;
+                const double sc = s / dj;
                 diag[jl] = dj;
                 norm[jl] = s;
-                score[jl] = s / dj;
+                score[jl] = sc;
+                atomicMin(cand_key, (dj > 0.0) ? cand_key_of(sc, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
             }
         }
         ++k;
@@ -775,7 +761,7 @@ static Plan make_plan(int d_row, int d_col) {
     const size_t lds_cap = 158 * 1024;
     p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb).total <= lds_cap ? 1 : 0;
     p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb).total;
-    p.feasible = p.lds_bytes <= lds_cap && p.cpb <= MAX_CPB;
+    p.feasible = p.lds_bytes <= lds_cap && p.cpb <= MAX_CPB && d_col <= MAX_D;
     return p;
 }
 
