@@ -69,7 +69,7 @@ static int run_hessian(const gemm::Args &base, const HessianPlan &plan, hipStrea
                        dim3(gemm::THREADS), 0, stream, g);
     ZIPLM_HIP_TRY(hipGetLastError());
     g.flags &= ~gemm::F_PARTIAL;
-    hipLaunchKernelGGL(gemm::splitk_reduce_kernel, dim3(plan.tiles), dim3(gemm::THREADS), 0, stream, g,
+    hipLaunchKernelGGL(gemm::splitk_reduce_kernel, dim3(plan.tiles, 4), dim3(gemm::THREADS), 0, stream, g,
                        plan.nsplit, plan.tiles);
     ZIPLM_HIP_TRY(hipGetLastError());
     return ZIPLM_OK;

@@ -4,10 +4,10 @@
 //   A  = H + lambda I, embedded in a dp x dp matrix (dp = d_col rounded up to 128) whose padding is
 //        the identity, so that every internal product runs on whole tiles;
 //   A  = L L^T     right-looking blocked Cholesky, 64-column panels:
-//                  diagonal block factored and inverted in the registers of one wavefront,
-//                  panel  L21 = A21 inv(L11)^T  and trailing update  A22 -= L21 L21^T  on the
-//                  fp32 matrix cores;
-//   T  = L^-1      bottom-up pairwise merges  T21 = -T22 (L21 T11), all pairs of a level in one
+//                  diagonal block factored in the registers of one wavefront, panel
+//                  L21 = A21 L11^-T by substitution (one thread per row), trailing update
+//                  A22 -= L21 L21^T on the fp32 matrix cores;
+//   T  = L^-1      diagonal blocks inverted in one batched launch, then bottom-up pairwise merges  T21 = -T22 (L21 T11), all pairs of a level in one
 //                  batched launch;
 //   Hinv = T^T T   lower tiles computed, mirrored to the upper triangle.
 #include "common.h"
@@ -49,53 +49,114 @@ __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ H,
     }
 }
 
-// Factor the 64 x 64 diagonal block at (k0, k0) of A in place (lower triangle) and store the
-// inverse of the factor, a dense 64 x 64 lower-triangular matrix, in dinv.
-// One wavefront, everything in registers: lane i holds row i of the block (64 VGPRs) and, for the
-// inverse, lane c holds column c of T = L^-1.  An entry another lane needs is always "register j
-// of lane c" with both known at compile time after full unrolling, i.e. one v_readlane.
-//   factorisation, right-looking:  L[i][j] = A[i][j] / l_jj ;  A[i][c] -= L[i][j] L[c][j]  (j < c <= i)
-//   inverse, forward substitution: T[i][c] = (delta_ic - sum_{k<i} L[i][k] T[k][c]) / L[i][i]
-// A non-positive pivot records 1 + its global column in *info (first one wins) and is replaced by 1
-// so that the remaining arithmetic stays finite.
+// Factor the 64 x 64 diagonal block at (k0, k0) of A in place (lower triangle), one wavefront, the
+// block in registers: lane i holds row i (64 VGPRs).  Right-looking:
+//     l_jj = sqrt(a_jj);  L[i][j] = A[i][j] / l_jj;  A[i][c] -= L[i][j] L[c][j]   (j < c <= i).
+// "Entry j of row c" is register j of lane c, both known at compile time after full unrolling: one
+// v_readlane.  A non-positive pivot records 1 + its global column in *info (first one wins) and is
+// replaced by 1 so that the remaining arithmetic stays finite.
 __device__ __forceinline__ float lane_bcast(float v, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-__global__ __launch_bounds__(64) void potrf_diag_kernel(float *__restrict__ A, int ld, int k0,
-                                                        float *__restrict__ dinv, int *__restrict__ info) {
+__global__ __launch_bounds__(64) void potrf_diag_kernel(float *__restrict__ A, int ld, int k0, int *__restrict__ info) {
     const int lane = threadIdx.x;
     float *Ab = A + (int64_t)k0 * ld + k0;
     float a[NB];
 #pragma unroll
-    for (int c = 0; c < NB; ++c) a[c] = Ab[(int64_t)lane * ld + c];   // upper entries are never used
-    float rdiag[NB];                                                  // 1 / l_jj, uniform
+    for (int c = 0; c < NB; c += 4) {
+        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
+        a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];        // upper entries are never used
+    }
+    int first_bad = -1;                                   // branch-free bookkeeping: one straight-line block
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
         float piv = lane_bcast(a[j], j);
-        if (!(piv > 0.f)) {                  // uniform
-            if (lane == 0 && *info == 0) *info = 1 + k0 + j;
-            piv = 1.f;
-        }
-        const float ljj = sqrtf(piv);
-        const float r = 1.0f / ljj;
-        rdiag[j] = r;
-        a[j] = (lane == j) ? ljj : a[j] * r;              // column j of L (rows above j: unused)
+        const bool bad = !(piv > 0.f);                    // uniform
+        first_bad = (bad && first_bad < 0) ? j : first_bad;
+        piv = bad ? 1.f : piv;
+        const float r = __builtin_amdgcn_rsqf(piv);       // 1 ulp reciprocal square root
+        a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
 #pragma unroll
-        for (int c = j + 1; c < NB; ++c) a[c] -= a[j] * lane_bcast(a[j], c);
+        for (int c = j + 1; c < NB; ++c) {
+            a[c] -= a[j] * lane_bcast(a[j], c);
+            // bound how many broadcast values (scalar registers) are alive at once
+            if ((c & 15) == 15) __builtin_amdgcn_sched_barrier(0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
-    // T = L^-1, lane = column
+#pragma unroll
+    for (int c = 0; c < NB; ++c)
+        if (c <= lane) Ab[(int64_t)lane * ld + c] = a[c];
+    if (first_bad >= 0 && lane == 0 && *info == 0) *info = 1 + k0 + first_bad;
+}
+
+// Panel below a factored diagonal block:  X L11^T = A21, solved row by row in place.  One thread per
+// row of A21 (its 64 entries in registers), L11 in LDS (row j read with 128-bit broadcast reads):
+//     x_j = (a_j - sum_{k<j} x_k L11[j][k]) / L11[j][j].
+__global__ __launch_bounds__(256) void trsm_panel_kernel(float *__restrict__ A, int ld, int k0, int rows) {
+    __shared__ __attribute__((aligned(16))) float L[NB][NB];
+    __shared__ float rdiag[NB];
+    const int tid = threadIdx.x;
+    const float *Lb = A + (int64_t)k0 * ld + k0;
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int i = e / NB, j = e % NB;
+        L[i][j] = (j <= i) ? Lb[(int64_t)i * ld + j] : 0.f;
+    }
+    __syncthreads();
+    if (tid < NB) rdiag[tid] = 1.0f / L[tid][tid];
+    __syncthreads();
+    const int row = blockIdx.x * 256 + tid;
+    if (row >= rows) return;
+    float *xr = A + (int64_t)(k0 + NB + row) * ld + k0;
+    float x[NB];
+#pragma unroll
+    for (int c = 0; c < NB; c += 4) {
+        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(xr + c);
+        x[c] = v[0]; x[c + 1] = v[1]; x[c + 2] = v[2]; x[c + 3] = v[3];
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        float s = x[j];
+#pragma unroll
+        for (int k4 = 0; k4 < (j + 3) / 4; ++k4) {
+            const gemm::floatx4 l = *reinterpret_cast<const gemm::floatx4 *>(&L[j][4 * k4]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (4 * k4 + e < j) s -= x[4 * k4 + e] * l[e];
+        }
+        x[j] = s * rdiag[j];
+    }
+#pragma unroll
+    for (int c = 0; c < NB; c += 4) {
+        gemm::floatx4 v = {x[c], x[c + 1], x[c + 2], x[c + 3]};
+        *reinterpret_cast<gemm::floatx4 *>(xr + c) = v;
+    }
+}
+
+// Inverses of all factored 64 x 64 diagonal blocks at once (off the factorisation's critical path):
+// one wavefront per block, lane i holds row i of L, lane c builds column c of T = L^-1 by forward
+// substitution, T[i][c] = (delta_ic - sum_{k<i} L[i][k] T[k][c]) / L[i][i]; "entry k of row i" is
+// register k of lane i, one v_readlane.
+__global__ __launch_bounds__(64) void trtri_diag_kernel(const float *__restrict__ A, int ld, float *__restrict__ dinv_all) {
+    const int lane = threadIdx.x;
+    const int k0 = blockIdx.x * NB;
+    const float *Ab = A + (int64_t)k0 * ld + k0;
+    float *dinv = dinv_all + (size_t)blockIdx.x * NB * NB;
+    float a[NB];
+#pragma unroll
+    for (int c = 0; c < NB; c += 4) {
+        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
+        a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];
+    }
     float t[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         float s = (lane == i) ? 1.f : 0.f;
 #pragma unroll
         for (int k = 0; k < i; ++k) s -= lane_bcast(a[k], i) * t[k];
-        t[i] = s * rdiag[i];
+        t[i] = s / lane_bcast(a[i], i);
     }
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-        if (c <= lane) Ab[(int64_t)lane * ld + c] = a[c];
 #pragma unroll
     for (int i = 0; i < NB; ++i) dinv[i * NB + lane] = t[i];          // t[i] = T[i][lane], zero above the diagonal
 }
@@ -159,20 +220,12 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
 
     // ---- A = L L^T, right-looking over 64-column panels --------------------------------------
     for (int k0 = 0; k0 < dp; k0 += NB) {
-        float *dinv = l.dinv + (size_t)(k0 / NB) * NB * NB;
-        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(64), 0, st, l.A, dp, k0, dinv, l.info);
+        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(64), 0, st, l.A, dp, k0, l.info);
         const int rest = dp - k0 - NB;
         if (rest <= 0) break;
         float *A21 = l.A + (int64_t)(k0 + NB) * dp + k0;
-        Args p = {};
-        // L21 = A21 inv(L11)^T, in place: the single tile column covers all 64 columns of the panel
-        // and a workgroup reads only the rows it later writes, all of them before its epilogue.
-        p.A = A21; p.lda = dp;
-        p.B = dinv; p.ldb = NB;
-        p.C = A21; p.ldc = dp;
-        p.M = rest; p.N = NB; p.K = NB;
-        p.alpha = 1.f; p.beta = 0.f; p.flags = 0;
-        ZIPLM_HIP_TRY((launch<K_CONTIG, K_CONTIG, true, false>(p, 1, st)));
+        // L21 = A21 inv(L11)^T by substitution, in place
+        hipLaunchKernelGGL(trsm_panel_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, l.A, dp, k0, rest);
         // A22 -= L21 L21^T, lower tiles only
         Args u = {};
         u.A = A21; u.lda = dp;
@@ -183,7 +236,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         ZIPLM_HIP_TRY((launch<K_CONTIG, K_CONTIG, true, false>(u, 1, st)));
     }
 
-    // ---- T = L^-1: leaves, then pairwise merges -------------------------------------------------
+    // ---- T = L^-1: leaves (all diagonal blocks in one launch), then pairwise merges -------------------
+    hipLaunchKernelGGL(trtri_diag_kernel, dim3(dp / NB), dim3(64), 0, st, l.A, dp, l.dinv);
     hipLaunchKernelGGL(place_diag_kernel, dim3(fill_blocks), dim3(256), 0, st, l.T, dp, l.dinv);
     ZIPLM_HIP_TRY(hipGetLastError());
     for (int s = NB; s < dp; s *= 2) {

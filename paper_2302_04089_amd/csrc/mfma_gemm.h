@@ -181,6 +181,7 @@ __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn) {
 }
 
 // Epilogue for one accumulator set: C = alpha * acc + beta * C, optional mirrored copy.
+template <int V0 = 0, int V1 = 16>
 __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__restrict__ C, int64_t ldc,
                                          int M, int N, int tm, int tn, float alpha, float beta,
                                          bool mirror, int wm, int wn, int lane) {
@@ -191,7 +192,7 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
         for (int j = 0; j < 2; ++j) {
             const int col = tn * BN + wn * 64 + j * 32 + r;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
+            for (int v = V0; v < V1; ++v) {
                 const int row = tm * BM + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
                 if (row < M && col < N) {
                     float *p = C + (int64_t)row * ldc + col;
@@ -293,12 +294,15 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
 }
 
 // Second pass of a split-K product: sums the raw accumulators of all splits in split order and
-// applies the epilogue.  Same thread <-> element mapping as gemm_kernel.
+// applies the epilogue.  Same thread <-> element mapping as gemm_kernel; blockIdx.y selects one of the
+// four groups of four accumulator registers (rows 8q..8q+7 of each 32-row block), so that a tile's
+// reduction is spread over four workgroups.
 static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, int nsplit, int ntiles) {
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int tile_linear = blockIdx.x;
+    const int q = blockIdx.y;
     int tm, tn;
     if (g.flags & F_TRI_GRID) {
         tri_decode(tile_linear, tm, tn);
@@ -321,10 +325,16 @@ static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, i
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] += src[((i * 2 + j) * 16 + v) * THREADS + tid];
+                for (int v = 0; v < 4; ++v)
+                    acc[i][j][4 * q + v] += src[((i * 2 + j) * 16 + 4 * q + v) * THREADS + tid];
     }
     const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
-    epilogue(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
+    switch (q) {
+        case 0: epilogue<0, 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
+        case 1: epilogue<4, 8>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
+        case 2: epilogue<8, 12>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
+        default: epilogue<12, 16>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
+    }
 }
 
 // Host-side launch of a full (non split-K) product.  `batch` >= 1.
