@@ -299,25 +299,69 @@ __global__ __launch_bounds__(256) void group_init_kernel(PruneState P) {
     if (gtid == 0) *P.sel = -1;
 }
 
-// One workgroup per structure s: B = (Hd[S,S])^-1 by in-place Gauss-Jordan elimination in LDS (the
-// pivots of a positive definite block are its successive Schur complements, all > 0; no pivoting),
-// then score_s = sum_i w_i B w_i^T = <B, W[:,S]^T W[:,S]> with the Gram matrix accumulated in fp64.
+typedef double doublex4 __attribute__((ext_vector_type(4)));
+
+// One workgroup per structure s:
+//   G = W[:,S]^T W[:,S]  (g x g, fp64) on the fp64 matrix cores (v_mfma_f64_16x16x4_f64: lane l supplies
+//       A[row l%16][k l/16] and B[k l/16][col l%16], accumulator v holds D[row 4v + l/16][col l%16]), the
+//       rows of W streamed through LDS 64 at a time, four 16 x 16 tiles of G per wavefront;
+//   B = (Hd[S,S])^-1 by in-place Gauss-Jordan elimination in LDS (the pivots of a positive definite
+//       block are its successive Schur complements, all > 0; no pivoting);
+//   score_s = sum_i w_i B w_i^T = <B, G>.
 __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step) {
     __shared__ double Bm[GMAX][GMAX + 1];
     __shared__ double rowk[GMAX], colk[GMAX];
-    __shared__ float Wt[64][GMAX + 1];
+    __shared__ float Wt[64][GMAX + 4];
     __shared__ double red[256];
     __shared__ int bad;
     const int s = blockIdx.x, tid = threadIdx.x, g = P.g, d = P.d;
+    const int lane = tid & 63, wave = tid >> 6, q4 = lane >> 4, cl16 = lane & 15;
     if (*P.status != 0) return;
     if (!P.alive[s]) {
         if (tid == 0) P.score[s] = 0.0;
         return;
     }
     const int c0 = s * g;
-    for (int e = tid; e < g * g; e += 256) Bm[e / g][e % g] = P.Hd[(size_t)(c0 + e / g) * d + c0 + e % g];
+    // element mapping of the g x g block without divisions: column lane, rows wave + 4 q
+    for (int i = wave; i < g; i += 4)
+        if (lane < g) Bm[i][lane] = P.Hd[(size_t)(c0 + i) * d + c0 + lane];
     if (tid == 0) bad = 0;
+
+    // ---- Gram matrix: tiles (ta, tb) of 16 x 16, tile index = wave + 4 * x, x < 4 (g <= 64)
+    const int nt = (g + 15) / 16;
+    doublex4 acc[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
+    for (int i0 = 0; i0 < P.m; i0 += 64) {
+        __syncthreads();
+        {
+            float wv[16];                                  // sixteen loads in flight per thread
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int r = wave + 4 * q, c = lane;
+                wv[q] = (i0 + r < P.m && c < g) ? P.W[(size_t)(i0 + r) * d + c0 + c] : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 16; ++q) Wt[wave + 4 * q][lane] = wv[q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int x = 0; x < 4; ++x) {
+            const int tile = wave + 4 * x;
+            if (tile < nt * nt) {                       // wave-uniform
+                const int ta = tile / nt, tb = tile % nt;
+#pragma unroll
+                for (int ks = 0; ks < 16; ++ks) {
+                    const double av = (double)Wt[4 * ks + q4][16 * ta + cl16];
+                    const double bv = (double)Wt[4 * ks + q4][16 * tb + cl16];
+                    acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[x], 0, 0, 0);
+                }
+            }
+        }
+    }
     __syncthreads();
+
+    // ---- B = A^-1 in place
     for (int k = 0; k < g; ++k) {
         const double piv = Bm[k][k];
         if (tid < g) { rowk[tid] = Bm[k][tid]; colk[tid] = Bm[tid][k]; }
@@ -327,14 +371,25 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step
             break;
         }
         const double ip = 1.0 / piv;
-        for (int e = tid; e < g * g; e += 256) {
-            const int i = e / g, j = e % g;
-            double v;
-            if (i == k && j == k) v = ip;
-            else if (i == k) v = rowk[j] * ip;
-            else if (j == k) v = -colk[i] * ip;
-            else v = Bm[i][j] - colk[i] * rowk[j] * ip;
-            Bm[i][j] = v;
+        if (lane < g) {
+            const int j = lane;
+            const double rj = rowk[j] * ip;
+            double cur[GMAX / 4], ck[GMAX / 4];
+#pragma unroll
+            for (int q = 0; q < GMAX / 4; ++q) {           // all loads first: sixteen rows per lane
+                const int i = wave + 4 * q;
+                cur[q] = (i < g) ? Bm[i][j] : 0.0;
+                ck[q] = (i < g) ? colk[i] : 0.0;
+            }
+#pragma unroll
+            for (int q = 0; q < GMAX / 4; ++q) {
+                const int i = wave + 4 * q;
+                double v;
+                if (i == k) v = (j == k) ? ip : rj;
+                else if (j == k) v = -ck[q] * ip;
+                else v = cur[q] - ck[q] * rj;
+                if (i < g) Bm[i][j] = v;
+            }
         }
         __syncthreads();
     }
@@ -344,35 +399,22 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step
         return;
     }
     double *Bout = P.Binv + (size_t)s * g * g;
-    for (int e = tid; e < g * g; e += 256) Bout[e] = Bm[e / g][e % g];
+    for (int i = wave; i < g; i += 4)
+        if (lane < g) Bout[i * g + lane] = Bm[i][lane];
 
-    // Gram contraction: thread owns pairs e = tid + 256 q
-    double acc[16];
-#pragma unroll
-    for (int q = 0; q < 16; ++q) acc[q] = 0.0;
-    for (int i0 = 0; i0 < P.m; i0 += 64) {
-        for (int e = tid; e < 64 * g; e += 256) {
-            const int r = e / g, c = e % g;
-            Wt[r][c] = (i0 + r < P.m) ? P.W[(size_t)(i0 + r) * d + c0 + c] : 0.f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int q = 0; q < 16; ++q) {
-            const int e = tid + 256 * q;
-            if (e < g * g) {
-                const int a = e / g, c = e % g;
-                double sacc = acc[q];
-                for (int r = 0; r < 64; ++r) sacc += (double)Wt[r][a] * (double)Wt[r][c];
-                acc[q] = sacc;
-            }
-        }
-        __syncthreads();
-    }
+    // ---- <B, G>: each lane holds G[16 ta + 4 v + q4][16 tb + cl16]
     double part = 0.0;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) {
-        const int e = tid + 256 * q;
-        if (e < g * g) part += Bm[e / g][e % g] * acc[q];
+    for (int x = 0; x < 4; ++x) {
+        const int tile = wave + 4 * x;
+        if (tile < nt * nt) {
+            const int ta = tile / nt, tb = tile % nt;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int a = 16 * ta + 4 * v + q4, c = 16 * tb + cl16;
+                if (a < g && c < g) part += Bm[a][c] * acc[x][v];
+            }
+        }
     }
     red[tid] = part;
     __syncthreads();
@@ -429,6 +471,7 @@ __global__ __launch_bounds__(256) void group_prepare_kernel(PruneState P) {
 // zeroed at the end); the rows Hd[S,:] read here are therefore the pre-step ones.
 constexpr int G_ROWS = 16;
 __global__ __launch_bounds__(256) void group_update_kernel(PruneState P) {
+    __shared__ double Cs[G_ROWS][GMAX];       // this tile's rows of C_H or C_W
     if (*P.status != 0) return;
     const int g = P.g, d = P.d, m = P.m, p = *P.sel, c0 = p * g;
     const int ncc = (d + 255) / 256;
@@ -441,6 +484,12 @@ __global__ __launch_bounds__(256) void group_update_kernel(PruneState P) {
         const int rows = is_h ? d : m;
         const bool live = (j < d) && P.alive[j / g];   // the selected structure is already marked removed
         const double *C = is_h ? P.CH : P.CW;
+        __syncthreads();
+        for (int e = threadIdx.x; e < G_ROWS * g; e += 256) {
+            const int ii = e / g, b = e % g;
+            Cs[ii][b] = (i0 + ii < rows) ? C[(size_t)(i0 + ii) * g + b] : 0.0;
+        }
+        __syncthreads();
         double acc[G_ROWS];
 #pragma unroll
         for (int ii = 0; ii < G_ROWS; ++ii) acc[ii] = 0.0;
@@ -448,10 +497,7 @@ __global__ __launch_bounds__(256) void group_update_kernel(PruneState P) {
             for (int b = 0; b < g; ++b) {
                 const double r = P.Hd[(size_t)(c0 + b) * d + j];
 #pragma unroll
-                for (int ii = 0; ii < G_ROWS; ++ii) {
-                    const int i = i0 + ii;
-                    if (i < rows) acc[ii] += C[(size_t)i * g + b] * r;
-                }
+                for (int ii = 0; ii < G_ROWS; ++ii) acc[ii] += Cs[ii][b] * r;
             }
 #pragma unroll
             for (int ii = 0; ii < G_ROWS; ++ii) {
