@@ -221,7 +221,11 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
 
     int tm, tn, split = 0, tile_linear;
     if (g.flags & F_TRI_GRID) {
-        tile_linear = blockIdx.x;
+        // Workgroups are dealt to the 8 XCDs round-robin by blockIdx.x.  Neighbouring entries of the tile
+        // list share their row slab of A, so each XCD takes a contiguous eighth of the list and finds
+        // that slab in its own L2.
+        const int n = gridDim.x, x = blockIdx.x % 8;
+        tile_linear = x * (n / 8) + min(x, n % 8) + blockIdx.x / 8;
         tri_decode(tile_linear, tm, tn);
     } else {
         tile_linear = blockIdx.x;

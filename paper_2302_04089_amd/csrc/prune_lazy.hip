@@ -195,13 +195,22 @@ __device__ __forceinline__ double readlane_d(double v, int lane) {
 }
 constexpr int DPP_XOR1 = 0xB1, DPP_XOR2 = 0x4E, DPP_HALF_MIRROR = 0x141, DPP_MIRROR = 0x140;
 
-// Sum over the 64 lanes, returned in every lane.
+// Sum over the 64 lanes, returned in every lane.  Four butterfly steps inside the 16-lane rows, then
+// the row totals are chained with the row-broadcast permutes (lane 15 of rows 0 and 2 into rows 1 and
+// 3, lane 31 into rows 2 and 3), which leaves the grand total in lane 63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_rows_d(double v) {
+    return dmake((unsigned)__builtin_amdgcn_update_dpp(0, (int)dhi(v), CTRL, ROW_MASK, 0xf, false),
+                 (unsigned)__builtin_amdgcn_update_dpp(0, (int)dlo(v), CTRL, ROW_MASK, 0xf, false));
+}
 __device__ __forceinline__ double wave_sum(double v) {
     v += dpp_d<DPP_XOR1>(v);
     v += dpp_d<DPP_XOR2>(v);
     v += dpp_d<DPP_HALF_MIRROR>(v);
     v += dpp_d<DPP_MIRROR>(v);          // every lane of a 16-lane row holds the row's sum
-    return (readlane_d(v, 0) + readlane_d(v, 16)) + (readlane_d(v, 32) + readlane_d(v, 48));
+    v += dpp_rows_d<0x142, 0xa>(v);     // row_bcast:15 into rows 1 and 3 (other rows add 0)
+    v += dpp_rows_d<0x143, 0xc>(v);     // row_bcast:31 into rows 2 and 3
+    return readlane_d(v, 63);
 }
 
 template <int CTRL>
@@ -229,14 +238,17 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, uprev, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, misc, wt, total;
+    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, misc, wt, total;
 };
+__host__ __device__ inline int padded_rows(int m) { return (m + 255) / 256 * 256; }   // Eq. 3 runs unguarded
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
     Lds l;
+    const int mp = padded_rows(m);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 15) / 16 * 16; return r; };
     l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [row][k]
     l.uprev = take(sizeof(double) * BMAX * cp);          // the same for the previous block (background flush)
+    l.coefa = take(sizeof(double) * AFRAG);               // matrix-core A fragments of a synchronous flush
     l.coefbg = take(sizeof(double) * AFRAG);              // matrix-core A fragments of the background flush
     l.bgacc = take(sizeof(double) * 4 * 64 * NBG);       // its accumulators between steps: [wavefront][4][lane]
     l.bgpart = take(sizeof(int) * NW);                   // k-group quarter each background wavefront is at
@@ -245,9 +257,7 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.pivprev = take(sizeof(double) * BMAX);
     l.seq_done = take(sizeof(int) * NW);                 // column tiles each background wavefront has finished
     l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
-    l.wcol = take(m * sizeof(float) > AFRAG * sizeof(double) ? m * sizeof(float) : AFRAG * sizeof(double));
-                                                         // column p of W (fp32) during a step; matrix-core A
-                                                         // fragments [k/4][lane] (fp64) during a flush
+    l.wcol = take(mp * sizeof(float));                   // column p of W, zero beyond row m
     l.norm = take(sizeof(double) * cp);
     l.diag = take(sizeof(double) * cp);
     l.score = take(sizeof(double) * cp);
@@ -257,7 +267,7 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.snap_bits = take(sizeof(unsigned) * ((d + 32) / 32 + 1));
     l.red_s = take(sizeof(unsigned long long) * NW);     // per-wavefront minima of the candidate keys
     l.misc = take(96);
-    l.wt = take(w_in_lds ? sizeof(float) * (size_t)cpb * m : 0);
+    l.wt = take(w_in_lds ? sizeof(float) * (size_t)cpb * mp : 0);
     l.total = o;
     return l;
 }
@@ -361,7 +371,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     int *seq_done = reinterpret_cast<int *>(smem + L.seq_done);
     double *pivs = reinterpret_cast<double *>(smem + L.pivs);
     float *wcol = reinterpret_cast<float *>(smem + L.wcol);
-    double *coefa = reinterpret_cast<double *>(smem + L.wcol);
+    double *coefa = reinterpret_cast<double *>(smem + L.coefa);
     double *norm = reinterpret_cast<double *>(smem + L.norm);
     double *diag = reinterpret_cast<double *>(smem + L.diag);
     double *score = reinterpret_cast<double *>(smem + L.score);
@@ -378,8 +388,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     const int nown = max(0, min(cpb, d - j0));
     double *P = S.P + (size_t)b * d * cp;       // this workgroup's panel: P[c * cp + r] = Hinv[j0 + r][c]
     float *wt_lds = reinterpret_cast<float *>(smem + L.wt);
-    float *wt_glb = S.Wt + (size_t)j0 * m;
-#define WT(jl, i) (*(W_IN_LDS ? &wt_lds[(size_t)(jl) * m + (i)] : &wt_glb[(size_t)(jl) * m + (i)]))
+    const int mp = padded_rows(m);               // row pitch of wt and length of wcol: padding holds zeros
+    float *wt_glb = S.Wt + (size_t)j0 * mp;
+#define WT(jl, i) (*(W_IN_LDS ? &wt_lds[(size_t)(jl) * mp + (i)] : &wt_glb[(size_t)(jl) * mp + (i)]))
 
     // ------------------------------------------------------------------ set-up (own data only)
     for (int w = tid; w < (d + 31) / 32; w += LT) {
@@ -394,6 +405,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     for (int w = tid; w < (d + 32) / 32 + 1; w += LT) snap_bits[w] = 0;
     for (int r = tid; r < cp; r += LT) { alive_own[r] = 0; norm[r] = 0.0; diag[r] = 1.0; score[r] = 0.0; hstale[r] = 0.0; }
     for (int e = tid; e < BMAX * cp; e += LT) uloc[e] = 0.0;
+    for (int i = tid; i < mp; i += LT) wcol[i] = 0.f;
     __syncthreads();
     for (int q = tid; q < S.n_snap; q += LT) {
         const int sstep = S.snap_steps[q];
@@ -404,8 +416,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     for (int jl = wave; jl < nown; jl += NW) {
         const int j = j0 + jl;
         double s = 0.0;
-        for (int i = lane; i < m; i += 64) {
-            const float w = S.W[(size_t)i * d + j];
+        for (int i = lane; i < mp; i += 64) {
+            const float w = (i < m) ? S.W[(size_t)i * d + j] : 0.f;
             WT(jl, i) = w;
             s += (double)w * (double)w;
         }
@@ -638,21 +650,18 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             const double f = u * rpiv;
             const float nf = -(float)f;
             double s = 0.0;
-            for (int i0 = 0; i0 < m; i0 += 256) {
-                float w[4], c[4];
+            for (int i0 = 0; i0 < mp; i0 += 256) {         // rows beyond m hold zeros and stay zero
+                // four consecutive rows per lane: one 128-bit LDS access per operand
+                typedef float floatx4 __attribute__((ext_vector_type(4)));
+                floatx4 *wp = reinterpret_cast<floatx4 *>(&WT(jl, i0 + 4 * lane));
+                floatx4 w = *wp;
+                const floatx4 c = *reinterpret_cast<const floatx4 *>(&wcol[i0 + 4 * lane]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const int i = i0 + lane + 64 * e;
-                    w[e] = (i < m) ? WT(jl, i) : 0.f;
-                    c[e] = (i < m) ? wcol[i] : 0.f;
+                    w[e] = __builtin_fmaf(c[e], nf, w[e]);               // Eq. 3 on the fp32 state, one rounding
+                    s += (double)w[e] * (double)w[e];
                 }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = i0 + lane + 64 * e;
-                    const float v = __builtin_fmaf(c[e], nf, w[e]);       // Eq. 3 on the fp32 state, one rounding
-                    if (i < m) WT(jl, i) = v;
-                    s += (double)v * (double)v;
-                }
+                *wp = w;
             }
             s = wave_sum(s);
             if (lane == 0) {
@@ -776,7 +785,7 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     State &s = l.st;
     Carver c(ws);
     s.P = c.take<double>((size_t)p.nb * d_col * p.cp);
-    s.Wt = c.take<float>(p.w_in_lds ? 1 : (size_t)d_col * d_row);
+    s.Wt = c.take<float>(p.w_in_lds ? 1 : (size_t)d_col * padded_rows(d_row));
     s.U = c.take<double>((size_t)2 * BMAX * d_col);
     // zero-initialised region: slots, payload, barrier epochs, status
     s.slots = c.take<unsigned long long>((size_t)2 * p.nb);
