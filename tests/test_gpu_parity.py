@@ -255,3 +255,55 @@ def test_end_to_end_pipeline(z, oracle, m, d, g, n, kind):
     assert lam == pytest.approx(lam_or, rel=1e-5)
     ref = compare_run(oracle, W32, Hi_or, g, G, order.cpu().numpy(), err.cpu().numpy(), snap_steps=snaps)
     assert rel_fro(W_snap[0].cpu().numpy(), ref["W_snap"][0]) <= REL_TOL
+
+
+# ------------------------------------------------------------------------------------------ more shapes
+
+def _spd_inverse_like(d, rank, seed):
+    """A cheap symmetric positive definite stand-in for an inverse Hessian of a large layer:
+    diagonal plus low-rank, fp32 (only the loop stage is under test, it never sees H itself)."""
+    rng = np.random.default_rng(seed)
+    V = rng.standard_normal((d, rank)).astype(np.float32) / np.sqrt(rank)
+    a = (0.5 + rng.random(d)).astype(np.float32)
+    Hi = (V @ V.T) * 0.3
+    Hi[np.diag_indices(d)] += a
+    return np.ascontiguousarray((Hi + Hi.T) * 0.5, dtype=np.float32)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_prune_random_small_shapes(z, oracle, seed):
+    """Seeded random shapes: 1..64 rows, 2..96 columns, groups of 1, 2, 4 or 8, random removal count."""
+    rng = np.random.default_rng(1000 + seed)
+    g = int(rng.choice([1, 1, 2, 4, 8]))
+    G = int(rng.integers(2, 96 // g + 1))
+    d = G * g
+    m = int(rng.integers(1, 65))
+    n = int(rng.integers(d + 8, 4 * d + 64))
+    k = int(rng.integers(1, G + 1))
+    spec = workloads.small(m, d, g, n, x_kind=["gelu", "normal", "scaled_normal"][seed % 3], seed=100 + seed)
+    _run_prune_case(z, oracle, spec, k, sorted({0, k // 2, k}))
+
+
+@pytest.mark.parametrize("m", [8, 1100])
+def test_prune_more_than_sixteen_columns_per_workgroup(z, oracle, m):
+    """4352 columns = 17 per workgroup on 256 compute units: two 16-row groups per panel and the
+    synchronous flush; with 1100 rows the transposed W no longer fits LDS and lives in the workspace."""
+    d, k = 4352, 200
+    Hi32 = _spd_inverse_like(d, 16, seed=m)
+    rng = np.random.default_rng(m)
+    W32 = (0.05 * rng.standard_normal((m, d))).astype(np.float32)
+    Wd, Hd = dev(W32), dev(Hi32)
+    order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hd, 1, k, snapshot_steps=[k // 2])
+    torch.cuda.synchronize()
+    ref = compare_run(oracle, W32, Hi32, 1, k, order.cpu().numpy(), err.cpu().numpy(), snap_steps=[k // 2])
+    assert rel_fro(Wd.cpu().numpy(), ref["W"]) <= REL_TOL
+    assert rel_fro(W_snap[0].cpu().numpy(), ref["W_snap"][0]) <= REL_TOL
+    assert rel_fro(Hd.cpu().numpy(), ref["Hinv"]) <= REL_TOL
+
+
+def test_prune_eager_fallback_kernel(z, oracle, monkeypatch):
+    """The eager single-column kernel (used when the deferred-update kernel's state does not fit) is
+    selected with ZIPLM_PRUNE_EAGER=1 and must meet the same bar."""
+    monkeypatch.setenv("ZIPLM_PRUNE_EAGER", "1")
+    spec = workloads.small(40, 300, 1, 1200, x_kind="gelu", seed=31)
+    _run_prune_case(z, oracle, spec, 300, [0, 150, 300])
