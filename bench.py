@@ -5,11 +5,14 @@ HBM: Hessian accumulation (H = 2 X X^T), dampened Cholesky inverse, and the gree
 removes every structure of the layer (Algorithm 1).  Default workload: configuration 3, the
 BERT-base feed-forward down-projection (W 768 x 3072, 16384 calibration tokens, post-GELU).
 
-Prints ONE JSON line.  `value` is seconds per layer for the whole path (lower is better).
+Prints ONE JSON line.  `value` is seconds per layer for the whole path (lower is better); with
+--config 5 it is seconds for the 24 problems of the 12-layer sweep, one after another.
 `roofline` describes the greedy-loop kernel against HBM bandwidth with the algorithmic byte
 count  sum over steps of (8 r^2 + 8 d_row r + 4 r), r = live columns;  `roofline_hessian` the
 Hessian kernel against the fp32 matrix-core peak with d (d + 1) n_tok useful flops.
-`cpu_baseline` is the fp64 CPU oracle timed on this host on the same layer.
+`hbm_triad_gbs` is what a plain triad over 1 GiB arrays reaches on the same device (the achievable
+HBM rate; `frac_of_triad` prices the loop against it).  `cpu_baseline` is the fp64 CPU oracle timed
+on this host on the same layer.
 """
 import argparse
 import json
@@ -46,7 +49,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--config", type=int, default=3, help="workload configuration 1..4")
+    ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5 (5: the 24-problem sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="also run one plain device-to-device copy of this many MiB before the timed steps, so a "
@@ -66,42 +69,58 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     ziplm.lib()
-    spec = workloads.config(args.config)
-    d, m, g, G = spec.d_col, spec.d_row, spec.group_size, spec.n_groups
-    t0 = time.time()
-    X_host = workloads.make_X(spec)
-    W_host = workloads.make_W(spec)
-    gen_s = time.time() - t0
+    if args.config == 5:
+        # the sweep: 12 layers, each an attention output projection (heads) and a feed-forward down-projection (columns)
+        specs = [workloads.config(5, layer=l, kind=k) for l in range(12) for k in ("attn", "ffn")]
+    else:
+        specs = [workloads.config(args.config)]
 
-    X = torch.from_numpy(X_host).cuda()
-    W0 = torch.from_numpy(W_host).cuda()
-    W = torch.empty_like(W0)
-    H = torch.empty((d, d), dtype=torch.float32, device="cuda")
-    Hi = torch.empty_like(H)
-    ws_h = torch.empty(max(ziplm.ziplm_hessian_workspace_bytes(d, spec.n_tok), 256), dtype=torch.uint8, device="cuda")
-    ws_i = torch.empty(ziplm.ziplm_hinv_workspace_bytes(d), dtype=torch.uint8, device="cuda")
-    ws_p = torch.empty(ziplm.ziplm_prune_workspace_bytes(m, d, g, 0), dtype=torch.uint8, device="cuda")
+    class Problem:
+        pass
+
+    t0 = time.time()
+    problems = []
+    for spec in specs:
+        q = Problem()
+        q.spec = spec
+        q.X = torch.from_numpy(workloads.make_X(spec)).cuda()
+        q.W0 = torch.from_numpy(workloads.make_W(spec)).cuda()
+        d, m, g = spec.d_col, spec.d_row, spec.group_size
+        q.W = torch.empty_like(q.W0)
+        q.H = torch.empty((d, d), dtype=torch.float32, device="cuda")
+        q.Hi = torch.empty_like(q.H)
+        q.ws_h = torch.empty(max(ziplm.ziplm_hessian_workspace_bytes(d, spec.n_tok), 256), dtype=torch.uint8, device="cuda")
+        q.ws_i = torch.empty(ziplm.ziplm_hinv_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+        q.ws_p = torch.empty(ziplm.ziplm_prune_workspace_bytes(m, d, g, 0), dtype=torch.uint8, device="cuda")
+        problems.append(q)
+    gen_s = time.time() - t0
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
     stage_ms = {"hessian": [], "hinv": [], "loop": []}
+    loop_ms_columns = []          # loop time of the single-column problems of one step (the roofline kernel)
+    hess_ms_all = []
     result = {}
 
     def one_step(record):
-        e = [ev() for _ in range(4)]
-        W.copy_(W0)
-        H.zero_()
-        e[0].record()
-        ziplm.ziplm_hessian_accumulate(H, X, 2.0, workspace=ws_h)
-        e[1].record()
-        ziplm.ziplm_hinv(H, spec.damp_rel, out=Hi, workspace=ws_i, check=False)
-        e[2].record()
-        order, err, _ = ziplm.ziplm_structured_obs_prune(W, Hi, g, G, workspace=ws_p, check=False)
-        e[3].record()
+        marks = []
+        for q in problems:
+            spec = q.spec
+            e = [ev() for _ in range(4)]
+            q.W.copy_(q.W0)
+            q.H.zero_()
+            e[0].record()
+            ziplm.ziplm_hessian_accumulate(q.H, q.X, 2.0, workspace=q.ws_h)
+            e[1].record()
+            ziplm.ziplm_hinv(q.H, spec.damp_rel, out=q.Hi, workspace=q.ws_i, check=False)
+            e[2].record()
+            q.order, q.err, _ = ziplm.ziplm_structured_obs_prune(q.W, q.Hi, spec.group_size, spec.n_groups,
+                                                                 workspace=q.ws_p, check=False)
+            e[3].record()
+            marks.append(e)
         if record:
-            result["events"].append(e)
-        return order, err
+            result["events"].append(marks)
 
     if args.calibration_copy_mib > 0:
         n = args.calibration_copy_mib * (1 << 20) // 4
@@ -117,23 +136,51 @@ def main():
     result["events"] = []
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        order, err = one_step(True)
+        one_step(True)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    for e in result["events"]:
-        stage_ms["hessian"].append(e[0].elapsed_time(e[1]))
-        stage_ms["hinv"].append(e[1].elapsed_time(e[2]))
-        stage_ms["loop"].append(e[2].elapsed_time(e[3]))
+    for marks in result["events"]:
+        tot = [0.0, 0.0, 0.0]
+        cols = 0.0
+        for q, e in zip(problems, marks):
+            dt = [e[i].elapsed_time(e[i + 1]) for i in range(3)]
+            tot = [a + b for a, b in zip(tot, dt)]
+            if q.spec.group_size == 1:
+                cols += dt[2]
+        stage_ms["hessian"].append(tot[0])
+        stage_ms["hinv"].append(tot[1])
+        stage_ms["loop"].append(tot[2])
+        loop_ms_columns.append(cols)
     ms_per_step = wall * 1e3 / args.steps
     mean = {k: float(np.mean(v)) for k, v in stage_ms.items()}
+    median = {k: float(np.median(v)) for k, v in stage_ms.items()}
 
-    order_h = order.cpu().numpy()
-    assert sorted(order_h.tolist()) == list(range(G)), "loop did not remove every structure exactly once"
-    assert float(W.abs().max()) == 0.0
+    for q in problems:
+        G = q.spec.n_groups
+        assert sorted(q.order.cpu().numpy().tolist()) == list(range(G)), "loop did not remove every structure exactly once"
+        assert float(q.W.abs().max()) == 0.0
 
-    loop_bytes = loop_algorithmic_bytes(m, d, g, G)
-    loop_gbs = loop_bytes / (mean["loop"] * 1e-3) / 1e9
-    syrk_flops = float(d) * (d + 1) * spec.n_tok
+    # achievable HBM rate on this device: a plain triad a = b + s * c over 1 GiB arrays (3 x 4 bytes per element)
+    n_tri = 1 << 28
+    ta = torch.empty(n_tri, dtype=torch.float32, device="cuda")
+    tb = torch.ones(n_tri, dtype=torch.float32, device="cuda")
+    tc = torch.ones(n_tri, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        torch.add(tb, tc, alpha=0.5, out=ta)
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(10):
+        torch.add(tb, tc, alpha=0.5, out=ta)
+    e1.record()
+    torch.cuda.synchronize()
+    triad_gbs = 10 * 3 * 4 * n_tri / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del ta, tb, tc
+
+    column_specs = [q.spec for q in problems if q.spec.group_size == 1]
+    loop_bytes = sum(loop_algorithmic_bytes(sp.d_row, sp.d_col, 1, sp.n_groups) for sp in column_specs)
+    loop_ms = float(np.mean(loop_ms_columns)) if column_specs else None
+    loop_gbs = loop_bytes / (loop_ms * 1e-3) / 1e9 if column_specs else None     # head-only workloads: time only
+    syrk_flops = sum(float(q.spec.d_col) * (q.spec.d_col + 1) * q.spec.n_tok for q in problems)
     hess_tflops = syrk_flops / (mean["hessian"] * 1e-3) / 1e12
 
     traffic = None
@@ -141,6 +188,17 @@ def main():
     if kib is not None:
         traffic = (kib[0] + kib[1]) * 1024.0
 
+    if args.config == 5:
+        workload = ("config 5: GPT-2-small-shaped sweep, 12 layers x (attention out-proj W 768x768 in 12 heads of 64 "
+                    "columns, N(0,1) inputs + FFN down-proj W 768x3072 single columns, GELU inputs), 32768 tokens each, "
+                    "damp 0.01, remove everything; value = the 24 problems one after another")
+        n_steps_loop = sum(sp.n_groups for sp in column_specs)      # the 12 x 3072 single-column removals
+    else:
+        spec = specs[0]
+        workload = ("config %d: %s, W %dx%d, group %d, %d tokens %s, damp %.2g, remove all %d"
+                    % (args.config, spec.name, spec.d_row, spec.d_col, spec.group_size, spec.n_tok, spec.x_kind,
+                       spec.damp_rel, spec.n_groups))
+        n_steps_loop = spec.n_groups
     out = {
         "metric": "structured-OBS prune time per layer (Hessian + inverse + greedy loop)",
         "value": ms_per_step / 1e3,
@@ -154,15 +212,17 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": "config %d: %s, W %dx%d, group %d, %d tokens %s, damp %.2g, remove all %d"
-                   % (args.config, spec.name, m, d, g, spec.n_tok, spec.x_kind, spec.damp_rel, G)},
+        "config": {"workload": workload},
         "stage_ms": mean,
+        "stage_ms_median": median,
         "hessian_tflops": hess_tflops,
         "loop_hbm_gbs": loop_gbs,
-        "us_per_loop_step": mean["loop"] * 1e3 / G,
+        "us_per_loop_step": (loop_ms if column_specs else mean["loop"]) * 1e3 / n_steps_loop,
+        "hbm_triad_gbs": triad_gbs,
         "roofline": {"kernel": "greedy loop", "bound": "hbm", "achieved": loop_gbs, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": loop_gbs / HBM_PEAK_GBS, "traffic": traffic,
-                     "algorithmic_bytes": loop_bytes},
+                     "unit": "GB/s", "frac": loop_gbs / HBM_PEAK_GBS if column_specs else None,
+                     "frac_of_triad": loop_gbs / triad_gbs if column_specs else None,
+                     "traffic": traffic, "algorithmic_bytes": loop_bytes},
         "roofline_hessian": {"kernel": "hessian syrk", "bound": "mfma", "achieved": hess_tflops,
                              "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": hess_tflops / MFMA_F32_PEAK_TFLOPS, "useful_flops": syrk_flops},
@@ -171,17 +231,27 @@ def main():
     if not args.no_cpu_baseline:
         from oracle import ziplm_oracle as oracle
         oracle.build()
-        t0 = time.perf_counter()
-        H_or = oracle.hessian(X_host, 2.0)
-        t1 = time.perf_counter()
-        Hi_or, _ = oracle.hinv(H_or, spec.damp_rel)
-        t2 = time.perf_counter()
-        oracle.prune(W_host, Hi_or.astype(np.float32), g, G)
-        t3 = time.perf_counter()
+        # config 5: one layer (its two problems) is timed and multiplied by 12
+        sample_specs = specs[:2] if args.config == 5 else specs
+        parts = [0.0, 0.0, 0.0]
+        for sp in sample_specs:
+            X_host = workloads.make_X(sp)
+            W_host = workloads.make_W(sp)
+            t0 = time.perf_counter()
+            H_or = oracle.hessian(X_host, 2.0)
+            t1 = time.perf_counter()
+            Hi_or, _ = oracle.hinv(H_or, sp.damp_rel)
+            t2 = time.perf_counter()
+            oracle.prune(W_host, Hi_or.astype(np.float32), sp.group_size, sp.n_groups)
+            t3 = time.perf_counter()
+            parts = [parts[0] + t1 - t0, parts[1] + t2 - t1, parts[2] + t3 - t2]
+            del X_host
+        mult = 12 if args.config == 5 else 1
         out["cpu_baseline"] = {
-            "value": t3 - t0, "unit": "s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": "the whole layer of the same workload, once (Hessian %.2f s, inverse %.2f s, loop %.2f s)"
-                      % (t1 - t0, t2 - t1, t3 - t2)}
+            "value": mult * sum(parts), "unit": "s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": ("layer 0 of the sweep (both problems), once, times 12" if args.config == 5 else
+                       "the whole layer of the same workload, once")
+                      + " (Hessian %.2f s, inverse %.2f s, loop %.2f s)" % tuple(mult * x for x in parts)}
     out["input_generation_s"] = gen_s
     print(json.dumps(out))
 

@@ -343,3 +343,58 @@ int ziplm_oracle_prune(double *W, double *Hinv, int d_row, int d_col, int g,
     free(alive); free(score); free(bad); free(Lp); free(B); free(R); free(CW); free(CH);
     return rc;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Layer-wise error of dropping a whole module ("Pruned structures": a      */
+/* whole attention or feed-forward module may be removed): every column is  */
+/* pruned and nothing is left to compensate, so the error of Eq. 1, in the   */
+/* quadratic form the pruner uses, is                                       */
+/*   sum_i W_i (H + lambda I) W_i^T  =  tr(W (H + lambda I) W^T).            */
+/* With H = scale * X X^T and lambda = 0 this is scale * ||W X||_F^2, the    */
+/* squared denominator of the prior p_s (Section 3.2).                       */
+/* Written as the double sum it is; rows are independent.                    */
+/* ------------------------------------------------------------------------ */
+int ziplm_oracle_module_error(const double *W, const double *H, int d_row, int d_col,
+                              double lambda, double *err_out)
+{
+    if (!W || !H || !err_out || d_row <= 0 || d_col <= 0) return ORACLE_ERR_INVALID_ARG;
+    const size_t d = (size_t)d_col;
+    double total = 0.0;
+    #pragma omp parallel for schedule(static) reduction(+ : total)
+    for (int i = 0; i < d_row; ++i) {
+        const double *w = W + (size_t)i * d;
+        double row = 0.0;
+        for (size_t j = 0; j < d; ++j) {
+            double hw = lambda * w[j];                    /* ((H + lambda I) w^T)_j */
+            for (size_t k = 0; k < d; ++k) hw += H[j * d + k] * w[k];
+            row += w[j] * hw;
+        }
+        total += row;
+    }
+    *err_out = total;
+    return ORACLE_OK;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Prior of Section 3.2 ("Structured SPDY search"):                          */
+/*   p_s = ||W_s X - W X|| / ||W X||                                        */
+/* for the layer after its first t+1 removals.  The squared numerator is the */
+/* layer-wise error of the pruned layer, which is the running sum of the     */
+/* per-step errors of Algorithm 1 (the cross terms vanish because each       */
+/* intermediate W is the least-squares optimum on its support); the squared  */
+/* denominator is the whole-module error above.  The text calls p_s a        */
+/* "squared error" but prints a ratio of norms; reading: the printed ratio,  */
+/* i.e. the square root of the ratio of the quadratic forms, measured with   */
+/* the same (dampened) H the pruner works with.  A fully dropped layer gives */
+/* 1, as the text says.                                                      */
+/* ------------------------------------------------------------------------ */
+int ziplm_oracle_prior(const double *err, int n, double total, double *prior_out)
+{
+    if (n < 0 || (n > 0 && (!err || !prior_out)) || !(total > 0.0)) return ORACLE_ERR_INVALID_ARG;
+    double run = 0.0;
+    for (int t = 0; t < n; ++t) {
+        run += err[t];
+        prior_out[t] = sqrt(run / total);
+    }
+    return ORACLE_OK;
+}

@@ -47,6 +47,10 @@ def _load():
                                        ctypes.c_int, ip, dp]
     lib.ziplm_oracle_threads.restype = ctypes.c_int
     lib.ziplm_oracle_threads.argtypes = []
+    lib.ziplm_oracle_module_error.restype = ctypes.c_int
+    lib.ziplm_oracle_module_error.argtypes = [dp, dp, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp]
+    lib.ziplm_oracle_prior.restype = ctypes.c_int
+    lib.ziplm_oracle_prior.argtypes = [dp, ctypes.c_int, ctypes.c_double, dp]
     _lib = lib
     return lib
 
@@ -130,3 +134,29 @@ def prune(W, Hinv, group_size, n_remove, alive=None, forced=None, snap_steps=Non
     if rc:
         raise OracleError(rc)
     return dict(W=W, Hinv=Hinv, order=order, err=err, best=best, gap=gap, W_snap=W_snap)
+
+
+def module_error(W, H, lam=0.0):
+    """tr(W (H + lam I) W^T): the layer-wise error of dropping the whole module."""
+    lib = _load()
+    W = _f64(W)
+    H = _f64(H)
+    m, d = W.shape
+    assert H.shape == (d, d)
+    out = ctypes.c_double(0.0)
+    rc = lib.ziplm_oracle_module_error(_ptr(W, ctypes.c_double), _ptr(H, ctypes.c_double), m, d, float(lam),
+                                       ctypes.byref(out))
+    if rc:
+        raise OracleError(rc)
+    return out.value
+
+
+def prior(err, total):
+    """p_s after each removal: sqrt(cumulative error / whole-module error)."""
+    lib = _load()
+    err = _f64(err).reshape(-1)
+    out = np.empty_like(err)
+    rc = lib.ziplm_oracle_prior(_ptr(err, ctypes.c_double), int(err.size), float(total), _ptr(out, ctypes.c_double))
+    if rc:
+        raise OracleError(rc)
+    return out

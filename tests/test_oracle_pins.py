@@ -240,6 +240,53 @@ def test_one_group_is_whole_module_drop(oracle):
     assert np.all(r["W"] == 0.0)
 
 
+def test_module_error_is_the_output_energy_and_the_one_group_score(oracle):
+    """tr(W (H + lam I) W^T) three independent ways: from the layer outputs (scale*||W X||^2 +
+    lam*||W||^2), as the Eq. 2 score of the single group holding every column (through the pruning
+    routine, which never forms H), and as the sum of the errors of a column-by-column removal."""
+    W0, X = _problem(71, 5, 12, 50)
+    H = 2.0 * X @ X.T
+    Hi, lam = oracle.hinv(H, 0.01)
+    e = oracle.module_error(W0, H, lam)
+    assert e == pytest.approx(2.0 * ((W0 @ X) ** 2).sum() + lam * (W0 ** 2).sum(), rel=1e-12)
+    assert e == pytest.approx(oracle.prune(W0, Hi, 12, 1)["err"][0], rel=1e-9)
+    assert e == pytest.approx(oracle.prune(W0, Hi, 1, 12)["err"].sum(), rel=1e-9)
+    # lam = 0, an asymmetric probe: H must enter as H[j][k] w_j w_k, not through its diagonal or a norm
+    Hs = np.arange(9.0).reshape(3, 3)
+    Hs = Hs + Hs.T + 20.0 * np.eye(3)
+    w = np.array([[1.0, -2.0, 0.5]])
+    assert oracle.module_error(w, Hs, 0.0) == pytest.approx(float((w @ Hs @ w.T)[0, 0]), rel=1e-14)
+    assert oracle.module_error(w, Hs, 3.0) == pytest.approx(float((w @ Hs @ w.T)[0, 0]) + 3.0 * 5.25, rel=1e-14)
+
+
+def test_prior_is_the_relative_output_error_of_the_pruned_layer(oracle):
+    """lam = 0, scale = 1: p after t+1 removals equals ||W_t X - W X|| / ||W X|| with W_t the
+    least-squares optimum on the surviving columns, computed directly from the outputs; it is
+    non-decreasing and reaches exactly 1 when everything is removed."""
+    m, d, n, g = 4, 12, 60, 2
+    W0, X = _problem(72, m, d, n)
+    H = X @ X.T
+    Hi, lam = oracle.hinv(H, 0.0)
+    assert lam == 0.0
+    G = d // g
+    r = oracle.prune(W0, Hi, g, G)
+    total = oracle.module_error(W0, H, 0.0)
+    p = oracle.prior(r["err"], total)
+    base = np.sqrt(((W0 @ X) ** 2).sum())
+    removed = []
+    for t in range(G):
+        removed += list(range(r["order"][t] * g, r["order"][t] * g + g))
+        keep = [c for c in range(d) if c not in removed]
+        _, sq = _ls_restricted(W0, X, keep)
+        assert p[t] == pytest.approx(np.sqrt(sq) / base, rel=1e-8)
+    assert np.all(np.diff(p) >= -1e-15)
+    assert p[-1] == pytest.approx(1.0, rel=1e-10)
+    # plain arithmetic of the definition
+    assert np.allclose(oracle.prior([1.0, 3.0, 5.0], 16.0), [0.25, 0.5, 0.75])
+    with pytest.raises(Exception):
+        oracle.prior([1.0], 0.0)
+
+
 def test_duplicate_feature_is_cheap_once_then_expensive(oracle):
     """Two identical input features: each looks cheap alone; after the first is removed its
     weights move onto the twin, which is then no longer cheap (the S1/S2 example, Section 3.1)."""
