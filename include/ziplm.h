@@ -8,6 +8,9 @@
  *   3. ziplm_structured_obs_prune the greedy loop: score every remaining structure (Eq. 2),
  *                                 remove the cheapest, compensate the remaining weights (Eq. 3),
  *                                 eliminate the structure from Hinv (Eq. 4), k times; then mask.
+ *   and, for the sparsity search that consumes the pruned layers (Section 3.2):
+ *      ziplm_module_error         error of dropping the whole module, tr(W (H + lambda I) W^T)
+ *      ziplm_prior                p_s after every removal of a run
  *
  * Conventions
  *   - Every matrix is row-major.  W is d_row x d_col; a structure is a set of COLUMNS of W
@@ -125,6 +128,41 @@ int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int 
                                int *info_host, void *workspace, size_t workspace_bytes,
                                void *stream);
 size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap);
+
+/*
+ * Error of dropping a whole module ("Pruned structures", Section 3.1: besides heads and
+ * feed-forward columns, an entire attention or feed-forward module may be removed).  With every
+ * column pruned nothing is left to compensate, so the layer-wise error in the quadratic form of
+ * Eq. 2 is
+ *
+ *   *err_out = tr(W (H + lambda I) W^T) = sum_i W_i (H + lambda I) W_i^T
+ *
+ * which for H = scale X X^T is scale ||W X||^2 + lambda ||W||^2, and equals the sum of err_out of
+ * a ziplm_structured_obs_prune run that removes every structure.  It is also the squared
+ * denominator of the prior below.
+ * W d_row x d_col and H d_col x d_col (symmetric; the UNdampened Hessian, both triangles), fp32,
+ * row-major, only read.  lambda >= 0 is the dampening constant that ziplm_hinv reports.
+ * err_out: one DEVICE double.  Products are fp32 matrix-core multiply-accumulates, the final sums
+ * fp64 in a fixed order.
+ */
+int ziplm_module_error(const float *W, const float *H, int d_row, int d_col, float lambda,
+                       double *err_out, void *workspace, size_t workspace_bytes, void *stream);
+size_t ziplm_module_error_workspace_bytes(int d_row, int d_col);
+
+/*
+ * Prior of the sparsity search (Section 3.2, "Structured SPDY search"):
+ * p_s = ||W_s X - W X|| / ||W X|| for the layer after each removal of a greedy run,
+ *
+ *   prior_out[t] = sqrt((err[0] + ... + err[t]) / *total),   t = 0 .. n-1
+ *
+ * err: the err_out of ziplm_structured_obs_prune (device, double[n]); the running sum is the
+ * layer-wise error of the pruned layer because every intermediate W is the least-squares optimum
+ * on its support.  total: one device double, the whole-module error from ziplm_module_error (with
+ * the same lambda the pruner's Hinv was built with); a fully dropped layer gets 1.
+ * prior_out: device double[n].  n == 0 is a no-op.  *total must be positive (not checked: the
+ * value is on the device).
+ */
+int ziplm_prior(const double *err, int n, const double *total, double *prior_out, void *stream);
 
 #ifdef __cplusplus
 }

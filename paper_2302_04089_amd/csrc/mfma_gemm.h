@@ -49,8 +49,10 @@ enum Flags : unsigned {
     F_KSTART_MAXMN = 8u,   // k starts at max(tile_row, tile_col) * 128 (T^T T with T lower triangular)
     F_KEND_M = 16u,        // k ends at (tile_row + 1) * 128 (A is lower triangular: A(m, k) = 0 for k > m)
     F_TRI_GRID = 32u,      // blockIdx.x enumerates the lower-triangular tile list instead of a 2-D grid
-    F_PARTIAL = 64u        // split-K: write raw accumulators to `partial`, no epilogue
+    F_PARTIAL = 64u,       // split-K: write raw accumulators to `partial`, no epilogue
 };
+// The DOT variant of the kernel writes no output matrix: it sums (alpha * acc + dot_lambda * C) * C over the tile,
+// C read-only, in fp64, into dot_partial[tile].
 
 struct Args {
     const float *A;
@@ -67,6 +69,9 @@ struct Args {
     int64_t k_chunk;
     float *partial;   // [split][tile][64 regs][256 threads]
     int tiles_n;      // number of tile columns (2-D grid decoding)
+    // DOT variant
+    double *dot_partial;   // [tiles]
+    float dot_lambda;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -211,7 +216,7 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
         }
 }
 
-template <int AMODE, int BMODE, bool VEC, bool KGUARD>
+template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false>
 __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     __shared__ __attribute__((aligned(16))) float lds[2][2][SLAB];
 
@@ -293,6 +298,34 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
                 for (int v = 0; v < 16; ++v) dst[((i * 2 + j) * 16 + v) * THREADS + tid] = acc[i][j][v];
         return;
     }
+    if (DOT) {
+        // every thread sums its 64 products in fp64, then the 256 partial sums are added in thread order
+        const int r = lane & 31, half = lane >> 5;
+        double sum = 0.0;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = tn * BN + wn * 64 + j * 32 + r;
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = tm * BM + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                    if (row < g.M && col < g.N) {
+                        const float c = C[(int64_t)row * g.ldc + col];
+                        sum += ((double)(g.alpha * acc[i][j][v]) + (double)g.dot_lambda * (double)c) * (double)c;
+                    }
+                }
+            }
+        double *red = reinterpret_cast<double *>(&lds[0][0][0]);   // all waves are past the last slice's barrier
+        red[tid] = sum;
+        __syncthreads();
+        if (tid == 0) {
+            double total = 0.0;
+            for (int q = 0; q < THREADS; ++q) total += red[q];
+            g.dot_partial[tile_linear] = total;
+        }
+        return;
+    }
     const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
     epilogue(acc, C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
 }
@@ -342,7 +375,7 @@ static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, i
 }
 
 // Host-side launch of a full (non split-K) product.  `batch` >= 1.
-template <int AMODE, int BMODE, bool VEC, bool KGUARD>
+template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false>
 inline hipError_t launch(Args g, int batch, hipStream_t stream) {
     if (g.M <= 0 || g.N <= 0 || batch <= 0) return hipSuccess;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
@@ -350,7 +383,7 @@ inline hipError_t launch(Args g, int batch, hipStream_t stream) {
     dim3 grid;
     if (g.flags & F_TRI_GRID) grid = dim3(tiles_m * (tiles_m + 1) / 2, 1, batch);
     else grid = dim3(tiles_m * tiles_n, 1, batch);
-    hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD>), grid, dim3(THREADS), 0, stream, g);
+    hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD, DOT>), grid, dim3(THREADS), 0, stream, g);
     return hipGetLastError();
 }
 

@@ -27,6 +27,7 @@ EXPORTS = (
     "ziplm_hessian_accumulate", "ziplm_hessian_workspace_bytes",
     "ziplm_hinv", "ziplm_hinv_workspace_bytes",
     "ziplm_structured_obs_prune", "ziplm_prune_workspace_bytes",
+    "ziplm_module_error", "ziplm_module_error_workspace_bytes", "ziplm_prior",
 )
 
 _lib = None
@@ -67,6 +68,12 @@ def lib():
                                              vp, sz, vp]
     L.ziplm_prune_workspace_bytes.restype = sz
     L.ziplm_prune_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    L.ziplm_module_error.restype = i32
+    L.ziplm_module_error.argtypes = [vp, vp, i32, i32, f32, vp, vp, sz, vp]
+    L.ziplm_module_error_workspace_bytes.restype = sz
+    L.ziplm_module_error_workspace_bytes.argtypes = [i32, i32]
+    L.ziplm_prior.restype = i32
+    L.ziplm_prior.argtypes = [vp, i32, vp, vp, vp]
     _lib = L
     return L
 
@@ -163,3 +170,52 @@ def ziplm_structured_obs_prune(W, Hinv, group_size, n_remove, alive=None, snapsh
     if rc != OK:
         raise ZiplmError(rc, info.value)
     return order[:n_remove], err[:n_remove], W_snap
+
+
+def database_steps(n_structures, kind):
+    """Removal counts at which to snapshot W so that one greedy run yields the per-layer database of
+    Section 3.2 on the grid of its "Runtime awareness" paragraph (host-side list arithmetic only).
+
+    kind "columns": intermediate sizes n * 0.9**i, i = 0..42 (truncated to integers, duplicates
+    dropped) -> snapshot after n - size removals.  kind "heads": 0, 1, ..., n heads removed.
+    Returns a sorted list of distinct step counts, usable as `snapshot_steps`."""
+    n = int(n_structures)
+    if kind == "heads":
+        return list(range(n + 1))
+    if kind == "columns":
+        return sorted({n - int(n * 0.9 ** i) for i in range(43)})
+    raise ValueError("kind must be 'columns' or 'heads'")
+
+
+def ziplm_module_error_workspace_bytes(d_row, d_col):
+    return int(lib().ziplm_module_error_workspace_bytes(int(d_row), int(d_col)))
+
+
+def ziplm_module_error(W, H, lam=0.0, out=None, workspace=None, stream=None):
+    """tr(W (H + lam I) W^T) as a one-element float64 device tensor."""
+    _check(W, torch.float32, "W")
+    _check(H, torch.float32, "H")
+    m, d = W.shape
+    assert H.shape == (d, d)
+    out = torch.empty(1, dtype=torch.float64, device=W.device) if out is None else out
+    _check(out, torch.float64, "out")
+    need = ziplm_module_error_workspace_bytes(m, d)
+    ws = workspace if workspace is not None else _workspace(need, W.device)
+    rc = lib().ziplm_module_error(W.data_ptr(), H.data_ptr(), m, d, float(lam), out.data_ptr(), ws.data_ptr(),
+                                  ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return out
+
+
+def ziplm_prior(err, total, out=None, stream=None):
+    """p_s after each removal: sqrt(cumsum(err) / total); err float64[n] and total float64[1] on the device."""
+    _check(err, torch.float64, "err")
+    _check(total, torch.float64, "total")
+    out = torch.empty_like(err) if out is None else out
+    _check(out, torch.float64, "out")
+    assert out.numel() >= err.numel()
+    rc = lib().ziplm_prior(err.data_ptr(), int(err.numel()), total.data_ptr(), out.data_ptr(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return out

@@ -65,7 +65,9 @@ def test_config3_full_pipeline_matches_oracle(z, oracle):
     assert resid <= 1e-3, "||(H + lambda I) Hinv - I||_max = %.3e" % resid     # cond ~ 2e3, fp32 factorisation
     assert lam == pytest.approx(0.01 * np.trace(Hh.astype(np.float64)) / d, rel=1e-5)
 
-    snaps = [d // 4, d // 2, (3 * d) // 4, (9 * d) // 10, d - 8]
+    # the per-layer database of Section 3.2 out of this one run: intermediate sizes 3072 * 0.9^i, i = 0..42
+    snaps = z.database_steps(d, "columns")
+    assert snaps[0] == 0 and snaps[-1] == d - int(d * 0.9 ** 42) and len(snaps) == 43
     Wd = torch.from_numpy(W32).cuda()
     order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hi, 1, d, snapshot_steps=snaps)
     torch.cuda.synchronize()
@@ -139,3 +141,24 @@ def test_config4_properties(z):
     # and the first k errors add up to the error of that joint removal: tr((W_k - W0) H (W_k - W0)^T)
     joint = np.sum(G * (Wk - W64))
     assert err_h[:k_snap].sum() == pytest.approx(joint, rel=1e-4)
+
+
+def test_config3_module_error_equals_sum_of_step_errors(z):
+    """Full size, device only: removing all 3072 columns one at a time must add up to the error of
+    dropping the module at once, tr(W (H + lambda I) W^T); the prior of the run then ends at 1 and
+    never decreases."""
+    spec = workloads.config(3)
+    X = torch.from_numpy(workloads.make_X(spec)).cuda()
+    W = torch.from_numpy(workloads.make_W(spec)).cuda()
+    d = spec.d_col
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, X, scale=2.0)
+    del X
+    Hi, lam = z.ziplm_hinv(H, spec.damp_rel)
+    total = z.ziplm_module_error(W, H, lam)
+    order, err, _ = z.ziplm_structured_obs_prune(W, Hi, 1, d)
+    p = z.ziplm_prior(err, total)
+    torch.cuda.synchronize()
+    assert abs(float(err.sum()) / float(total[0]) - 1.0) <= 1e-4
+    p = p.cpu().numpy()
+    assert abs(p[-1] - 1.0) <= 1e-4 and np.all(np.diff(p) >= -1e-12)

@@ -307,3 +307,65 @@ def test_prune_eager_fallback_kernel(z, oracle, monkeypatch):
     monkeypatch.setenv("ZIPLM_PRUNE_EAGER", "1")
     spec = workloads.small(40, 300, 1, 1200, x_kind="gelu", seed=31)
     _run_prune_case(z, oracle, spec, 300, [0, 150, 300])
+
+
+# ------------------------------------------------------------------------------------------ module error, prior
+
+@pytest.mark.parametrize("m,d,n,kind,lam_rel", [
+    (64, 256, 1024, "gelu", 0.01),          # whole tiles
+    (100, 300, 700, "scaled_normal", 0.01), # ragged rows and columns
+    (5, 70, 333, "gelu", 0.0),              # d_col % 4 != 0: scalar loads; no dampening
+    (300, 130, 512, "normal", 0.1),
+])
+def test_module_error_matches_oracle(z, oracle, m, d, n, kind, lam_rel):
+    """tr(W (H + lam I) W^T) on the device's own fp32 H against the fp64 double sum on the same matrix."""
+    spec = workloads.small(m, d, 1, n, x_kind=kind, seed=m + d)
+    X, W = workloads.make_X(spec), workloads.make_W(spec)
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, dev(X), scale=2.0)
+    Hh = H.cpu().numpy()
+    lam = float(np.float32(lam_rel * np.diag(Hh).astype(np.float64).mean()))
+    out = z.ziplm_module_error(dev(W), H, lam)
+    torch.cuda.synchronize()
+    ref = oracle.module_error(W, Hh, lam)
+    assert abs(float(out[0]) - ref) <= REL_TOL * ref
+    # and it is what the layer outputs say: scale * ||W X||^2 + lam * ||W||^2 in fp64 from the inputs
+    direct = 2.0 * ((W.astype(np.float64) @ X.astype(np.float64)) ** 2).sum() + lam * (W.astype(np.float64) ** 2).sum()
+    assert abs(float(out[0]) - direct) <= REL_TOL * direct
+    # deterministic
+    out2 = z.ziplm_module_error(dev(W), H, lam)
+    assert float(out2[0]) == float(out[0])
+
+
+def test_prior_of_a_full_run_matches_oracle_and_ends_at_one(z, oracle):
+    """Pipeline on the device: Hessian, inverse, remove every column, whole-module error, prior.  The
+    prior is compared with the oracle's on the oracle's own chain, and its last value with 1: the
+    errors of a remove-all run add up to the whole-module error (a cross-check between the greedy loop
+    and the trace kernel that involves no CPU arithmetic)."""
+    spec = workloads.small(48, 320, 1, 2048, x_kind="gelu", seed=21)
+    X, W = workloads.make_X(spec), workloads.make_W(spec)
+    d = spec.d_col
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, dev(X), scale=2.0)
+    Hi, lam = z.ziplm_hinv(H, spec.damp_rel)
+    Wd = dev(W)
+    total = z.ziplm_module_error(Wd, H, lam)
+    order, err, _ = z.ziplm_structured_obs_prune(Wd, Hi, 1, d)
+    p = z.ziplm_prior(err, total)
+    torch.cuda.synchronize()
+    p = p.cpu().numpy()
+    assert abs(p[-1] - 1.0) <= REL_TOL
+    assert np.all(np.diff(p) >= -1e-12)
+    H_or = oracle.hessian(X, 2.0)
+    Hi_or, lam_or = oracle.hinv(H_or, spec.damp_rel)
+    r = oracle.prune(W, Hi_or, 1, d)
+    p_or = oracle.prior(r["err"], oracle.module_error(W, H_or, lam_or))
+    if np.array_equal(order.cpu().numpy(), r["order"]):
+        assert np.max(np.abs(p - p_or) / p_or) <= REL_TOL
+    # the prior kernel alone, on the oracle's errors: plain arithmetic, long enough for several chunks per thread
+    e_long = np.abs(np.random.default_rng(5).standard_normal(5000)) + 0.1
+    tot = float(e_long.sum()) * 1.25
+    got = z.ziplm_prior(dev(e_long, torch.float64), dev(np.array([tot]), torch.float64)).cpu().numpy()
+    assert np.max(np.abs(got - oracle.prior(e_long, tot))) <= 1e-12
+    empty = z.ziplm_prior(torch.empty(0, dtype=torch.float64, device="cuda"), total)
+    assert empty.numel() == 0
