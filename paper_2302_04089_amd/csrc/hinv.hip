@@ -3,10 +3,11 @@
 //
 //   A  = H + lambda I, embedded in a dp x dp matrix (dp = d_col rounded up to 128) whose padding is
 //        the identity, so that every internal product runs on whole tiles;
-//   A  = L L^T     right-looking blocked Cholesky, 64-column panels:
-//                  diagonal block factored in the registers of one wavefront, panel
-//                  L21 = A21 L11^-T by substitution (one thread per row), trailing update
-//                  A22 -= L21 L21^T on the fp32 matrix cores;
+//   A  = L L^T     right-looking blocked Cholesky, 64-column panels, two launches per panel (every dependent
+//                  launch costs far more than the arithmetic of a panel): one that factors the diagonal
+//                  block in the registers of a wavefront and solves the panel L21 = A21 L11^-T by
+//                  substitution (one thread per row), one for the trailing update A22 -= L21 L21^T on
+//                  the fp32 matrix cores;
 //   T  = L^-1      diagonal blocks inverted in one batched launch, then bottom-up pairwise merges  T21 = -T22 (L21 T11), all pairs of a level in one
 //                  batched launch;
 //   Hinv = T^T T   lower tiles computed, mirrored to the upper triangle.
@@ -59,78 +60,101 @@ __device__ __forceinline__ float lane_bcast(float v, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-__global__ __launch_bounds__(64) void potrf_diag_kernel(float *__restrict__ A, int ld, int k0, int *__restrict__ info) {
-    const int lane = threadIdx.x;
-    float *Ab = A + (int64_t)k0 * ld + k0;
-    float a[NB];
-#pragma unroll
-    for (int c = 0; c < NB; c += 4) {
-        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
-        a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];        // upper entries are never used
-    }
-    int first_bad = -1;                                   // branch-free bookkeeping: one straight-line block
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        float piv = lane_bcast(a[j], j);
-        const bool bad = !(piv > 0.f);                    // uniform
-        first_bad = (bad && first_bad < 0) ? j : first_bad;
-        piv = bad ? 1.f : piv;
-        const float r = __builtin_amdgcn_rsqf(piv);       // 1 ulp reciprocal square root
-        a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
-#pragma unroll
-        for (int c = j + 1; c < NB; ++c) {
-            a[c] -= a[j] * lane_bcast(a[j], c);
-            // bound how many broadcast values (scalar registers) are alive at once
-            if ((c & 15) == 15) __builtin_amdgcn_sched_barrier(0);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-    }
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-        if (c <= lane) Ab[(int64_t)lane * ld + c] = a[c];
-    if (first_bad >= 0 && lane == 0 && *info == 0) *info = 1 + k0 + first_bad;
-}
+constexpr int PANEL_ROWS = 128;     // rows of the panel one workgroup solves
+constexpr int PANEL_THREADS = 256;
 
-// Panel below a factored diagonal block:  X L11^T = A21, solved row by row in place.  One thread per
-// row of A21 (its 64 entries in registers), L11 in LDS (row j read with 128-bit broadcast reads):
-//     x_j = (a_j - sum_{k<j} x_k L11[j][k]) / L11[j][j].
-__global__ __launch_bounds__(256) void trsm_panel_kernel(float *__restrict__ A, int ld, int k0, int rows) {
-    __shared__ __attribute__((aligned(16))) float L[NB][NB];
+// One launch per 64-column panel: every workgroup factors the diagonal block at (k0, k0) itself (wavefront
+// 0, redundantly: it is cheaper than a second dependent launch), while its other wavefronts stage the
+// workgroup's 128 rows of the panel below it in LDS with coalesced reads; then one thread per row solves
+//     x L11^T = a:   x_j = (a_j - sum_{k<j} x_k L11[j][k]) / L11[j][j]
+// with its 64 entries in registers and L11 read from LDS with 128-bit broadcast reads, and the rows go back
+// through LDS with coalesced writes.  Workgroup 0 stores the factor L11 to `Ldiag` (a separate 64 x 64
+// buffer: the diagonal block in A is still being read by the other workgroups) and reports a non-positive
+// pivot in *info (1 + global column of the first one; it is replaced by 1 so that the arithmetic stays finite).
+__global__ __launch_bounds__(PANEL_THREADS) void panel_kernel(float *__restrict__ A, int ld, int k0, int rows,
+                                                               float *__restrict__ Ldiag, int *__restrict__ info) {
+    __shared__ __attribute__((aligned(16))) float Ls[NB][NB];
     __shared__ float rdiag[NB];
-    const int tid = threadIdx.x;
-    const float *Lb = A + (int64_t)k0 * ld + k0;
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int i = e / NB, j = e % NB;
-        L[i][j] = (j <= i) ? Lb[(int64_t)i * ld + j] : 0.f;
-    }
-    __syncthreads();
-    if (tid < NB) rdiag[tid] = 1.0f / L[tid][tid];
-    __syncthreads();
-    const int row = blockIdx.x * 256 + tid;
-    if (row >= rows) return;
-    float *xr = A + (int64_t)(k0 + NB + row) * ld + k0;
-    float x[NB];
+    __shared__ float Xs[PANEL_ROWS][NB + 1];       // pitch 65: a thread's row is conflict-free to walk
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row0 = blockIdx.x * PANEL_ROWS;
+    float *Xg = A + (int64_t)(k0 + NB + row0) * ld + k0;     // this workgroup's rows of the panel
+    if (wave == 0) {
+        const float *Ab = A + (int64_t)k0 * ld + k0;
+        float a[NB];
 #pragma unroll
-    for (int c = 0; c < NB; c += 4) {
-        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(xr + c);
-        x[c] = v[0]; x[c + 1] = v[1]; x[c + 2] = v[2]; x[c + 3] = v[3];
-    }
-#pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        float s = x[j];
-#pragma unroll
-        for (int k4 = 0; k4 < (j + 3) / 4; ++k4) {
-            const gemm::floatx4 l = *reinterpret_cast<const gemm::floatx4 *>(&L[j][4 * k4]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if (4 * k4 + e < j) s -= x[4 * k4 + e] * l[e];
+        for (int c = 0; c < NB; c += 4) {
+            const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
+            a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];        // upper entries are never used
         }
-        x[j] = s * rdiag[j];
-    }
+        int first_bad = -1;                                   // branch-free bookkeeping: one straight-line block
+        float my_rdiag = 1.f;
 #pragma unroll
-    for (int c = 0; c < NB; c += 4) {
-        gemm::floatx4 v = {x[c], x[c + 1], x[c + 2], x[c + 3]};
-        *reinterpret_cast<gemm::floatx4 *>(xr + c) = v;
+        for (int j = 0; j < NB; ++j) {
+            float piv = lane_bcast(a[j], j);
+            const bool bad = !(piv > 0.f);                    // uniform
+            first_bad = (bad && first_bad < 0) ? j : first_bad;
+            piv = bad ? 1.f : piv;
+            const float r = __builtin_amdgcn_rsqf(piv);       // 1 ulp reciprocal square root
+            my_rdiag = (lane == j) ? r : my_rdiag;            // 1 / l_jj
+            a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
+#pragma unroll
+            for (int c = j + 1; c < NB; ++c) {
+                a[c] -= a[j] * lane_bcast(a[j], c);
+                // bound how many broadcast values (scalar registers) are alive at once
+                if ((c & 15) == 15) __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int c = 0; c < NB; c += 4) {
+            gemm::floatx4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = (c + e <= lane) ? a[c + e] : 0.f;
+            *reinterpret_cast<gemm::floatx4 *>(&Ls[lane][c]) = v;
+            if (blockIdx.x == 0) *reinterpret_cast<gemm::floatx4 *>(Ldiag + lane * NB + c) = v;
+        }
+        rdiag[lane] = my_rdiag;
+        if (blockIdx.x == 0 && first_bad >= 0 && lane == 0 && *info == 0) *info = 1 + k0 + first_bad;
+    } else {
+        // 128 rows x 16 pieces of four floats, 16 consecutive lanes per row
+        for (int e = tid - 64; e < PANEL_ROWS * (NB / 4); e += PANEL_THREADS - 64) {
+            const int r = e >> 4, c4 = e & 15;
+            gemm::floatx4 v = {0.f, 0.f, 0.f, 0.f};
+            if (row0 + r < rows) v = *reinterpret_cast<const gemm::floatx4 *>(Xg + (int64_t)r * ld + 4 * c4);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) Xs[r][4 * c4 + q] = v[q];
+        }
+    }
+    __syncthreads();
+    if (tid < PANEL_ROWS && row0 + tid < rows) {
+        float x[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) x[c] = Xs[tid][c];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            float sum = x[j];
+#pragma unroll
+            for (int k4 = 0; k4 < (j + 3) / 4; ++k4) {
+                const gemm::floatx4 l = *reinterpret_cast<const gemm::floatx4 *>(&Ls[j][4 * k4]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * k4 + e < j) sum -= x[4 * k4 + e] * l[e];
+            }
+            x[j] = sum * rdiag[j];
+        }
+#pragma unroll
+        for (int c = 0; c < NB; ++c) Xs[tid][c] = x[c];
+    }
+    __syncthreads();
+    for (int e = tid; e < PANEL_ROWS * (NB / 4); e += PANEL_THREADS) {
+        const int r = e >> 4, c4 = e & 15;
+        if (row0 + r < rows) {
+            gemm::floatx4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = Xs[r][4 * c4 + q];
+            *reinterpret_cast<gemm::floatx4 *>(Xg + (int64_t)r * ld + 4 * c4) = v;
+        }
     }
 }
 
@@ -138,15 +162,14 @@ __global__ __launch_bounds__(256) void trsm_panel_kernel(float *__restrict__ A, 
 // one wavefront per block, lane i holds row i of L, lane c builds column c of T = L^-1 by forward
 // substitution, T[i][c] = (delta_ic - sum_{k<i} L[i][k] T[k][c]) / L[i][i]; "entry k of row i" is
 // register k of lane i, one v_readlane.
-__global__ __launch_bounds__(64) void trtri_diag_kernel(const float *__restrict__ A, int ld, float *__restrict__ dinv_all) {
+__global__ __launch_bounds__(64) void trtri_diag_kernel(const float *__restrict__ Ldiag_all, float *__restrict__ dinv_all) {
     const int lane = threadIdx.x;
-    const int k0 = blockIdx.x * NB;
-    const float *Ab = A + (int64_t)k0 * ld + k0;
+    const float *Lb = Ldiag_all + (size_t)blockIdx.x * NB * NB;
     float *dinv = dinv_all + (size_t)blockIdx.x * NB * NB;
     float a[NB];
 #pragma unroll
     for (int c = 0; c < NB; c += 4) {
-        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
+        const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Lb + lane * NB + c);
         a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];
     }
     float t[NB];
@@ -174,7 +197,7 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
 
 struct HinvLayout {
     int dp;
-    float *A, *T, *S, *dinv;
+    float *A, *T, *S, *dinv, *ldiag;
     double *lambda;
     int *info;
     size_t bytes;
@@ -189,6 +212,7 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.T = c.take<float>(n2);
     l.S = c.take<float>(n2);
     l.dinv = c.take<float>((size_t)(l.dp / NB) * NB * NB);
+    l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored diagonal blocks
     l.lambda = c.take<double>(1);
     l.info = c.take<int>(1);
     l.bytes = c.off;
@@ -220,12 +244,13 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
 
     // ---- A = L L^T, right-looking over 64-column panels --------------------------------------
     for (int k0 = 0; k0 < dp; k0 += NB) {
-        hipLaunchKernelGGL(potrf_diag_kernel, dim3(1), dim3(64), 0, st, l.A, dp, k0, l.info);
         const int rest = dp - k0 - NB;
+        // diagonal block factored and the panel below it solved, L21 = A21 inv(L11)^T, in one launch
+        const int pblocks = rest > 0 ? (rest + PANEL_ROWS - 1) / PANEL_ROWS : 1;
+        hipLaunchKernelGGL(panel_kernel, dim3(pblocks), dim3(PANEL_THREADS), 0, st, l.A, dp, k0, rest,
+                           l.ldiag + (size_t)(k0 / NB) * NB * NB, l.info);
         if (rest <= 0) break;
         float *A21 = l.A + (int64_t)(k0 + NB) * dp + k0;
-        // L21 = A21 inv(L11)^T by substitution, in place
-        hipLaunchKernelGGL(trsm_panel_kernel, dim3((rest + 255) / 256), dim3(256), 0, st, l.A, dp, k0, rest);
         // A22 -= L21 L21^T, lower tiles only
         Args u = {};
         u.A = A21; u.lda = dp;
@@ -237,7 +262,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     }
 
     // ---- T = L^-1: leaves (all diagonal blocks in one launch), then pairwise merges -------------------
-    hipLaunchKernelGGL(trtri_diag_kernel, dim3(dp / NB), dim3(64), 0, st, l.A, dp, l.dinv);
+    hipLaunchKernelGGL(trtri_diag_kernel, dim3(dp / NB), dim3(64), 0, st, l.ldiag, l.dinv);
     hipLaunchKernelGGL(place_diag_kernel, dim3(fill_blocks), dim3(256), 0, st, l.T, dp, l.dinv);
     ZIPLM_HIP_TRY(hipGetLastError());
     for (int s = NB; s < dp; s *= 2) {

@@ -185,7 +185,9 @@ __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn) {
     tn = t - m * (m + 1) / 2;
 }
 
-// Epilogue for one accumulator set: C = alpha * acc + beta * C, optional mirrored copy.
+// Epilogue for one accumulator set: C = alpha * acc + beta * C, optional mirrored copy.  With beta != 0 the
+// old values of a 32 x 32 block are all loaded before the first store, so that their latencies overlap
+// (a load issued after a store to the same array would otherwise have to wait for it).
 template <int V0 = 0, int V1 = 16>
 __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__restrict__ C, int64_t ldc,
                                          int M, int N, int tm, int tn, float alpha, float beta,
@@ -196,21 +198,27 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int col = tn * BN + wn * 64 + j * 32 + r;
+            const int row_base = tm * BM + wm * 64 + i * 32 + 4 * half;
+            float old[V1 - V0], old_t[V1 - V0];
+            if (beta != 0.f) {
+#pragma unroll
+                for (int v = V0; v < V1; ++v) {
+                    const int row = row_base + 8 * (v >> 2) + (v & 3);
+                    const bool ok = row < M && col < N;
+                    old[v - V0] = ok ? C[(int64_t)row * ldc + col] : 0.f;
+                    old_t[v - V0] = (ok && mirror) ? C[(int64_t)col * ldc + row] : 0.f;
+                }
+            }
 #pragma unroll
             for (int v = V0; v < V1; ++v) {
-                const int row = tm * BM + wm * 64 + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+                const int row = row_base + 8 * (v >> 2) + (v & 3);
                 if (row < M && col < N) {
-                    float *p = C + (int64_t)row * ldc + col;
                     float val = alpha * acc[i][j][v];
-                    if (beta != 0.f) val += beta * (*p);
-                    *p = val;
-                    if (mirror) {
-                        // symmetric output (M == N): transposed element of a strictly-lower tile
-                        float *pt = C + (int64_t)col * ldc + row;
-                        float vt = alpha * acc[i][j][v];
-                        if (beta != 0.f) vt += beta * (*pt);
-                        *pt = vt;
-                    }
+                    float vt = val;
+                    if (beta != 0.f) { val += beta * old[v - V0]; vt += beta * old_t[v - V0]; }
+                    C[(int64_t)row * ldc + col] = val;
+                    // symmetric output (M == N): transposed element of a strictly-lower tile
+                    if (mirror) C[(int64_t)col * ldc + row] = vt;
                 }
             }
         }
