@@ -12,6 +12,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, 
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
+# hinv.hip keeps 64-entry rows in registers inside doubly nested, fully unrolled loops; past the default size limit
+# of "#pragma unroll" the compiler would leave the outer loop rolled and put those rows in scratch memory
+FILE_FLAGS = {"hinv.hip": ["-mllvm", "-pragma-unroll-threshold=1000000"]}
 
 
 def build(verbose=False):
@@ -29,7 +32,7 @@ def build(verbose=False):
     procs = []
     for s in SOURCES:
         obj = os.path.join(objdir, s.replace(".hip", ".o"))
-        cmd = [hipcc] + FLAGS + extra + ["-c", os.path.join(CSRC, s), "-o", obj]
+        cmd = [hipcc] + FLAGS + FILE_FLAGS.get(s, []) + extra + ["-c", os.path.join(CSRC, s), "-o", obj]
         if verbose:
             print(" ".join(cmd))
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

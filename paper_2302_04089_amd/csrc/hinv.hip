@@ -3,11 +3,11 @@
 //
 //   A  = H + lambda I, embedded in a dp x dp matrix (dp = d_col rounded up to 128) whose padding is
 //        the identity, so that every internal product runs on whole tiles;
-//   A  = L L^T     right-looking blocked Cholesky, 64-column panels, two launches per panel (every dependent
+//   A  = L L^T     right-looking blocked Cholesky, 128-column panels, two launches per panel (every dependent
 //                  launch costs far more than the arithmetic of a panel): one that factors the diagonal
-//                  block in the registers of a wavefront and solves the panel L21 = A21 L11^-T by
-//                  substitution (one thread per row), one for the trailing update A22 -= L21 L21^T on
-//                  the fp32 matrix cores;
+//                  block (two 64 x 64 factorisations in the registers of a wavefront) and solves the panel
+//                  L21 = A21 L11^-T by substitution (one thread per row), one for the trailing update
+//                  A22 -= L21 L21^T on the fp32 matrix cores;
 //   T  = L^-1      diagonal blocks inverted in one batched launch, then bottom-up pairwise merges  T21 = -T22 (L21 T11), all pairs of a level in one
 //                  batched launch;
 //   Hinv = T^T T   lower tiles computed, mirrored to the upper triangle.
@@ -60,102 +60,238 @@ __device__ __forceinline__ float lane_bcast(float v, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
+// In-register factorisation of a 64 x 64 block held one row per lane (a[c] = entry c of the lane's row; entries
+// above the diagonal are ignored).  Right-looking; see the comment above lane_bcast.  On return a[c], c <= lane,
+// is the factor, *my_rdiag = 1 / l_(lane,lane), and *first_bad the first column with a non-positive pivot (or -1;
+// such a pivot is replaced by 1 so that the arithmetic stays finite).  Column j of the factor is also written
+// to Lt[j][lane] (LDS): the transposed factor, whose row j the substitution below reads contiguously.
+// Branch-free on purpose: one straight-line block.  The broadcasts of a column are issued sixteen at a time
+// into sixteen scalar registers before the multiply-adds that consume them: issued in pairs, every
+// multiply-add would wait for its own broadcast.
+__device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
+    first_bad = -1;
+    my_rdiag = 1.f;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        float piv = lane_bcast(a[j], j);
+        const bool bad = !(piv > 0.f);                    // uniform
+        first_bad = (bad && first_bad < 0) ? j : first_bad;
+        piv = bad ? 1.f : piv;
+        const float r = __builtin_amdgcn_rsqf(piv);       // 1 ulp reciprocal square root
+        my_rdiag = (lane == j) ? r : my_rdiag;            // 1 / l_jj
+        a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
+        Lt[j][lane] = a[j];
+#pragma unroll
+        for (int g = 0; g < NB / 16; ++g) {               // constant trip counts: everything unrolls
+            float bc[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (16 * g + e > j) bc[e] = lane_bcast(a[j], 16 * g + e);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (16 * g + e > j) a[16 * g + e] -= a[j] * bc[e];
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+// x L^T = a for one row held in registers, column by column: x_j = a_j / L[j][j], then a_c -= x_j L[c][j] for
+// every c > j (independent multiply-adds).  Lt[j][c] = L[c][j] and the reciprocals of the diagonal are in LDS;
+// rows of Lt are read with 128-bit broadcast reads.
+__device__ __forceinline__ void solve_row_in_registers(float (&x)[NB], const float (*Lt)[NB], const float *rdiag) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const float xj = x[j] * rdiag[j];
+        x[j] = xj;
+#pragma unroll
+        for (int c4 = 0; c4 < NB / 4; ++c4) {
+            if (4 * c4 + 3 > j) {
+                const gemm::floatx4 l = *reinterpret_cast<const gemm::floatx4 *>(&Lt[j][4 * c4]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * c4 + e > j) x[4 * c4 + e] -= xj * l[e];
+            }
+        }
+    }
+}
+
+constexpr int PW = 2 * NB;          // panel width: two 64-column blocks per launch
 constexpr int PANEL_ROWS = 128;     // rows of the panel one workgroup solves
 constexpr int PANEL_THREADS = 256;
+constexpr int PITCH_B = NB + 1;     // 64 x 64 blocks that lanes walk by rows
+constexpr int PITCH_X = PW + 1;     // the 128 x 128 row tile
 
-// One launch per 64-column panel: every workgroup factors the diagonal block at (k0, k0) itself (wavefront
-// 0, redundantly: it is cheaper than a second dependent launch), while its other wavefronts stage the
-// workgroup's 128 rows of the panel below it in LDS with coalesced reads; then one thread per row solves
-//     x L11^T = a:   x_j = (a_j - sum_{k<j} x_k L11[j][k]) / L11[j][j]
-// with its 64 entries in registers and L11 read from LDS with 128-bit broadcast reads, and the rows go back
-// through LDS with coalesced writes.  Workgroup 0 stores the factor L11 to `Ldiag` (a separate 64 x 64
-// buffer: the diagonal block in A is still being read by the other workgroups) and reports a non-positive
-// pivot in *info (1 + global column of the first one; it is replaced by 1 so that the arithmetic stays finite).
-__global__ __launch_bounds__(PANEL_THREADS) void panel_kernel(float *__restrict__ A, int ld, int k0, int rows,
-                                                               float *__restrict__ Ldiag, int *__restrict__ info) {
-    __shared__ __attribute__((aligned(16))) float Ls[NB][NB];
-    __shared__ float rdiag[NB];
-    __shared__ float Xs[PANEL_ROWS][NB + 1];       // pitch 65: a thread's row is conflict-free to walk
+struct PanelLds {
+    float Lt1[NB][NB];              // transposed factor of the first diagonal block: Lt1[j][c] = L11[c][j], c >= j
+    float Lt2[NB][NB];              // the same for the second one
+    float Lm[NB][PITCH_B];          // block below L11 inside the diagonal 128 x 128: A21, then L21 = A21 L11^-T
+    float D22[NB][PITCH_B];         // second diagonal block: A22, then A22 - L21 L21^T
+    float rd1[NB], rd2[NB];         // reciprocals of the diagonals of L11 and L22
+    float Xs[PANEL_ROWS][PITCH_X];  // this workgroup's rows of the panel
+};
+
+// acc(32 x 32) = Aop[ra + i][0..63] . Bop[rb + j][0..63]^T on the fp32 matrix cores (lane l supplies
+// A[row l % 32][k l / 32] and B[k l / 32][col l % 32]), then Dst[rd + i][cd + j] -= acc.  Accumulator register v
+// of lane l holds row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32.
+__device__ __forceinline__ void tile_downdate(const float *Aop, int pitch_a, int ra, const float *Bop, int pitch_b, int rb,
+                                              float *Dst, int pitch_d, int rd, int cd, int lane) {
+    const int r = lane & 31, half = lane >> 5;
+    gemm::floatx16 acc;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+    const float *ap = Aop + (ra + r) * pitch_a + half;
+    const float *bp = Bop + (rb + r) * pitch_b + half;
+#pragma unroll 8
+    for (int kk = 0; kk < NB; kk += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ap[kk], bp[kk], acc, 0, 0, 0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int row = 8 * (v >> 2) + 4 * half + (v & 3);
+        Dst[(rd + row) * pitch_d + cd + r] -= acc[v];
+    }
+}
+
+// One launch per 128-column panel (two 64-column blocks): on this machine a dependent launch costs more than
+// the arithmetic of a panel, so the whole panel step is one kernel.  Every workgroup factors the 128 x 128
+// diagonal block at (k0, k0) itself, redundantly -- L11 in the registers of wavefront 0, L21 = A21 L11^-T by
+// substitution, A22 - L21 L21^T on the matrix cores, L22 in registers again -- while the other wavefronts
+// stage the workgroup's 128 rows of the panel below it in LDS with coalesced reads and solve them against the
+// finished parts: x1 = a1 L11^-T (one thread per row, 64 entries in registers), a2 - x1 L21^T (matrix cores),
+// x2 = (.) L22^-T.  Rows go back through LDS with coalesced writes.  Workgroup 0 stores the factor of the
+// diagonal block to separate buffers (`Ldiag`: L11 and L22, `Loff`: L21; the block in A is still being read by
+// the other workgroups) and reports a non-positive pivot in *info (1 + its global column, first one wins).
+__global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1, 1))) void panel_kernel(float *__restrict__ A, int ld, int k0, int rows,
+                                                               float *__restrict__ Ldiag, float *__restrict__ Loff,
+                                                               int *__restrict__ info) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char panel_smem[];
+    PanelLds &S = *reinterpret_cast<PanelLds *>(panel_smem);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row0 = blockIdx.x * PANEL_ROWS;
-    float *Xg = A + (int64_t)(k0 + NB + row0) * ld + k0;     // this workgroup's rows of the panel
+    const float *Ab = A + (int64_t)k0 * ld + k0;                  // the diagonal 128 x 128 block
+    float *Xg = A + (int64_t)(k0 + PW + row0) * ld + k0;          // this workgroup's rows of the panel
+    int bad1 = -1, bad2 = -1;
+
+    // ---- first diagonal block in registers || everything else staged in LDS
     if (wave == 0) {
-        const float *Ab = A + (int64_t)k0 * ld + k0;
         float a[NB];
 #pragma unroll
         for (int c = 0; c < NB; c += 4) {
             const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
-            a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];        // upper entries are never used
+            a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];
         }
-        int first_bad = -1;                                   // branch-free bookkeeping: one straight-line block
-        float my_rdiag = 1.f;
+        float my_rdiag;
+        potrf64_in_registers(a, lane, S.Lt1, my_rdiag, bad1);
+        S.rd1[lane] = my_rdiag;
+        if (blockIdx.x == 0) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            float piv = lane_bcast(a[j], j);
-            const bool bad = !(piv > 0.f);                    // uniform
-            first_bad = (bad && first_bad < 0) ? j : first_bad;
-            piv = bad ? 1.f : piv;
-            const float r = __builtin_amdgcn_rsqf(piv);       // 1 ulp reciprocal square root
-            my_rdiag = (lane == j) ? r : my_rdiag;            // 1 / l_jj
-            a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
+            for (int c = 0; c < NB; c += 4) {
+                gemm::floatx4 v;
 #pragma unroll
-            for (int c = j + 1; c < NB; ++c) {
-                a[c] -= a[j] * lane_bcast(a[j], c);
-                // bound how many broadcast values (scalar registers) are alive at once
-                if ((c & 15) == 15) __builtin_amdgcn_sched_barrier(0);
+                for (int e = 0; e < 4; ++e) v[e] = (c + e <= lane) ? a[c + e] : 0.f;
+                *reinterpret_cast<gemm::floatx4 *>(Ldiag + lane * NB + c) = v;
             }
-            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int c = 0; c < NB; c += 4) {
-            gemm::floatx4 v;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] = (c + e <= lane) ? a[c + e] : 0.f;
-            *reinterpret_cast<gemm::floatx4 *>(&Ls[lane][c]) = v;
-            if (blockIdx.x == 0) *reinterpret_cast<gemm::floatx4 *>(Ldiag + lane * NB + c) = v;
-        }
-        rdiag[lane] = my_rdiag;
-        if (blockIdx.x == 0 && first_bad >= 0 && lane == 0 && *info == 0) *info = 1 + k0 + first_bad;
     } else {
-        // 128 rows x 16 pieces of four floats, 16 consecutive lanes per row
-        for (int e = tid - 64; e < PANEL_ROWS * (NB / 4); e += PANEL_THREADS - 64) {
-            const int r = e >> 4, c4 = e & 15;
+        const int t = tid - 64, nt = PANEL_THREADS - 64;
+        // A21 and A22 of the diagonal block: 64 rows x 16 pieces of four floats each
+        for (int e = t; e < 2 * NB * (NB / 4); e += nt) {
+            const int which = e >> 10, r = (e >> 4) & 63, c4 = e & 15;
+            const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)(NB + r) * ld + which * NB + 4 * c4);
+            float *dst = which ? &S.D22[r][4 * c4] : &S.Lm[r][4 * c4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dst[q] = v[q];
+        }
+        // the workgroup's rows: 128 rows x 32 pieces, 32 consecutive lanes per row
+        for (int e = t; e < PANEL_ROWS * (PW / 4); e += nt) {
+            const int r = e >> 5, c4 = e & 31;
             gemm::floatx4 v = {0.f, 0.f, 0.f, 0.f};
             if (row0 + r < rows) v = *reinterpret_cast<const gemm::floatx4 *>(Xg + (int64_t)r * ld + 4 * c4);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) Xs[r][4 * c4 + q] = v[q];
+            for (int q = 0; q < 4; ++q) S.Xs[r][4 * c4 + q] = v[q];
         }
     }
     __syncthreads();
-    if (tid < PANEL_ROWS && row0 + tid < rows) {
+
+    // ---- against L11: the block below it (wavefront 1) and the first half of the workgroup's rows (wavefronts 2, 3)
+    if (wave >= 1) {
+        float *rowp = (wave == 1) ? &S.Lm[lane][0] : &S.Xs[tid - 128][0];
         float x[NB];
 #pragma unroll
-        for (int c = 0; c < NB; ++c) x[c] = Xs[tid][c];
+        for (int c = 0; c < NB; ++c) x[c] = rowp[c];
+        solve_row_in_registers(x, S.Lt1, S.rd1);
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            float sum = x[j];
-#pragma unroll
-            for (int k4 = 0; k4 < (j + 3) / 4; ++k4) {
-                const gemm::floatx4 l = *reinterpret_cast<const gemm::floatx4 *>(&Ls[j][4 * k4]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (4 * k4 + e < j) sum -= x[4 * k4 + e] * l[e];
-            }
-            x[j] = sum * rdiag[j];
-        }
-#pragma unroll
-        for (int c = 0; c < NB; ++c) Xs[tid][c] = x[c];
+        for (int c = 0; c < NB; ++c) rowp[c] = x[c];
     }
     __syncthreads();
-    for (int e = tid; e < PANEL_ROWS * (NB / 4); e += PANEL_THREADS) {
-        const int r = e >> 4, c4 = e & 15;
+
+    // ---- matrix cores: D22 -= L21 L21^T (lower 32 x 32 tiles) and Xs[:, 64:128] -= Xs[:, 0:64] L21^T
+    for (int tile = wave; tile < 11; tile += 4) {
+        if (tile < 3) {
+            const int ti = (tile == 0) ? 0 : 1, tj = (tile == 2) ? 1 : 0;
+            tile_downdate(&S.Lm[0][0], PITCH_B, 32 * ti, &S.Lm[0][0], PITCH_B, 32 * tj, &S.D22[0][0], PITCH_B, 32 * ti, 32 * tj, lane);
+        } else {
+            const int q = tile - 3, rt = q >> 1, ct = q & 1;
+            tile_downdate(&S.Xs[0][0], PITCH_X, 32 * rt, &S.Lm[0][0], PITCH_B, 32 * ct, &S.Xs[0][0], PITCH_X, 32 * rt, NB + 32 * ct, lane);
+        }
+    }
+    __syncthreads();
+
+    // ---- second diagonal block in registers
+    if (wave == 0) {
+        float a[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) a[c] = S.D22[lane][c];
+        float my_rdiag;
+        potrf64_in_registers(a, lane, S.Lt2, my_rdiag, bad2);
+        S.rd2[lane] = my_rdiag;
+        if (blockIdx.x == 0) {
+#pragma unroll
+            for (int c = 0; c < NB; c += 4) {
+                gemm::floatx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (c + e <= lane) ? a[c + e] : 0.f;
+                *reinterpret_cast<gemm::floatx4 *>(Ldiag + NB * NB + lane * NB + c) = v;
+            }
+        }
+        if (blockIdx.x == 0 && lane == 0 && *info == 0) {
+            if (bad1 >= 0) *info = 1 + k0 + bad1;
+            else if (bad2 >= 0) *info = 1 + k0 + NB + bad2;
+        }
+    }
+    __syncthreads();
+
+    // ---- against L22: second half of the workgroup's rows; workgroup 0 meanwhile stores the diagonal factor
+    if (tid < PANEL_ROWS) {
+        float *rowp = &S.Xs[tid][NB];
+        float x[NB];
+#pragma unroll
+        for (int c = 0; c < NB; ++c) x[c] = rowp[c];
+        solve_row_in_registers(x, S.Lt2, S.rd2);
+#pragma unroll
+        for (int c = 0; c < NB; ++c) rowp[c] = x[c];
+    } else if (blockIdx.x == 0) {
+        for (int e = tid - PANEL_ROWS; e < NB * NB; e += PANEL_THREADS - PANEL_ROWS) {
+            Loff[e] = S.Lm[e >> 6][e & 63];
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < PANEL_ROWS * (PW / 4); e += PANEL_THREADS) {
+        const int r = e >> 5, c4 = e & 31;
         if (row0 + r < rows) {
             gemm::floatx4 v;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = Xs[r][4 * c4 + q];
+            for (int q = 0; q < 4; ++q) v[q] = S.Xs[r][4 * c4 + q];
             *reinterpret_cast<gemm::floatx4 *>(Xg + (int64_t)r * ld + 4 * c4) = v;
         }
     }
+}
+
+// Puts the blocks L21 of all diagonal 128 x 128 blocks (kept aside by panel_kernel) into the factor:
+// A[k0 + 64 + r][k0 + c] = Loff[k0 / 128][r][c].
+__global__ __launch_bounds__(256) void place_offdiag_kernel(float *__restrict__ A, int ld, const float *__restrict__ Loff) {
+    const int k0 = blockIdx.x * PW;
+    const float *src = Loff + (size_t)blockIdx.x * NB * NB;
+    for (int e = threadIdx.x; e < NB * NB; e += 256) A[(int64_t)(k0 + NB + (e >> 6)) * ld + k0 + (e & 63)] = src[e];
 }
 
 // Inverses of all factored 64 x 64 diagonal blocks at once (off the factorisation's critical path):
@@ -197,7 +333,7 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
 
 struct HinvLayout {
     int dp;
-    float *A, *T, *S, *dinv, *ldiag;
+    float *A, *T, *S, *dinv, *ldiag, *loff;
     double *lambda;
     int *info;
     size_t bytes;
@@ -212,7 +348,8 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.T = c.take<float>(n2);
     l.S = c.take<float>(n2);
     l.dinv = c.take<float>((size_t)(l.dp / NB) * NB * NB);
-    l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored diagonal blocks
+    l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored 64 x 64 diagonal blocks
+    l.loff = c.take<float>((size_t)(l.dp / PW) * NB * NB);    // the block below the first one in every 128 x 128
     l.lambda = c.take<double>(1);
     l.info = c.take<int>(1);
     l.bytes = c.off;
@@ -242,24 +379,31 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.A, dp, l.lambda);
     ZIPLM_HIP_TRY(hipGetLastError());
 
-    // ---- A = L L^T, right-looking over 64-column panels --------------------------------------
-    for (int k0 = 0; k0 < dp; k0 += NB) {
-        const int rest = dp - k0 - NB;
-        // diagonal block factored and the panel below it solved, L21 = A21 inv(L11)^T, in one launch
+    // ---- A = L L^T, right-looking over 128-column panels: one panel launch, one trailing update ----
+    static bool panel_attr_set = false;
+    if (!panel_attr_set) {
+        ZIPLM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                          (int)sizeof(PanelLds)));
+        panel_attr_set = true;
+    }
+    for (int k0 = 0; k0 < dp; k0 += PW) {
+        const int rest = dp - k0 - PW;
         const int pblocks = rest > 0 ? (rest + PANEL_ROWS - 1) / PANEL_ROWS : 1;
-        hipLaunchKernelGGL(panel_kernel, dim3(pblocks), dim3(PANEL_THREADS), 0, st, l.A, dp, k0, rest,
-                           l.ldiag + (size_t)(k0 / NB) * NB * NB, l.info);
+        hipLaunchKernelGGL(panel_kernel, dim3(pblocks), dim3(PANEL_THREADS), sizeof(PanelLds), st, l.A, dp, k0, rest,
+                           l.ldiag + (size_t)(k0 / NB) * NB * NB, l.loff + (size_t)(k0 / PW) * NB * NB, l.info);
+        ZIPLM_HIP_TRY(hipGetLastError());
         if (rest <= 0) break;
-        float *A21 = l.A + (int64_t)(k0 + NB) * dp + k0;
+        float *A21 = l.A + (int64_t)(k0 + PW) * dp + k0;
         // A22 -= L21 L21^T, lower tiles only
         Args u = {};
         u.A = A21; u.lda = dp;
         u.B = A21; u.ldb = dp;
-        u.C = l.A + (int64_t)(k0 + NB) * dp + (k0 + NB); u.ldc = dp;
-        u.M = rest; u.N = rest; u.K = NB;
+        u.C = l.A + (int64_t)(k0 + PW) * dp + (k0 + PW); u.ldc = dp;
+        u.M = rest; u.N = rest; u.K = PW;
         u.alpha = -1.f; u.beta = 1.f; u.flags = F_TRI_GRID;
         ZIPLM_HIP_TRY((launch<K_CONTIG, K_CONTIG, true, false>(u, 1, st)));
     }
+    hipLaunchKernelGGL(place_offdiag_kernel, dim3(dp / PW), dim3(256), 0, st, l.A, dp, l.loff);
 
     // ---- T = L^-1: leaves (all diagonal blocks in one launch), then pairwise merges -------------------
     hipLaunchKernelGGL(trtri_diag_kernel, dim3(dp / NB), dim3(64), 0, st, l.ldiag, l.dinv);
