@@ -162,3 +162,55 @@ def test_config3_module_error_equals_sum_of_step_errors(z):
     assert abs(float(err.sum()) / float(total[0]) - 1.0) <= 1e-4
     p = p.cpu().numpy()
     assert abs(p[-1] - 1.0) <= 1e-4 and np.all(np.diff(p) >= -1e-12)
+
+
+def _pipeline_against_oracle(z, oracle, spec, kind):
+    """Hessian, inverse and the greedy loop of one benchmark configuration at its full size: the Hessian
+    against the fp64 definition, the inverse against the oracle's, the loop through the complete protocol
+    on the device's own fp32 inverse with the paper's database grid as snapshots."""
+    d, m, g, G = spec.d_col, spec.d_row, spec.group_size, spec.n_groups
+    X = workloads.make_X(spec)
+    W32 = workloads.make_W(spec)
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H, torch.from_numpy(X).cuda(), 2.0)
+    Hh = H.cpu().numpy()
+    H_or = oracle.hessian(X, 2.0)
+    dg = np.sqrt(np.diag(H_or))
+    assert (np.abs(Hh - H_or) / np.outer(dg, dg)).max() <= 1e-5
+    assert np.array_equal(Hh, Hh.T)
+
+    Hi, lam = z.ziplm_hinv(H, spec.damp_rel)
+    Hi32 = Hi.cpu().numpy()
+    Hi_or, lam_or = oracle.hinv(Hh, spec.damp_rel)           # same fp32 Hessian, fp64 inverse
+    assert lam == pytest.approx(lam_or, rel=1e-5)
+    assert rel_fro(Hi32, Hi_or) <= REL_TOL
+    assert (np.abs(np.diag(Hi32) - np.diag(Hi_or)) / np.diag(Hi_or)).max() <= REL_TOL
+
+    snaps = z.database_steps(G, kind)
+    Wd = torch.from_numpy(W32).cuda()
+    order, err, W_snap = z.ziplm_structured_obs_prune(Wd, Hi, g, G, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    order_h, err_h = order.cpu().numpy(), err.cpu().numpy()
+    assert sorted(order_h.tolist()) == list(range(G))
+    assert float(Wd.abs().max()) == 0.0 and float(Hi.abs().max()) == 0.0
+    ref = compare_run(oracle, W32, Hi32, g, G, order_h, err_h, snap_steps=snaps)
+    for q, k in enumerate(snaps):
+        assert rel_fro(W_snap[q].cpu().numpy(), ref["W_snap"][q]) <= REL_TOL, "W after %d removals" % k
+    return ref
+
+
+def test_config1_full_pipeline_matches_oracle(z, oracle):
+    """Configuration 1: toy layer 256 x 1024, 2048 Gaussian tokens, all 1024 columns removed."""
+    _pipeline_against_oracle(z, oracle, workloads.config(1), "columns")
+
+
+def test_config2_full_pipeline_matches_oracle(z, oracle):
+    """Configuration 2: attention output projection 768 x 768, twelve heads of 64 columns, all removed."""
+    _pipeline_against_oracle(z, oracle, workloads.config(2), "heads")
+
+
+def test_config5_first_layer_matches_oracle(z, oracle):
+    """Configuration 5 (the 12-layer sweep, 32768 tokens per problem): both problems of its first layer.
+    The other layers differ only in their seeds."""
+    _pipeline_against_oracle(z, oracle, workloads.config(5, layer=0, kind="attn"), "heads")
+    _pipeline_against_oracle(z, oracle, workloads.config(5, layer=0, kind="ffn"), "columns")
