@@ -12,10 +12,11 @@
 // and the pass over Hd refreshes a compact copy of its diagonal, so a step reads the state once.
 // Rows of Hd that belong to removed columns are skipped; removed columns are masked per lane.
 //
-// Larger structures (2 <= group_size <= 64): a short sequence of ordinary launches per step
-//     score (one workgroup per live structure: block inverse in LDS, Gram contraction)
-//     -> select -> prepare (C_H = Hd[:,S] B, C_W = W[:,S] B) -> update,
-// with the selected index handed from kernel to kernel in device memory.
+// Larger structures (2 <= group_size <= 64): two ordinary launches per step,
+//     score  (one workgroup per live structure: block inverse in LDS, Gram contraction)
+//     update (every workgroup picks the cheapest structure itself from the scores and forms the coefficients
+//             C_H = Hd[:,S] B, C_W = W[:,S] B of its own rows on the fly),
+// because on this machine a dependent launch costs more than the arithmetic of a step.
 #include <hip/hip_cooperative_groups.h>
 
 #include <stdlib.h>
@@ -66,9 +67,7 @@ struct PruneState {
     // group path
     double *score;       // [G]
     double *Binv;        // [G][g*g]
-    double *CH;          // [d][g]
-    double *CW;          // [m][g]
-    int *sel;            // selected structure of the current step
+    int *dead_step;      // [G] step at which the structure was removed; kNever while alive, -1 if it came in removed
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -148,7 +147,8 @@ __device__ __forceinline__ void snapshot_copy(const PruneState &P, int removed, 
         const size_t total = (size_t)P.m * P.d;
         for (size_t idx = gtid; idx < total; idx += gthreads) {
             const int j = (int)(idx % P.d);
-            dst[idx] = P.alive[j / P.g] ? P.W[idx] : 0.f;
+            const bool live = P.dead_step ? (P.dead_step[j / P.g] >= removed) : (P.alive[j / P.g] != 0);
+            dst[idx] = live ? P.W[idx] : 0.f;
         }
         q = P.snap_next[q];
     }
@@ -290,13 +290,16 @@ __global__ __launch_bounds__(PT) void prune_columns_kernel(PruneState P) {
 // group_size > 1: per-step launches
 // ---------------------------------------------------------------------------------------------
 constexpr int GMAX = 64;
+constexpr int kNever = 0x7fffffff;
+// Structure s takes part in step t iff dead_step[s] >= t.  The workgroup that records the removal of step t
+// writes t, which a workgroup still choosing step t's structure reads as "alive" just like the old value:
+// all workgroups of a launch see the same set whatever the timing.
 
 __global__ __launch_bounds__(256) void group_init_kernel(PruneState P) {
     const int gtid = blockIdx.x * 256 + threadIdx.x, gthreads = gridDim.x * 256;
     const size_t total = (size_t)P.d * P.d;
     for (size_t idx = gtid; idx < total; idx += gthreads) P.Hd[idx] = (double)P.Hinv[idx];
-    for (int s = gtid; s < P.G; s += gthreads) P.alive[s] = P.alive_in ? (P.alive_in[s] != 0) : 1;
-    if (gtid == 0) *P.sel = -1;
+    for (int s = gtid; s < P.G; s += gthreads) P.dead_step[s] = (P.alive_in && P.alive_in[s] == 0) ? -1 : kNever;
 }
 
 typedef double doublex4 __attribute__((ext_vector_type(4)));
@@ -317,7 +320,7 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step
     const int s = blockIdx.x, tid = threadIdx.x, g = P.g, d = P.d;
     const int lane = tid & 63, wave = tid >> 6, q4 = lane >> 4, cl16 = lane & 15;
     if (*P.status != 0) return;
-    if (!P.alive[s]) {
+    if (P.dead_step[s] < step) {
         if (tid == 0) P.score[s] = 0.0;
         return;
     }
@@ -425,69 +428,76 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step
     if (tid == 0) P.score[s] = red[0];
 }
 
-__global__ __launch_bounds__(256) void group_select_kernel(PruneState P, int step) {
+// Second (and last) launch of a step.  Every workgroup finds the cheapest live structure p itself from the
+// scores (lowest index on ties; the same inputs give the same answer everywhere; workgroup 0 records it), takes
+// B = (Hd[S,S])^-1 of that structure as left by the scoring launch, and for each of its 16-row tiles forms the
+// coefficients  C = rows[:, S] B  on the fly before applying
+//     Hd[i][j] -= sum_b C_H[i][b] Hd[S_b][j]   and   W[i][j] -= sum_b C_W[i][b] Hd[S_b][j]   (Eq. 4, Eq. 3).
+// Rows and columns of the selected structure and of earlier removed ones are left alone (they are zeroed at
+// the end), so the rows Hd[S,:] and the columns Hd[:,S] read here are the pre-step ones for every workgroup.
+constexpr int G_ROWS = 16;
+__global__ __launch_bounds__(256) void group_update_kernel(PruneState P, int step) {
+    __shared__ double Bs[GMAX][GMAX];         // B of the selected structure
+    __shared__ double As[G_ROWS][GMAX + 1];   // this tile's rows restricted to the columns of S
+    __shared__ double Cs[G_ROWS][GMAX];       // this tile's rows of C_H or C_W
     __shared__ double sh_s[4];
     __shared__ int sh_i[4];
     if (*P.status != 0) return;
-    double s = 0.0;
-    int idx = -1;
-    for (int q = threadIdx.x; q < P.G; q += 256) {
-        if (!P.alive[q]) continue;
+    const int g = P.g, d = P.d, m = P.m, tid = threadIdx.x;
+    double best = 0.0;
+    int p = -1;
+    for (int q = tid; q < P.G; q += 256) {
+        if (P.dead_step[q] < step) continue;
         const double v = P.score[q];
-        if (better(v, q, s, idx)) { s = v; idx = q; }
+        if (better(v, q, best, p)) { best = v; p = q; }
     }
-    block_argmin<256>(s, idx, sh_s, sh_i);
-    if (threadIdx.x == 0) {
-        if (idx < 0) { *P.status = 1 + step; return; }
-        *P.sel = idx;
-        P.order[step] = idx;
-        P.err[step] = s;
-        P.alive[idx] = 0;
+    block_argmin<256>(best, p, sh_s, sh_i);
+    if (p < 0) {                                   // nothing left to remove: the request was impossible
+        if (blockIdx.x == 0 && tid == 0) *P.status = 1 + step;
+        return;
     }
-}
-
-// C_H[i][b] = sum_a Hd[i][S_a] B[a][b] for every row i of Hd; C_W[i][b] likewise for W.
-__global__ __launch_bounds__(256) void group_prepare_kernel(PruneState P) {
-    if (*P.status != 0) return;
-    const int g = P.g, d = P.d, p = *P.sel, c0 = p * g;
+    if (blockIdx.x == 0 && tid == 0) {
+        P.order[step] = p;
+        P.err[step] = best;
+        P.dead_step[p] = step;
+    }
+    const int c0 = p * g;
     const double *B = P.Binv + (size_t)p * g * g;
-    const int total = (d + P.m) * g;
-    for (int e = blockIdx.x * 256 + threadIdx.x; e < total; e += gridDim.x * 256) {
-        const int i = e / g, b = e % g;
-        double s = 0.0;
-        if (i < d) {
-            for (int a = 0; a < g; ++a) s += P.Hd[(size_t)i * d + c0 + a] * B[a * g + b];
-            P.CH[(size_t)i * g + b] = s;
-        } else {
-            const int iw = i - d;
-            for (int a = 0; a < g; ++a) s += (double)P.W[(size_t)iw * d + c0 + a] * B[a * g + b];
-            P.CW[(size_t)iw * g + b] = s;
-        }
-    }
-}
-
-// Hd[i][j] -= sum_b C_H[i][b] Hd[S_b][j]   and   W[i][j] -= sum_b C_W[i][b] Hd[S_b][j]
-// Rows and columns of the selected structure and of earlier removed ones are left alone (they are
-// zeroed at the end); the rows Hd[S,:] read here are therefore the pre-step ones.
-constexpr int G_ROWS = 16;
-__global__ __launch_bounds__(256) void group_update_kernel(PruneState P) {
-    __shared__ double Cs[G_ROWS][GMAX];       // this tile's rows of C_H or C_W
-    if (*P.status != 0) return;
-    const int g = P.g, d = P.d, m = P.m, p = *P.sel, c0 = p * g;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int i = wave; i < g; i += 4)             // element mapping without divisions: column = lane (g <= 64)
+        if (lane < g) Bs[i][lane] = B[i * g + lane];
     const int ncc = (d + 255) / 256;
     const int n_h_tiles = ((d + G_ROWS - 1) / G_ROWS) * ncc;
     const int n_w_tiles = ((m + G_ROWS - 1) / G_ROWS) * ncc;
     for (int tile = blockIdx.x; tile < n_h_tiles + n_w_tiles; tile += gridDim.x) {
         const bool is_h = tile < n_h_tiles;
         const int tt = is_h ? tile : tile - n_h_tiles;
-        const int i0 = (tt / ncc) * G_ROWS, j = (tt % ncc) * 256 + threadIdx.x;
+        const int i0 = (tt / ncc) * G_ROWS, j = (tt % ncc) * 256 + tid;
         const int rows = is_h ? d : m;
-        const bool live = (j < d) && P.alive[j / g];   // the selected structure is already marked removed
-        const double *C = is_h ? P.CH : P.CW;
+        const int sj = (j < d) ? j / g : 0;
+        const bool live = (j < d) && sj != p && P.dead_step[sj] >= step;
         __syncthreads();
-        for (int e = threadIdx.x; e < G_ROWS * g; e += 256) {
-            const int ii = e / g, b = e % g;
-            Cs[ii][b] = (i0 + ii < rows) ? C[(size_t)(i0 + ii) * g + b] : 0.0;
+        if (lane < g) {
+#pragma unroll
+            for (int q = 0; q < G_ROWS / 4; ++q) {
+                const int ii = wave + 4 * q, i = i0 + ii;
+                double v = 0.0;
+                if (i < rows) v = is_h ? P.Hd[(size_t)i * d + c0 + lane] : (double)P.W[(size_t)i * d + c0 + lane];
+                As[ii][lane] = v;
+            }
+        }
+        __syncthreads();
+        if (lane < g) {
+            double sum[G_ROWS / 4];
+#pragma unroll
+            for (int q = 0; q < G_ROWS / 4; ++q) sum[q] = 0.0;
+            for (int a = 0; a < g; ++a) {
+                const double bv = Bs[a][lane];
+#pragma unroll
+                for (int q = 0; q < G_ROWS / 4; ++q) sum[q] += As[wave + 4 * q][a] * bv;
+            }
+#pragma unroll
+            for (int q = 0; q < G_ROWS / 4; ++q) Cs[wave + 4 * q][lane] = sum[q];
         }
         __syncthreads();
         double acc[G_ROWS];
@@ -504,7 +514,8 @@ __global__ __launch_bounds__(256) void group_update_kernel(PruneState P) {
                 const int i = i0 + ii;
                 if (i >= rows) continue;
                 if (is_h) {
-                    if (!P.alive[i / g]) continue;
+                    const int si = i / g;
+                    if (si == p || P.dead_step[si] < step) continue;
                     P.Hd[(size_t)i * d + j] -= acc[ii];
                 } else {
                     float *w = P.W + (size_t)i * d + j;
@@ -524,11 +535,11 @@ __global__ __launch_bounds__(256) void group_final_kernel(PruneState P) {
     const int d = P.d, g = P.g;
     const size_t totalw = (size_t)P.m * d;
     for (size_t idx = gtid; idx < totalw; idx += gthreads)
-        if (!P.alive[(idx % d) / g]) P.W[idx] = 0.f;
+        if (P.dead_step[(idx % d) / g] != kNever) P.W[idx] = 0.f;
     const size_t total = (size_t)d * d;
     for (size_t idx = gtid; idx < total; idx += gthreads) {
         const int i = (int)(idx / d), j = (int)(idx % d);
-        P.Hinv[idx] = (P.alive[i / g] && P.alive[j / g]) ? (float)P.Hd[idx] : 0.f;
+        P.Hinv[idx] = (P.dead_step[i / g] == kNever && P.dead_step[j / g] == kNever) ? (float)P.Hd[idx] : 0.f;
     }
 }
 
@@ -553,7 +564,6 @@ static PruneLayout prune_layout(int d_row, int d_col, int g, int n_snap, void *w
     s.alive = c.take<uint8_t>((size_t)s.G);
     s.bar = c.take<unsigned>(1);
     s.status = c.take<int>(1);
-    s.sel = c.take<int>(1);
     l.snap_of_step = c.take<int>((size_t)s.G + 1);
     l.snap_next = c.take<int>((size_t)(n_snap > 0 ? n_snap : 1));
     if (g == 1) {
@@ -564,8 +574,7 @@ static PruneLayout prune_layout(int d_row, int d_col, int g, int n_snap, void *w
     } else {
         s.score = c.take<double>((size_t)s.G);
         s.Binv = c.take<double>((size_t)s.G * g * g);
-        s.CH = c.take<double>((size_t)d_col * g);
-        s.CW = c.take<double>((size_t)d_row * g);
+        s.dead_step = c.take<int>((size_t)s.G);
     }
     l.bytes = c.off;
     return l;
@@ -641,8 +650,8 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
         P.snap_of_step = nullptr;
         P.snap_next = nullptr;
     }
-    // bar, status, sel are adjacent 256-byte slots
-    ZIPLM_HIP_TRY(hipMemsetAsync(P.bar, 0, 3 * kAlign, st));
+    // bar and status are adjacent 256-byte slots
+    ZIPLM_HIP_TRY(hipMemsetAsync(P.bar, 0, 2 * kAlign, st));
 
     // the device counts removals against the structures that are alive; an impossible request
     // (n_remove above the live count) shows up as "no candidate" -> status = 1 + step
@@ -659,13 +668,10 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
         hipLaunchKernelGGL(group_init_kernel, dim3(fill), dim3(256), 0, st, P);
         const int ncc = (d_col + 255) / 256;
         const int tiles = ((d_col + G_ROWS - 1) / G_ROWS + (d_row + G_ROWS - 1) / G_ROWS) * ncc;
-        const int prep_blocks = ((d_col + d_row) * group_size + 255) / 256;
         for (int t = 0; t < n_remove; ++t) {
             if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill), dim3(256), 0, st, P, t);
             hipLaunchKernelGGL(group_score_kernel, dim3(G), dim3(256), 0, st, P, t);
-            hipLaunchKernelGGL(group_select_kernel, dim3(1), dim3(256), 0, st, P, t);
-            hipLaunchKernelGGL(group_prepare_kernel, dim3(prep_blocks), dim3(256), 0, st, P);
-            hipLaunchKernelGGL(group_update_kernel, dim3(tiles), dim3(256), 0, st, P);
+            hipLaunchKernelGGL(group_update_kernel, dim3(tiles), dim3(256), 0, st, P, t);
         }
         if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill), dim3(256), 0, st, P, n_remove);
         hipLaunchKernelGGL(group_final_kernel, dim3(fill), dim3(256), 0, st, P);
