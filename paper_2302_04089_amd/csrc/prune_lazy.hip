@@ -28,7 +28,10 @@
 //      between stores ("flag in data"); buffers alternate with the step parity.
 //   2. every workgroup reads all candidates, takes the argmin (lowest index on ties), reads the
 //      winner's payload, forms its slice of the current pivot row, updates its diagonal entries,
-//      compensates its columns of W and refreshes their norms and scores.
+//      compensates its columns of W and refreshes their norms and scores.  The wavefront that reports the
+//      last of these scores publishes the workgroup's candidate for the next step at once: the barrier that
+//      ends the step also waits for the step's global stores to be acknowledged, and a candidate held back
+//      until then would reach the other workgroups most of a microsecond later.
 //
 // One exchange per step is the only device-wide synchronisation; every 64 steps one barrier makes the
 // finished block of pending rows visible.  When a workgroup owns at most 16 columns the flush of that
@@ -434,6 +437,15 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     }
     __syncthreads();
 
+    if (tid == 0) {
+        int n = 0;
+        for (int jl = 0; jl < nown; ++jl) n += alive_own[jl] ? 1 : 0;
+        misc[5] = n;
+    }
+    __syncthreads();
+    int nlive = misc[5];        // live owned columns (uniform)
+    bool slot_early = false;    // the slot of the coming step was already published at the end of the last one
+
     unsigned long long bar_epoch = 0;
     int k = 0;          // pending pivot rows
     int ublk = 0;       // which half of U the current block of steps writes
@@ -512,7 +524,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         const int cand = (key_idx == ENC_NONE) ? IDX_NONE : (key_idx == ENC_ERROR) ? IDX_ERROR : j0 + (int)key_idx;
         const double cand_score_trunc = __longlong_as_double((long long)(key & ~0xfffull));
         if (tid == 0) {
-            __hip_atomic_store(S.slots + (size_t)par * nb + b, key | tag4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!slot_early)
+                __hip_atomic_store(S.slots + (size_t)par * nb + b, key | tag4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #ifdef ZIPLM_LAZY_TIMING
             tlocal += wall_clock64() - texch;
 #endif
@@ -591,7 +604,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         if (misc[0]) { ok = false; break; }
         if (misc[2] || p < 0) { error_step = 1 + t; break; }   // same inputs in every workgroup: uniform
         const int owner = (int)(((unsigned long long)(unsigned)p * cpb_magic) >> 32);      // p / cpb
-        if (tid == 0) *cand_key = KEY_NONE;       // every thread read it before the barrier of the exchange
+        if (tid == 0) { *cand_key = KEY_NONE; misc[6] = 0; }   // every thread read the key before the barrier of the exchange
         if (owner == b && !published) publish_payload(p);
 
         // ---------------------------------------------------------- 3. winner's payload + stale column p
@@ -633,6 +646,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         if (misc[0]) { ok = false; break; }
         const double piv = misc_d[1], rpiv = misc_d[2];
         const bool unflushed = misc[4] != 0;
+        // columns that will report a new score in step 4; the last one to do so publishes the workgroup's
+        // slot of the next step at once, without waiting for the barrier and the loop head
+        const int participants = nlive - (owner == b ? 1 : 0);
+        const bool more_steps = t + 1 < S.n_remove;
         if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = score[p - j0]; }   // exact score, not the truncated one
         if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; }
 
@@ -673,8 +690,17 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 norm[jl] = s;
                 score[jl] = sc;
                 atomicMin(cand_key, (dj > 0.0) ? cand_key_of(sc, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
+                if (atomicAdd(&misc[6], 1) == participants - 1 && more_steps) {
+                    // LDS serves one wavefront's operations in order: every column's minimum is in
+                    const unsigned long long knext = *reinterpret_cast<volatile unsigned long long *>(cand_key);
+                    const unsigned tag4_next = (tag4 == 15u) ? 1u : tag4 + 1u;
+                    __hip_atomic_store(S.slots + (size_t)((t + 1) & 1) * nb + b, knext | tag4_next, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
+        slot_early = participants > 0 && more_steps;
+        if (owner == b) --nlive;
         ++k;
         __syncthreads();
         TICK(4);
