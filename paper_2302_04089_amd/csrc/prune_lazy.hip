@@ -180,6 +180,12 @@ __device__ __forceinline__ bool slot_wait(const unsigned long long *p, unsigned 
     }
 }
 
+// A value that is the same in every lane, moved to scalar registers (frees two vector registers).
+__device__ __forceinline__ unsigned long long uniform_u64(unsigned long long v) {
+    return ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+           (unsigned)__builtin_amdgcn_readfirstlane((int)(v & 0xffffffffu));
+}
+
 __device__ __forceinline__ unsigned dhi(double x) { return (unsigned)((unsigned long long)__double_as_longlong(x) >> 32); }
 __device__ __forceinline__ unsigned dlo(double x) { return (unsigned)((unsigned long long)__double_as_longlong(x) & 0xffffffffu); }
 __device__ __forceinline__ double dmake(unsigned hi, unsigned lo) {
@@ -241,7 +247,7 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, misc, wt, total;
+    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, rpivs, rpivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, misc, wt, total;
 };
 __host__ __device__ inline int padded_rows(int m) { return (m + 255) / 256 * 256; }   // Eq. 3 runs unguarded
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
@@ -258,6 +264,8 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.cvec = take(sizeof(double) * BMAX);                // u_k[p] / piv_k for the current pivot
     l.cprev = take(sizeof(double) * BMAX);               // the same over the previous block's rows
     l.pivprev = take(sizeof(double) * BMAX);
+    l.rpivs = take(sizeof(double) * BMAX);               // reciprocals of the pivots of the pending rows
+    l.rpivprev = take(sizeof(double) * BMAX);
     l.seq_done = take(sizeof(int) * NW);                 // column tiles each background wavefront has finished
     l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
     l.wcol = take(mp * sizeof(float));                   // column p of W, zero beyond row m
@@ -285,7 +293,12 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
                                                       const double *uloc, const double *pivs, double *coefa,
                                                       const int *alive_own, const unsigned *alive_bits,
                                                       int k, int d, int cp) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // This runs once per 64 steps at most.  The thread index is made opaque here so that the address arithmetic
+    // below is redone on entry instead of being hoisted out of the step loop, where it would hold vector
+    // registers through every step.
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63, wave = tid >> 6;
     const int q4 = lane >> 4, cl16 = lane & 15;
     const int nks = (k + 3) / 4;
     for (int g0 = 0; g0 < cp; g0 += RG) {
@@ -320,7 +333,7 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
                     const int kk = 4 * (h + e) + q4;
 #pragma unroll
                     for (int x = 0; x < NTI; ++x)
-                        bv[x][e] = (kk < k && col_ok[x]) ? ub[(size_t)(h + e) * 4 * d + c[x]] : 0.0;
+                        bv[x][e] = (kk < k && col_ok[x]) ? __hip_atomic_load(ub + (size_t)(h + e) * 4 * d + c[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
@@ -371,6 +384,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     double *cvec = reinterpret_cast<double *>(smem + L.cvec);
     double *cprev = reinterpret_cast<double *>(smem + L.cprev);
     double *pivprev = reinterpret_cast<double *>(smem + L.pivprev);
+    double *rpivs = reinterpret_cast<double *>(smem + L.rpivs);
+    double *rpivprev = reinterpret_cast<double *>(smem + L.rpivprev);
     int *seq_done = reinterpret_cast<int *>(smem + L.seq_done);
     double *pivs = reinterpret_cast<double *>(smem + L.pivs);
     float *wcol = reinterpret_cast<float *>(smem + L.wcol);
@@ -444,6 +459,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     }
     __syncthreads();
     int nlive = misc[5];        // live owned columns (uniform)
+    // bit r: owned column wave + NW * r is alive -- what alive_own says, without a dependent LDS read at the head
+    // of step 4 (every such read on the path from the exchange to the next slot costs a fifth of a microsecond)
+    unsigned my_live = 0;
+    for (int jl = wave, r = 0; jl < nown; jl += NW, ++r) my_live |= (alive_own[jl] ? 1u : 0u) << r;
     bool slot_early = false;    // the slot of the coming step was already published at the end of the last one
 
     unsigned long long bar_epoch = 0;
@@ -481,7 +500,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         }
         double bv[BG_KS];
 #pragma unroll
-        for (int e = 0; e < BG_KS; ++e) bv[e] = col_ok ? ub[(size_t)(part * BG_KS + e) * 4 * d] : 0.0;
+        for (int e = 0; e < BG_KS; ++e)
+            bv[e] = col_ok ? __hip_atomic_load(ub + (size_t)(part * BG_KS + e) * 4 * d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
 #pragma unroll
         for (int e = 0; e < BG_KS; ++e)
             acc = __builtin_amdgcn_mfma_f64_16x16x4f64(coefbg[(part * BG_KS + e) * 64 + lane], bv[e], acc, 0, 0, 0);
@@ -601,8 +621,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
 #ifdef ZIPLM_LAZY_TIMING
         if (tid == 0) texch = wall_clock64();
 #endif
-        if (misc[0]) { ok = false; break; }
-        if (misc[2] || p < 0) { error_step = 1 + t; break; }   // same inputs in every workgroup: uniform
+        // A dependent LDS read costs a fifth of a microsecond on this path: the time-out and error flags of the
+        // exchange are looked at after step 3 (p is a valid column or "none" whatever they say).
+        if (p < 0) { error_step = 1 + t; break; }              // same inputs in every workgroup: uniform
         const int owner = (int)(((unsigned long long)(unsigned)p * cpb_magic) >> 32);      // p / cpb
         if (tid == 0) { *cand_key = KEY_NONE; misc[6] = 0; }   // every thread read the key before the barrier of the exchange
         if (owner == b && !published) publish_payload(p);
@@ -621,7 +642,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 const int kk = tid - (LT - 3 * BMAX);
                 unsigned hi, lo;
                 if (!ll_wait2(pw + m + 2 * BMAX + 2 + 2 * kk, tag, hi, lo, S.status)) fail = true;
-                else cprev[kk] = dmake(hi, lo) / pivprev[kk];
+                else cprev[kk] = dmake(hi, lo) * rpivprev[kk];
             }
             for (int i = tid; i < m; i += LT) {
                 unsigned v;
@@ -632,33 +653,46 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 const int kk = tid - (LT - BMAX);
                 unsigned hi, lo;
                 if (!ll_wait2(pw + m + 2 * kk, tag, hi, lo, S.status)) fail = true;
-                else cvec[kk] = dmake(hi, lo) / pivs[kk];
+                else cvec[kk] = dmake(hi, lo) * rpivs[kk];
             }
             if (tid == LT - BMAX - 1) {
                 unsigned hi, lo;
                 if (!ll_wait2(pw + m + 2 * BMAX, tag, hi, lo, S.status)) fail = true;
-                else { const double pv = dmake(hi, lo); misc_d[1] = pv; misc_d[2] = 1.0 / pv; }
+                else {
+                    // reciprocal by two Newton steps from the hardware estimate: short enough not to hold up the barrier
+                    const double pv = dmake(hi, lo);
+                    double r = __builtin_amdgcn_rcp(pv);
+                    r = __builtin_fma(__builtin_fma(-pv, r, 1.0), r, r);
+                    r = __builtin_fma(__builtin_fma(-pv, r, 1.0), r, r);
+                    misc_d[1] = pv;
+                    misc_d[2] = r;
+                }
             }
             if (fail) misc[0] = 1;
             __syncthreads();
         }
         TICK(3);
-        if (misc[0]) { ok = false; break; }
+        const int flag_fail = misc[0], flag_err = misc[2], flag_unflushed = misc[4];    // one round trip for all five
         const double piv = misc_d[1], rpiv = misc_d[2];
-        const bool unflushed = misc[4] != 0;
+        if (flag_fail) { ok = false; break; }
+        if (flag_err) { error_step = 1 + t; break; }
+        const bool unflushed = flag_unflushed != 0;
         // columns that will report a new score in step 4; the last one to do so publishes the workgroup's
         // slot of the next step at once, without waiting for the barrier and the loop head
         const int participants = nlive - (owner == b ? 1 : 0);
         const bool more_steps = t + 1 < S.n_remove;
         if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = score[p - j0]; }   // exact score, not the truncated one
-        if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; }
+        if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; rpivs[k] = rpiv; }
 
         // ---------------------------------------------------------- 4. own slice of the pivot row, Eq. 3
-        for (int jl = wave; jl < nown; jl += NW) {
-            if (!alive_own[jl]) continue;                       // wave-uniform
+        for (int jl = wave, r = 0; jl < nown; jl += NW, ++r) {
+            // wave-uniform; with W in the workspace the kernel has no register to spare for what the early
+            // answer lets the compiler hoist, and asks LDS instead
+            if (W_IN_LDS ? !((my_live >> r) & 1u) : !alive_own[jl]) continue;
             const int j = j0 + jl;
             if (j == p) {
                 if (lane == 0) alive_own[jl] = 0;
+                my_live &= ~(1u << r);
                 continue;
             }
             double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
@@ -685,7 +719,13 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 uloc[jl * BMAX + k] = u;
                 __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const double dj = diag[jl] - u * f;
-                const double sc = s / dj;
+                // s / dj by Newton steps from the hardware reciprocal estimate plus one correction of the quotient: a
+                // third of the instructions of a full division, on the path that decides when the next slot goes out
+                double rd = __builtin_amdgcn_rcp(dj);
+                rd = __builtin_fma(__builtin_fma(-dj, rd, 1.0), rd, rd);
+                rd = __builtin_fma(__builtin_fma(-dj, rd, 1.0), rd, rd);
+                double sc = s * rd;
+                sc = __builtin_fma(__builtin_fma(-dj, sc, s), rd, sc);
                 diag[jl] = dj;
                 norm[jl] = s;
                 score[jl] = sc;
@@ -732,7 +772,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 }
                 if (fail) misc[0] = 1;
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            // No acquire fence: the pending rows are the only data of other workgroups read after this barrier,
+            // and they are read with device-scope loads (an invalidation of the L2 here costs a third of a
+            // microsecond per step, mostly in refetching this workgroup's own panel).
             __syncthreads();
             TICK(5);
             if (misc[0]) { ok = false; break; }
@@ -740,7 +782,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             if (bg_enabled && k == BMAX && t + 1 < S.n_remove) {
                 // hand this block to the background: keep its owned slices, pivots and A fragments
                 for (int e = tid; e < BMAX * cp; e += LT) uprev[e] = uloc[e];
-                if (tid < BMAX) pivprev[tid] = pivs[tid];
+                if (tid < BMAX) { pivprev[tid] = pivs[tid]; rpivprev[tid] = rpivs[tid]; }
                 for (int e = tid; e < AFRAG; e += LT) {
                     const int l = e & 63, kk = 4 * (e >> 6) + (l >> 4);
                     const int arow = 4 * (l & 3) + ((l & 15) >> 2);
