@@ -247,7 +247,7 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, rpivs, rpivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, red_s, misc, wt, total;
+    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, rpivs, rpivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, misc, wt, total;
 };
 __host__ __device__ inline int padded_rows(int m) { return (m + 255) / 256 * 256; }   // Eq. 3 runs unguarded
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
@@ -276,7 +276,6 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.alive_own = take(sizeof(int) * cp);
     l.alive_bits = take(sizeof(unsigned) * ((d + 31) / 32));
     l.snap_bits = take(sizeof(unsigned) * ((d + 32) / 32 + 1));
-    l.red_s = take(sizeof(unsigned long long) * NW);     // per-wavefront minima of the candidate keys
     l.misc = take(96);
     l.wt = take(w_in_lds ? sizeof(float) * (size_t)cpb * mp : 0);
     l.total = o;
@@ -397,9 +396,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     int *alive_own = reinterpret_cast<int *>(smem + L.alive_own);
     unsigned *alive_bits = reinterpret_cast<unsigned *>(smem + L.alive_bits);
     unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
-    unsigned long long *red_key = reinterpret_cast<unsigned long long *>(smem + L.red_s);
     int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet
     unsigned long long *cand_key = reinterpret_cast<unsigned long long *>(smem + L.misc + 64);   // best owned column
+    unsigned long long *gkey_min = reinterpret_cast<unsigned long long *>(smem + L.misc + 72);   // arg-min of the exchange
+    unsigned long long *gkey_max = reinterpret_cast<unsigned long long *>(smem + L.misc + 80);
     double *misc_d = reinterpret_cast<double *>(smem + L.misc + 32);  // [1] pivot, [2] 1 / pivot
 
     const int j0 = b * cpb;
@@ -419,7 +419,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         }
         alive_bits[w] = bits;
     }
-    if (tid == 0) { misc[0] = 0; misc[2] = 0; *cand_key = KEY_NONE; }
+    if (tid == 0) { misc[0] = 0; misc[2] = 0; *cand_key = KEY_NONE; *gkey_min = KEY_EMPTY; *gkey_max = 0; }
     for (int w = tid; w < (d + 32) / 32 + 1; w += LT) snap_bits[w] = 0;
     for (int r = tid; r < cp; r += LT) { alive_own[r] = 0; norm[r] = 0.0; diag[r] = 1.0; score[r] = 0.0; hstale[r] = 0.0; }
     for (int e = tid; e < BMAX * cp; e += LT) uloc[e] = 0.0;
@@ -601,17 +601,16 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             const int nwaves_used = min(NW, (nb + 63) / 64);
             if (wave < nwaves_used) {
                 mykey = wave_min_u64(mykey);
-                if (lane == 0) red_key[wave] = mykey;
+                // the smallest key of all slots, and the largest of the per-wavefront minima (next threshold)
+                if (lane == 0) {
+                    atomicMin(gkey_min, mykey);
+                    if (mykey != KEY_EMPTY) atomicMax(gkey_max, mykey);
+                }
             }
             if (fail) misc[0] = 1;
             if (err) misc[2] = 1;
             __syncthreads();
-            unsigned long long kmin = red_key[0], kmax = (red_key[0] == KEY_EMPTY) ? 0ull : red_key[0];
-            for (int w = 1; w < nwaves_used; ++w) {
-                const unsigned long long kw = red_key[w];
-                kmin = umin64(kmin, kw);
-                if (kw != KEY_EMPTY && kw > kmax) kmax = kw;
-            }
+            const unsigned long long kmin = *gkey_min, kmax = *gkey_max;
             p = (kmin == KEY_EMPTY) ? IDX_NONE : (int)(kmin & 0xffffu);
             // next step's publication threshold: the largest of the per-wavefront minima (each over 64
             // workgroups); with a single wavefront of candidates everybody keeps publishing
@@ -672,17 +671,15 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             __syncthreads();
         }
         TICK(3);
-        const int flag_fail = misc[0], flag_err = misc[2], flag_unflushed = misc[4];    // one round trip for all five
+        // One LDS round trip for all five; the two failure flags are acted on after step 4 (a branch here would
+        // keep the column wavefronts from issuing their loads; nothing of a failed run is written back).
+        const int flag_fail = misc[0], flag_err = misc[2], flag_unflushed = misc[4];
         const double piv = misc_d[1], rpiv = misc_d[2];
-        if (flag_fail) { ok = false; break; }
-        if (flag_err) { error_step = 1 + t; break; }
         const bool unflushed = flag_unflushed != 0;
         // columns that will report a new score in step 4; the last one to do so publishes the workgroup's
         // slot of the next step at once, without waiting for the barrier and the loop head
         const int participants = nlive - (owner == b ? 1 : 0);
         const bool more_steps = t + 1 < S.n_remove;
-        if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = score[p - j0]; }   // exact score, not the truncated one
-        if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; rpivs[k] = rpiv; }
 
         // ---------------------------------------------------------- 4. own slice of the pivot row, Eq. 3
         for (int jl = wave, r = 0; jl < nown; jl += NW, ++r) {
@@ -739,6 +736,11 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 }
             }
         }
+        // bookkeeping that nobody needs before the next step, after the columns (thread 0 belongs to a column wavefront)
+        if (owner == b && tid == 0) { S.order[t] = p; S.err[t] = score[p - j0]; }   // exact score, not the truncated one
+        if (tid == 0) { alive_bits[p >> 5] &= ~(1u << (p & 31)); pivs[k] = piv; rpivs[k] = rpiv; *gkey_min = KEY_EMPTY; *gkey_max = 0; }
+        if (flag_fail) { ok = false; break; }
+        if (flag_err) { error_step = 1 + t; break; }
         slot_early = participants > 0 && more_steps;
         if (owner == b) --nlive;
         ++k;
