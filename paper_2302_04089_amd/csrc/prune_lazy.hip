@@ -643,6 +643,13 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 if (!ll_wait2(pw + m + 2 * BMAX + 2 + 2 * kk, tag, hi, lo, S.status)) fail = true;
                 else cprev[kk] = dmake(hi, lo) * rpivprev[kk];
             }
+#ifdef ZIPLM_LAZY_TIMING
+            if (b == 1 && tid == 64 && owner != b) {      // was the payload there at the first look?
+                const unsigned long long v0 = __hip_atomic_load(pw + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                S.timing[8 + 1024] += 1;
+                S.timing[8 + 1025] += ((unsigned)(v0 & 0xffffffffu) == tag) ? 1 : 0;
+            }
+#endif
             for (int i = tid; i < m; i += LT) {
                 unsigned v;
                 if (!ll_wait(pw + i, tag, v, S.status)) { fail = true; break; }
@@ -864,7 +871,7 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     s.status = c.take<int>(1);
     l.snap_steps = c.take<int>((size_t)(n_snap > 0 ? n_snap : 1));
 #ifdef ZIPLM_LAZY_TIMING
-    s.timing = c.take<unsigned long long>(8 + 1024);
+    s.timing = c.take<unsigned long long>(8 + 1024 + 8);
 #endif
     l.bytes = c.off;
     return l;
@@ -927,6 +934,11 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
         double mn = 1e30, mx = 0, sum = 0; int imx = 0;
         for (int q = 0; q < p.nb; ++q) { double v = loc[q] * 1e-2 / (n_remove > 0 ? n_remove : 1); sum += v; if (v < mn) mn = v; if (v > mx) { mx = v; imx = q; } }
         fprintf(stderr, "[lazy timing] local us/step (exchange done -> slot published): min %.3f avg %.3f max %.3f (block %d)\n", mn, sum / p.nb, mx, imx);
+        { unsigned long long pr[2]; hipMemcpy(pr, S.timing + 8 + 1024, sizeof(pr), hipMemcpyDeviceToHost);
+          if (pr[0]) fprintf(stderr, "[lazy timing] winner's payload already visible at the first read of step 3: %.1f%% of %llu steps (workgroup 1)\n", 100.0 * pr[1] / pr[0], pr[0]); }
+        { double x[8] = {0}; int c[8] = {0}; for (int q = 0; q < p.nb; ++q) { x[q & 7] += loc[q] * 1e-2 / n_remove; c[q & 7]++; }
+          fprintf(stderr, "[lazy timing] local us/step by workgroup index mod 8:"); for (int q = 0; q < 8; ++q) fprintf(stderr, " %.3f", x[q] / (c[q] ? c[q] : 1)); fprintf(stderr, "\n");
+          fprintf(stderr, "[lazy timing] local us/step by workgroup index / 32:"); for (int g = 0; g < 8; ++g) { double a = 0; int n = 0; for (int q = 32 * g; q < 32 * g + 32 && q < p.nb; ++q) { a += loc[q] * 1e-2 / n_remove; ++n; } fprintf(stderr, " %.3f", n ? a / n : 0.0); } fprintf(stderr, "\n"); }
     }
 #endif
     *status_dev_out = S.status;
