@@ -130,6 +130,31 @@ int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int 
 size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap);
 
 /*
+ * The same loop for several layers of one shape in one sequence of launches (Section 3.2: every layer
+ * is treated independently).  Meant for many small problems, such as the attention output projections
+ * of all layers of a model, whose per-layer launch sequences are latency bound; layers do not interact.
+ *
+ *   W        n_layers matrices d_row x d_col, layer l at W + l*stride_w (stride_w >= d_row*d_col), in/out
+ *   Hinv     n_layers matrices d_col x d_col, layer l at Hinv + l*stride_hinv, in/out
+ *   order_out, err_out   [n_layers][n_remove]
+ *   W_snap   [n_layers][n_snap][d_row][d_col]; snapshot_steps_host is shared by all layers
+ *   info_host   optional host int[n_layers], as in the single-layer call; the return value is
+ *            ZIPLM_ERR_NOT_PD / ZIPLM_ERR_DEVICE if any layer reported it (the other layers are complete)
+ *
+ * 2 <= group_size <= 64 in this build (single columns: ZIPLM_ERR_UNSUPPORTED, call the single-layer
+ * function once per layer).  Every layer starts with all structures alive.  Results are identical to
+ * n_layers single-layer calls.
+ */
+int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_layers, int64_t stride_w,
+                                     int64_t stride_hinv, int d_row, int d_col, int group_size,
+                                     int n_remove, int32_t *order_out, double *err_out, int n_snap,
+                                     const int32_t *snapshot_steps_host, float *W_snap,
+                                     int *info_host, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+size_t ziplm_prune_batch_workspace_bytes(int n_layers, int d_row, int d_col, int group_size,
+                                         int n_snap);
+
+/*
  * Error of dropping a whole module ("Pruned structures", Section 3.1: besides heads and
  * feed-forward columns, an entire attention or feed-forward module may be removed).  With every
  * column pruned nothing is left to compensate, so the layer-wise error in the quadratic form of

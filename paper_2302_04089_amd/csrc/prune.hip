@@ -20,6 +20,7 @@
 #include <hip/hip_cooperative_groups.h>
 
 #include <stdlib.h>
+#include <type_traits>
 
 #include "common.h"
 
@@ -69,6 +70,27 @@ struct PruneState {
     double *Binv;        // [G][g*g]
     int *dead_step;      // [G] step at which the structure was removed; kNever while alive, -1 if it came in removed
 };
+
+// Several layers of one shape in one launch (grid dimension y = layer): layer l uses the state of layer 0
+// with every workspace pointer moved by l * ws_bytes and the caller's arrays by their own strides.  The
+// snapshot schedule is shared.  All strides are 0 for a single layer.
+struct BatchShift {
+    size_t ws_bytes;
+    long long w, hinv, order, err, snap;    // elements
+};
+
+__device__ __forceinline__ PruneState layer_state(PruneState P, const BatchShift &B, int l) {
+    if (l == 0) return P;
+    const size_t o = (size_t)l * B.ws_bytes;
+    auto mv = [o](auto *&ptr) { if (ptr) ptr = reinterpret_cast<std::remove_reference_t<decltype(ptr)>>(reinterpret_cast<char *>(ptr) + o); };
+    mv(P.Hd); mv(P.alive); mv(P.bar); mv(P.status); mv(P.score); mv(P.Binv); mv(P.dead_step);
+    P.W += (long long)l * B.w;
+    P.Hinv += (long long)l * B.hinv;
+    P.order += (long long)l * B.order;
+    P.err += (long long)l * B.err;
+    if (P.W_snap) P.W_snap += (long long)l * B.snap;
+    return P;
+}
 
 // ---------------------------------------------------------------------------------------------
 // helpers
@@ -295,7 +317,8 @@ constexpr int kNever = 0x7fffffff;
 // writes t, which a workgroup still choosing step t's structure reads as "alive" just like the old value:
 // all workgroups of a launch see the same set whatever the timing.
 
-__global__ __launch_bounds__(256) void group_init_kernel(PruneState P) {
+__global__ __launch_bounds__(256) void group_init_kernel(PruneState P, BatchShift B) {
+    P = layer_state(P, B, blockIdx.y);
     const int gtid = blockIdx.x * 256 + threadIdx.x, gthreads = gridDim.x * 256;
     const size_t total = (size_t)P.d * P.d;
     for (size_t idx = gtid; idx < total; idx += gthreads) P.Hd[idx] = (double)P.Hinv[idx];
@@ -311,7 +334,8 @@ typedef double doublex4 __attribute__((ext_vector_type(4)));
 //   B = (Hd[S,S])^-1 by in-place Gauss-Jordan elimination in LDS (the pivots of a positive definite
 //       block are its successive Schur complements, all > 0; no pivoting);
 //   score_s = sum_i w_i B w_i^T = <B, G>.
-__global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step) {
+__global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShift B, int step) {
+    P = layer_state(P, B, blockIdx.y);
     __shared__ double Bm[GMAX][GMAX + 1];
     __shared__ double rowk[GMAX], colk[GMAX];
     __shared__ float Wt[64][GMAX + 4];
@@ -436,7 +460,8 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, int step
 // Rows and columns of the selected structure and of earlier removed ones are left alone (they are zeroed at
 // the end), so the rows Hd[S,:] and the columns Hd[:,S] read here are the pre-step ones for every workgroup.
 constexpr int G_ROWS = 16;
-__global__ __launch_bounds__(256) void group_update_kernel(PruneState P, int step) {
+__global__ __launch_bounds__(256) void group_update_kernel(PruneState P, BatchShift Bsh, int step) {
+    P = layer_state(P, Bsh, blockIdx.y);
     __shared__ double Bs[GMAX][GMAX];         // B of the selected structure
     __shared__ double As[G_ROWS][GMAX + 1];   // this tile's rows restricted to the columns of S
     __shared__ double Cs[G_ROWS][GMAX];       // this tile's rows of C_H or C_W
@@ -526,11 +551,13 @@ __global__ __launch_bounds__(256) void group_update_kernel(PruneState P, int ste
     }
 }
 
-__global__ __launch_bounds__(256) void group_snapshot_kernel(PruneState P, int removed) {
+__global__ __launch_bounds__(256) void group_snapshot_kernel(PruneState P, BatchShift B, int removed) {
+    P = layer_state(P, B, blockIdx.y);
     snapshot_copy(P, removed, blockIdx.x * 256 + threadIdx.x, gridDim.x * 256);
 }
 
-__global__ __launch_bounds__(256) void group_final_kernel(PruneState P) {
+__global__ __launch_bounds__(256) void group_final_kernel(PruneState P, BatchShift B) {
+    P = layer_state(P, B, blockIdx.y);
     const int gtid = blockIdx.x * 256 + threadIdx.x, gthreads = gridDim.x * 256;
     const int d = P.d, g = P.g;
     const size_t totalw = (size_t)P.m * d;
@@ -578,6 +605,51 @@ static PruneLayout prune_layout(int d_row, int d_col, int g, int n_snap, void *w
     }
     l.bytes = c.off;
     return l;
+}
+
+// Uploads the snapshot schedule (first snapshot per step + chain of further ones at the same step) into the
+// tables of `l` and points P at them.  The sources are pageable: the copies have staged them when this returns.
+static int upload_snapshot_schedule(PruneLayout &l, PruneState &P, int G, int n_snap, const int32_t *steps_host,
+                                    hipStream_t st) {
+    if (n_snap <= 0) {
+        P.snap_of_step = nullptr;
+        P.snap_next = nullptr;
+        return ZIPLM_OK;
+    }
+    int *of_step = new int[(size_t)G + 1];
+    int *next = new int[(size_t)n_snap];
+    for (int t = 0; t <= G; ++t) of_step[t] = -1;
+    for (int q = n_snap - 1; q >= 0; --q) {
+        next[q] = of_step[steps_host[q]];
+        of_step[steps_host[q]] = q;
+    }
+    hipError_t e1 = hipMemcpyAsync(l.snap_of_step, of_step, sizeof(int) * ((size_t)G + 1), hipMemcpyHostToDevice, st);
+    hipError_t e2 = hipMemcpyAsync(l.snap_next, next, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st);
+    hipError_t e3 = hipStreamSynchronize(st);
+    delete[] of_step;
+    delete[] next;
+    if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return ZIPLM_ERR_DEVICE;
+    P.snap_of_step = l.snap_of_step;
+    P.snap_next = l.snap_next;
+    return ZIPLM_OK;
+}
+
+// The launch sequence of the group path for `layers` layers at once (grid dimension y).
+static int launch_group_steps(const PruneState &P, const BatchShift &B, int layers, int n_remove, int n_snap,
+                              hipStream_t st) {
+    const int fill = 1024;
+    const int ncc = (P.d + 255) / 256;
+    const int tiles = ((P.d + G_ROWS - 1) / G_ROWS + (P.m + G_ROWS - 1) / G_ROWS) * ncc;
+    hipLaunchKernelGGL(group_init_kernel, dim3(fill, layers), dim3(256), 0, st, P, B);
+    for (int t = 0; t < n_remove; ++t) {
+        if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill, layers), dim3(256), 0, st, P, B, t);
+        hipLaunchKernelGGL(group_score_kernel, dim3(P.G, layers), dim3(256), 0, st, P, B, t);
+        hipLaunchKernelGGL(group_update_kernel, dim3(tiles, layers), dim3(256), 0, st, P, B, t);
+    }
+    if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill, layers), dim3(256), 0, st, P, B, n_remove);
+    hipLaunchKernelGGL(group_final_kernel, dim3(fill, layers), dim3(256), 0, st, P, B);
+    ZIPLM_HIP_TRY(hipGetLastError());
+    return ZIPLM_OK;
 }
 
 }  // namespace ziplm
@@ -628,27 +700,9 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
     P.W = W; P.Hinv = Hinv; P.n_remove = n_remove;
     P.order = order_out; P.err = err_out; P.alive_in = alive_in; P.W_snap = W_snap;
 
-    // snapshot schedule: first snapshot per step + chain of further ones at the same step
-    if (n_snap > 0) {
-        int *of_step = new int[(size_t)G + 1];
-        int *next = new int[(size_t)n_snap];
-        for (int t = 0; t <= G; ++t) of_step[t] = -1;
-        for (int q = n_snap - 1; q >= 0; --q) {
-            next[q] = of_step[snapshot_steps_host[q]];
-            of_step[snapshot_steps_host[q]] = q;
-        }
-        hipError_t e1 = hipMemcpyAsync(l.snap_of_step, of_step, sizeof(int) * ((size_t)G + 1), hipMemcpyHostToDevice, st);
-        hipError_t e2 = hipMemcpyAsync(l.snap_next, next, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st);
-        // pageable source: the copies above have staged the data when they return
-        hipError_t e3 = hipStreamSynchronize(st);
-        delete[] of_step;
-        delete[] next;
-        if (e1 != hipSuccess || e2 != hipSuccess || e3 != hipSuccess) return ZIPLM_ERR_DEVICE;
-        P.snap_of_step = l.snap_of_step;
-        P.snap_next = l.snap_next;
-    } else {
-        P.snap_of_step = nullptr;
-        P.snap_next = nullptr;
+    {
+        const int rc = upload_snapshot_schedule(l, P, G, n_snap, snapshot_steps_host, st);
+        if (rc != ZIPLM_OK) return rc;
     }
     // bar and status are adjacent 256-byte slots
     ZIPLM_HIP_TRY(hipMemsetAsync(P.bar, 0, 2 * kAlign, st));
@@ -664,18 +718,9 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
         ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(reinterpret_cast<void *>(prune_columns_kernel), dim3(nblocks),
                                                  dim3(PT), args, 0, st));
     } else {
-        const int fill = 1024;
-        hipLaunchKernelGGL(group_init_kernel, dim3(fill), dim3(256), 0, st, P);
-        const int ncc = (d_col + 255) / 256;
-        const int tiles = ((d_col + G_ROWS - 1) / G_ROWS + (d_row + G_ROWS - 1) / G_ROWS) * ncc;
-        for (int t = 0; t < n_remove; ++t) {
-            if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill), dim3(256), 0, st, P, t);
-            hipLaunchKernelGGL(group_score_kernel, dim3(G), dim3(256), 0, st, P, t);
-            hipLaunchKernelGGL(group_update_kernel, dim3(tiles), dim3(256), 0, st, P, t);
-        }
-        if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill), dim3(256), 0, st, P, n_remove);
-        hipLaunchKernelGGL(group_final_kernel, dim3(fill), dim3(256), 0, st, P);
-        ZIPLM_HIP_TRY(hipGetLastError());
+        const BatchShift none = {};
+        const int rc = launch_group_steps(P, none, 1, n_remove, n_snap, st);
+        if (rc != ZIPLM_OK) return rc;
     }
 
     if (info_host) {
@@ -685,6 +730,66 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
         *info_host = status;
         if (status > 0) return ZIPLM_ERR_NOT_PD;
         if (status < 0) return ZIPLM_ERR_DEVICE;
+    }
+    return ZIPLM_OK;
+}
+
+
+extern "C" size_t ziplm_prune_batch_workspace_bytes(int n_layers, int d_row, int d_col, int group_size, int n_snap) {
+    if (n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size < 2 || group_size > ziplm::GMAX || d_col % group_size) return 0;
+    return (size_t)n_layers * ziplm::prune_layout(d_row, d_col, group_size, n_snap, nullptr).bytes;
+}
+
+extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_layers, int64_t stride_w,
+                                                int64_t stride_hinv, int d_row, int d_col, int group_size,
+                                                int n_remove, int32_t *order_out, double *err_out, int n_snap,
+                                                const int32_t *snapshot_steps_host, float *W_snap, int *info_host,
+                                                void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace ziplm;
+    if (!W || !Hinv || n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size)
+        return ZIPLM_ERR_INVALID_ARG;
+    if (stride_w < (int64_t)d_row * d_col || stride_hinv < (int64_t)d_col * d_col) return ZIPLM_ERR_INVALID_ARG;
+    const int G = d_col / group_size;
+    if (n_remove < 0 || n_remove > G) return ZIPLM_ERR_INVALID_ARG;
+    if (n_remove > 0 && (!order_out || !err_out)) return ZIPLM_ERR_INVALID_ARG;
+    if (n_snap < 0 || (n_snap > 0 && (!snapshot_steps_host || !W_snap))) return ZIPLM_ERR_INVALID_ARG;
+    for (int q = 0; q < n_snap; ++q)
+        if (snapshot_steps_host[q] < 0 || snapshot_steps_host[q] > n_remove) return ZIPLM_ERR_INVALID_ARG;
+    if (group_size < 2 || group_size > GMAX) return ZIPLM_ERR_UNSUPPORTED;    // single columns: one launch per layer
+    const size_t need = ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap);
+    if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    PruneLayout l = prune_layout(d_row, d_col, group_size, n_snap, workspace);
+    PruneState &P = l.st;
+    P.W = W; P.Hinv = Hinv; P.n_remove = n_remove;
+    P.order = order_out; P.err = err_out; P.alive_in = nullptr; P.W_snap = W_snap;
+    BatchShift B = {};
+    B.ws_bytes = l.bytes;
+    B.w = stride_w; B.hinv = stride_hinv; B.order = n_remove; B.err = n_remove;
+    B.snap = (long long)n_snap * d_row * d_col;
+    {
+        const int rc = upload_snapshot_schedule(l, P, G, n_snap, snapshot_steps_host, st);
+        if (rc != ZIPLM_OK) return rc;
+    }
+    for (int q = 0; q < n_layers; ++q)     // bar and status of every layer
+        ZIPLM_HIP_TRY(hipMemsetAsync(reinterpret_cast<char *>(P.bar) + (size_t)q * l.bytes, 0, 2 * kAlign, st));
+    {
+        const int rc = launch_group_steps(P, B, n_layers, n_remove, n_snap, st);
+        if (rc != ZIPLM_OK) return rc;
+    }
+    if (info_host) {
+        ZIPLM_HIP_TRY(hipStreamSynchronize(st));
+        int worst = ZIPLM_OK;
+        for (int q = 0; q < n_layers; ++q) {
+            int status = 0;
+            ZIPLM_HIP_TRY(hipMemcpy(&status, reinterpret_cast<char *>(P.status) + (size_t)q * l.bytes, sizeof(int),
+                                    hipMemcpyDeviceToHost));
+            info_host[q] = status;
+            if (status > 0 && worst == ZIPLM_OK) worst = ZIPLM_ERR_NOT_PD;
+            if (status < 0) worst = ZIPLM_ERR_DEVICE;
+        }
+        return worst;
     }
     return ZIPLM_OK;
 }

@@ -28,6 +28,7 @@ EXPORTS = (
     "ziplm_hinv", "ziplm_hinv_workspace_bytes",
     "ziplm_structured_obs_prune", "ziplm_prune_workspace_bytes",
     "ziplm_module_error", "ziplm_module_error_workspace_bytes", "ziplm_prior",
+    "ziplm_structured_obs_prune_batch", "ziplm_prune_batch_workspace_bytes",
 )
 
 _lib = None
@@ -68,6 +69,11 @@ def lib():
                                              vp, sz, vp]
     L.ziplm_prune_workspace_bytes.restype = sz
     L.ziplm_prune_workspace_bytes.argtypes = [i32, i32, i32, i32]
+    L.ziplm_structured_obs_prune_batch.restype = i32
+    L.ziplm_structured_obs_prune_batch.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, i32, vp, vp, i32,
+                                                   ctypes.POINTER(ctypes.c_int32), vp, ctypes.POINTER(i32), vp, sz, vp]
+    L.ziplm_prune_batch_workspace_bytes.restype = sz
+    L.ziplm_prune_batch_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     L.ziplm_module_error.restype = i32
     L.ziplm_module_error.argtypes = [vp, vp, i32, i32, f32, vp, vp, sz, vp]
     L.ziplm_module_error_workspace_bytes.restype = sz
@@ -170,6 +176,40 @@ def ziplm_structured_obs_prune(W, Hinv, group_size, n_remove, alive=None, snapsh
     if rc != OK:
         raise ZiplmError(rc, info.value)
     return order[:n_remove], err[:n_remove], W_snap
+
+
+def ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap=0):
+    return int(lib().ziplm_prune_batch_workspace_bytes(int(n_layers), int(d_row), int(d_col), int(group_size), int(n_snap)))
+
+
+def ziplm_structured_obs_prune_batch(W, Hinv, group_size, n_remove, snapshot_steps=None, workspace=None,
+                                     stream=None, check=True):
+    """Algorithm 1 for a stack of layers of one shape: W (n_layers, d_row, d_col), Hinv (n_layers, d_col,
+    d_col), both in place.  Returns (order int32[n_layers, n_remove], err float64[n_layers, n_remove],
+    W_snap (n_layers, n_snap, d_row, d_col) or None), all on the device."""
+    _check(W, torch.float32, "W")
+    _check(Hinv, torch.float32, "Hinv")
+    n_layers, m, d = W.shape
+    assert Hinv.shape == (n_layers, d, d)
+    dev = W.device
+    order = torch.empty((n_layers, max(n_remove, 1)), dtype=torch.int32, device=dev)
+    err = torch.empty((n_layers, max(n_remove, 1)), dtype=torch.float64, device=dev)
+    steps = [] if snapshot_steps is None else [int(s) for s in snapshot_steps]
+    n_snap = len(steps)
+    W_snap = torch.empty((n_layers, n_snap, m, d), dtype=torch.float32, device=dev) if n_snap else None
+    steps_c = (ctypes.c_int32 * n_snap)(*steps) if n_snap else None
+    need = ziplm_prune_batch_workspace_bytes(n_layers, m, d, group_size, n_snap)
+    ws = workspace if workspace is not None else _workspace(need, dev)
+    info = (ctypes.c_int * n_layers)()
+    rc = lib().ziplm_structured_obs_prune_batch(
+        W.data_ptr(), Hinv.data_ptr(), n_layers, m * d, d * d, m, d, int(group_size), int(n_remove),
+        order.data_ptr(), err.data_ptr(), n_snap, steps_c, W_snap.data_ptr() if n_snap else None,
+        info if check else None, ws.data_ptr(), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc, list(info))
+    if n_remove == 0:
+        return order[:, :0], err[:, :0], W_snap
+    return order, err, W_snap
 
 
 def database_steps(n_structures, kind):

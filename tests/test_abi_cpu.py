@@ -24,7 +24,7 @@ def _declared_functions():
 def test_header_functions_are_exported(L):
     from paper_2302_04089_amd import ziplm
     names = _declared_functions()
-    assert len(names) == 11
+    assert len(names) == 13
     assert sorted(ziplm.EXPORTS) == names
     for n in names:
         assert getattr(L, n) is not None
@@ -78,6 +78,14 @@ def test_argument_errors_return_before_any_device_work(L):
     assert pr(one, one, 2, 8, 1, 1, one, one, None, 1, steps, one, None, one, big, None) == -1     # step > n_remove
     assert pr(one, one, 2, 256, 128, 1, one, one, None, 0, None, None, None, one, big, None) == -5 # group too large
     assert pr(one, one, 2, 8, 1, 1, one, one, None, 0, None, None, None, None, 0, None) == -3
+    pb = L.ziplm_structured_obs_prune_batch
+    assert L.ziplm_prune_batch_workspace_bytes(12, 768, 768, 64, 0) == 12 * L.ziplm_prune_workspace_bytes(768, 768, 64, 0)
+    assert L.ziplm_prune_batch_workspace_bytes(12, 768, 768, 1, 0) == 0          # single columns are not batched
+    assert pb(one, one, 0, 64, 64, 8, 8, 4, 1, one, one, 0, None, None, None, one, big, None) == -1    # no layers
+    assert pb(one, one, 2, 63, 64, 8, 8, 4, 1, one, one, 0, None, None, None, one, big, None) == -1    # stride too small
+    assert pb(one, one, 2, 64, 64, 8, 8, 1, 1, one, one, 0, None, None, None, one, big, None) == -5    # single columns
+    assert pb(one, one, 2, 64, 64, 8, 8, 4, 3, one, one, 0, None, None, None, one, big, None) == -1    # n_remove > G
+    assert pb(one, one, 2, 64, 64, 8, 8, 4, 1, one, one, 0, None, None, None, None, 0, None) == -3
     me = L.ziplm_module_error
     assert L.ziplm_module_error_workspace_bytes(0, 8) == 0
     need = L.ziplm_module_error_workspace_bytes(768, 3072)

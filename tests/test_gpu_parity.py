@@ -369,3 +369,48 @@ def test_prior_of_a_full_run_matches_oracle_and_ends_at_one(z, oracle):
     assert np.max(np.abs(got - oracle.prior(e_long, tot))) <= 1e-12
     empty = z.ziplm_prior(torch.empty(0, dtype=torch.float64, device="cuda"), total)
     assert empty.numel() == 0
+
+
+# ------------------------------------------------------------------------------------------ batched layers
+
+def test_prune_batch_equals_single_layer_calls_and_oracle(z, oracle):
+    """Three layers of one shape (different seeds) in one batched call: bit-identical to three single-layer
+    calls (same kernels, same arithmetic), snapshots included, and the first layer through the oracle
+    protocol.  One layer is given an indefinite inverse Hessian block: it must report it without disturbing
+    the others."""
+    m, d, g, n = 40, 192, 16, 1024
+    G = d // g
+    Ws, His = [], []
+    for seed in (31, 32, 33):
+        spec = workloads.small(m, d, g, n, x_kind="scaled_normal", seed=seed)
+        X, W = workloads.make_X(spec), workloads.make_W(spec)
+        H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+        z.ziplm_hessian_accumulate(H, dev(X), scale=2.0)
+        Hi, _ = z.ziplm_hinv(H, spec.damp_rel)
+        Ws.append(dev(W))
+        His.append(Hi)
+    Wb, Hb = torch.stack(Ws).contiguous(), torch.stack(His).contiguous()
+    W0, H0 = Wb.clone(), Hb.clone()
+    snaps = [0, 3, G]
+    order_b, err_b, snap_b = z.ziplm_structured_obs_prune_batch(Wb, Hb, g, G, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    for l in range(3):
+        Wl, Hl = W0[l].clone(), H0[l].clone()
+        o, e, sn = z.ziplm_structured_obs_prune(Wl, Hl, g, G, snapshot_steps=snaps)
+        torch.cuda.synchronize()
+        assert torch.equal(o, order_b[l]) and torch.equal(e, err_b[l])
+        assert torch.equal(sn, snap_b[l]) and torch.equal(Wl, Wb[l]) and torch.equal(Hl, Hb[l])
+    ref = compare_run(oracle, W0[0].cpu().numpy(), H0[0].cpu().numpy(), g, G, order_b[0].cpu().numpy(),
+                      err_b[0].cpu().numpy(), snap_steps=snaps)
+    assert rel_fro(snap_b[0, 1].cpu().numpy(), ref["W_snap"][1]) <= REL_TOL
+
+    # partial removal, and one bad layer among good ones
+    Wb, Hb = W0.clone(), H0.clone()
+    Hb[1, 5, 5] = -1.0
+    with pytest.raises(z.ZiplmError) as ei:
+        z.ziplm_structured_obs_prune_batch(Wb, Hb, g, 4)
+    assert ei.value.status == z.ERR_NOT_PD and ei.value.info[0] == 0 and ei.value.info[1] > 0 and ei.value.info[2] == 0
+    Wl, Hl = W0[2].clone(), H0[2].clone()
+    o, e, _ = z.ziplm_structured_obs_prune(Wl, Hl, g, 4)
+    torch.cuda.synchronize()
+    assert torch.equal(Wl, Wb[2]) and torch.equal(Hl, Hb[2])      # the good layers are complete
