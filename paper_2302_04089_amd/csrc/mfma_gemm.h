@@ -338,6 +338,15 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     epilogue(acc, C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
 }
 
+template <int Q>
+__device__ __forceinline__ void reduce_epilogue(const float (&sum)[16], const Args &g, int tm, int tn, bool mirror,
+                                                int wm, int wn, int lane) {
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[e >> 3][(e >> 2) & 1][4 * Q + (e & 3)] = sum[e];
+    epilogue<4 * Q, 4 * Q + 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
+}
+
 // Second pass of a split-K product: sums the raw accumulators of all splits in split order and
 // applies the epilogue.  Same thread <-> element mapping as gemm_kernel; blockIdx.y selects one of the
 // four groups of four accumulator registers (rows 8q..8q+7 of each 32-row block), so that a tile's
@@ -356,29 +365,34 @@ static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, i
         tn = tile_linear % g.tiles_n;
         if ((g.flags & F_LOWER_ONLY) && tn > tm) return;
     }
-    floatx16 acc[2][2];
+    float sum[16];       // this workgroup's quarter of the thread's accumulators: [i][j][4 q + v] at e = 8 i + 4 j + v
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int e = 0; e < 16; ++e) sum[e] = 0.f;
+    // Splits are added in index order (fixed summation order); the loads of SU splits are issued together, since
+    // with few workgroups per tile list this kernel is a chain of memory round trips, not a bandwidth problem.
+    constexpr int SU = 6;
+    for (int s0 = 0; s0 < nsplit; s0 += SU) {
+        float part[SU][16];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int u = 0; u < SU; ++u) {
+            const float *src = g.partial + ((int64_t)(s0 + u) * ntiles + tile_linear) * (64 * THREADS);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-        const float *src = g.partial + ((int64_t)s * ntiles + tile_linear) * (64 * THREADS);
+            for (int e = 0; e < 16; ++e)
+                part[u][e] = (s0 + u < nsplit) ? src[((e >> 2) * 16 + 4 * q + (e & 3)) * THREADS + tid] : 0.f;
+        }
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int u = 0; u < SU; ++u) {
+            if (s0 + u >= nsplit) break;          // uniform; adding the zeros would turn -0 sums into +0
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-#pragma unroll
-                for (int v = 0; v < 4; ++v)
-                    acc[i][j][4 * q + v] += src[((i * 2 + j) * 16 + 4 * q + v) * THREADS + tid];
+            for (int e = 0; e < 16; ++e) sum[e] += part[u][e];
+        }
     }
     const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
     switch (q) {
-        case 0: epilogue<0, 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
-        case 1: epilogue<4, 8>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
-        case 2: epilogue<8, 12>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
-        default: epilogue<12, 16>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane); break;
+        case 0: reduce_epilogue<0>(sum, g, tm, tn, mirror, wm, wn, lane); break;
+        case 1: reduce_epilogue<1>(sum, g, tm, tn, mirror, wm, wn, lane); break;
+        case 2: reduce_epilogue<2>(sum, g, tm, tn, mirror, wm, wn, lane); break;
+        default: reduce_epilogue<3>(sum, g, tm, tn, mirror, wm, wn, lane); break;
     }
 }
 

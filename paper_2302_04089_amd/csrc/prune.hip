@@ -66,7 +66,7 @@ struct PruneState {
     unsigned *bar;       // barrier arrival counter
     int *status;         // 0 ok, >0: 1 + step with a non-positive pivot, -1: barrier timed out
     // group path
-    double *score;       // [G]
+    double *score;       // [G][SCORE_PARTS]
     double *Binv;        // [G][g*g]
     int *dead_step;      // [G] step at which the structure was removed; kNever while alive, -1 if it came in removed
 };
@@ -100,6 +100,12 @@ __device__ __forceinline__ bool better(double s1, int i1, double s2, int i2) {
     if (i2 < 0) return i1 >= 0;
     if (i1 < 0) return false;
     return (s1 < s2) || (s1 == s2 && i1 < i2);
+}
+
+// Workgroup barrier that orders LDS traffic only: __syncthreads() also waits for every global load in flight,
+// which would serialise loads issued ahead of the barrier with the work behind it.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 template <int NT>
@@ -312,6 +318,7 @@ __global__ __launch_bounds__(PT) void prune_columns_kernel(PruneState P) {
 // group_size > 1: per-step launches
 // ---------------------------------------------------------------------------------------------
 constexpr int GMAX = 64;
+constexpr int SCORE_PARTS = 8;      // workgroups that share the rows of W when one structure is scored
 constexpr int kNever = 0x7fffffff;
 // Structure s takes part in step t iff dead_step[s] >= t.  The workgroup that records the removal of step t
 // writes t, which a workgroup still choosing step t's structure reads as "alive" just like the old value:
@@ -327,31 +334,60 @@ __global__ __launch_bounds__(256) void group_init_kernel(PruneState P, BatchShif
 
 typedef double doublex4 __attribute__((ext_vector_type(4)));
 
-// One workgroup per structure s:
-//   G = W[:,S]^T W[:,S]  (g x g, fp64) on the fp64 matrix cores (v_mfma_f64_16x16x4_f64: lane l supplies
+// SCORE_PARTS workgroups per structure s, each with its own share of the rows of W:
+//   G = W[rows,S]^T W[rows,S]  (g x g, fp64) on the fp64 matrix cores (v_mfma_f64_16x16x4_f64: lane l supplies
 //       A[row l%16][k l/16] and B[k l/16][col l%16], accumulator v holds D[row 4v + l/16][col l%16]), the
-//       rows of W streamed through LDS 64 at a time, four 16 x 16 tiles of G per wavefront;
-//   B = (Hd[S,S])^-1 by in-place Gauss-Jordan elimination in LDS (the pivots of a positive definite
-//       block are its successive Schur complements, all > 0; no pivoting);
-//   score_s = sum_i w_i B w_i^T = <B, G>.
+//       rows of W streamed through LDS 64 at a time, four 16 x 16 tiles of G per wavefront.  The whole Gram
+//       matrix of a 768 x 64 structure is 3072 such instructions, 20 us on the four SIMDs of one compute
+//       unit: that, not memory, is why the rows are shared out;
+//   B = (Hd[S,S])^-1 by Gauss-Jordan elimination in registers (the pivots of a positive definite block are its
+//       successive Schur complements, all > 0; no pivoting), repeated by every part: same inputs, same
+//       operations, same B everywhere; part 0 stores it for the update launch;
+//   score_s[part] = sum_{i in rows} w_i B w_i^T = <B, G>; the update launch adds the parts in index order.
 __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShift B, int step) {
-    P = layer_state(P, B, blockIdx.y);
-    __shared__ double Bm[GMAX][GMAX + 1];
-    __shared__ double rowk[GMAX], colk[GMAX];
-    __shared__ float Wt[64][GMAX + 4];
+    P = layer_state(P, B, blockIdx.z);
+    constexpr int GR = 128;                      // rows of W per pass of the Gram product
+    // the Gram product's staging area and the inverse's final home are never live together
+    __shared__ __attribute__((aligned(16))) unsigned char stage[sizeof(float) * GR * (GMAX + 4)];
+    static_assert(sizeof(stage) >= sizeof(double) * GMAX * (GMAX + 1), "the inverse must fit the staging area");
+    float (*Wt)[GMAX + 4] = reinterpret_cast<float (*)[GMAX + 4]>(stage);
+    double (*Bm)[GMAX + 1] = reinterpret_cast<double (*)[GMAX + 1]>(stage);
+    __shared__ __attribute__((aligned(16))) double rowk[2][2][GMAX], colk[2][2][4][GMAX / 4];
     __shared__ double red[256];
     __shared__ int bad;
     const int s = blockIdx.x, tid = threadIdx.x, g = P.g, d = P.d;
     const int lane = tid & 63, wave = tid >> 6, q4 = lane >> 4, cl16 = lane & 15;
-    if (*P.status != 0) return;
-    if (P.dead_step[s] < step) {
-        if (tid == 0) P.score[s] = 0.0;
+    const int part_idx = blockIdx.y;
+    const int c0 = s * g;
+    // this workgroup's rows of W: a SCORE_PARTS-th of them, in whole groups of four (one matrix-core k step)
+    const int rows_per_part = ((P.m + SCORE_PARTS - 1) / SCORE_PARTS + 3) / 4 * 4;
+    const int r_begin = min(P.m, part_idx * rows_per_part), r_end = min(P.m, r_begin + rows_per_part);
+    // A kernel this short is a chain of memory round trips: the status word, the structure's state, its block
+    // of the inverse Hessian and the first rows of W are all asked for before any of them is looked at.
+    const int status = *P.status;
+    const int ds = P.dead_step[s];
+    // The g x g block lives in registers: this thread holds column `lane`, rows wave + 4 q; beyond g the matrix
+    // is continued by the identity, which the elimination leaves alone.
+    double cur[GMAX / 4];
+#pragma unroll
+    for (int q = 0; q < GMAX / 4; ++q) {
+        const int i = wave + 4 * q;
+        cur[q] = (i < g && lane < g) ? P.Hd[(size_t)(c0 + i) * d + c0 + lane] : (i == lane ? 1.0 : 0.0);
+    }
+    float wv[GR / 4];                            // rows wave + 4 q of the pass, column `lane` of the structure
+    auto load_rows = [&](int i0) {
+#pragma unroll
+        for (int q = 0; q < GR / 4; ++q) {
+            const int r = i0 + wave + 4 * q;
+            wv[q] = (r < r_end && lane < g) ? P.W[(size_t)r * d + c0 + lane] : 0.f;
+        }
+    };
+    load_rows(r_begin);
+    if (status != 0) return;
+    if (ds < step) {
+        if (tid == 0) P.score[s * SCORE_PARTS + part_idx] = 0.0;
         return;
     }
-    const int c0 = s * g;
-    // element mapping of the g x g block without divisions: column lane, rows wave + 4 q
-    for (int i = wave; i < g; i += 4)
-        if (lane < g) Bm[i][lane] = P.Hd[(size_t)(c0 + i) * d + c0 + lane];
     if (tid == 0) bad = 0;
 
     // ---- Gram matrix: tiles (ta, tb) of 16 x 16, tile index = wave + 4 * x, x < 4 (g <= 64)
@@ -359,26 +395,22 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
     doublex4 acc[4];
 #pragma unroll
     for (int x = 0; x < 4; ++x) acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
-    for (int i0 = 0; i0 < P.m; i0 += 64) {
-        __syncthreads();
-        {
-            float wv[16];                                  // sixteen loads in flight per thread
-#pragma unroll
-            for (int q = 0; q < 16; ++q) {
-                const int r = wave + 4 * q, c = lane;
-                wv[q] = (i0 + r < P.m && c < g) ? P.W[(size_t)(i0 + r) * d + c0 + c] : 0.f;
-            }
-#pragma unroll
-            for (int q = 0; q < 16; ++q) Wt[wave + 4 * q][lane] = wv[q];
+    for (int i0 = r_begin; i0 < r_end; i0 += GR) {
+        if (i0 != r_begin) {
+            lds_barrier();                       // the previous pass has been read
+            load_rows(i0);
         }
-        __syncthreads();
+#pragma unroll
+        for (int q = 0; q < GR / 4; ++q) Wt[wave + 4 * q][lane] = wv[q];
+        lds_barrier();
+        const int nks = (min(GR, r_end - i0) + 3) / 4;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int tile = wave + 4 * x;
             if (tile < nt * nt) {                       // wave-uniform
                 const int ta = tile / nt, tb = tile % nt;
-#pragma unroll
-                for (int ks = 0; ks < 16; ++ks) {
+#pragma unroll 8
+                for (int ks = 0; ks < nks; ++ks) {
                     const double av = (double)Wt[4 * ks + q4][16 * ta + cl16];
                     const double bv = (double)Wt[4 * ks + q4][16 * tb + cl16];
                     acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[x], 0, 0, 0);
@@ -386,48 +418,77 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
             }
         }
     }
-    __syncthreads();
+    lds_barrier();          // Wt is dead from here on: its memory becomes Bm at the end of the elimination
 
-    // ---- B = A^-1 in place
-    for (int k = 0; k < g; ++k) {
-        const double piv = Bm[k][k];
-        if (tid < g) { rowk[tid] = Bm[k][tid]; colk[tid] = Bm[tid][k]; }
-        __syncthreads();
-        if (!(piv > 0.0)) {          // uniform: every thread read the same pivot
-            if (tid == 0) bad = 1;
-            break;
-        }
-        const double ip = 1.0 / piv;
-        if (lane < g) {
-            const int j = lane;
-            const double rj = rowk[j] * ip;
-            double cur[GMAX / 4], ck[GMAX / 4];
+    // ---- B = A^-1 in place, two pivots at a time (block Gauss-Jordan).  With K = {k0, k0 + 1}, P = A[K,K]:
+    //     A[K,K] <- P^-1,  A[K,j] <- P^-1 A[K,j],  A[i,K] <- -A[i,K] P^-1,  A[i,j] <- A[i,j] - A[i,K] (P^-1 A[K,j]).
+    // A step needs rows K (one value per lane each, held by two wavefronts) and columns K (sixteen values per
+    // wavefront each, held by lanes k0 and k0 + 1): they go through LDS, and that round trip, not the arithmetic,
+    // is what a step costs, hence two pivots per trip.  The buffers alternate, so one barrier per step is enough
+    // (a wavefront writes a buffer again only after the barrier of the next step, which every wavefront reaches
+    // after its reads of this one).  After every two steps the sixteen registers rotate by one, so that the rows
+    // handed out are always register 0 of wavefronts 0,1 or 2,3 and the loop needs neither full unrolling nor
+    // indexed registers: register q holds row wave + 4 ((q + nrot) % 16).
+    int nrot = 0;
+    bool stop = false;
+    for (int kq = 0; 4 * kq < g && !stop; ++kq) {
 #pragma unroll
-            for (int q = 0; q < GMAX / 4; ++q) {           // all loads first: sixteen rows per lane
-                const int i = wave + 4 * q;
-                cur[q] = (i < g) ? Bm[i][j] : 0.0;
-                ck[q] = (i < g) ? colk[i] : 0.0;
+        for (int r = 0; r < 2; ++r) {
+            const int k0 = 4 * kq + 2 * r;
+            if (k0 >= g) break;
+            if ((wave >> 1) == r) rowk[r][wave & 1][lane] = cur[0];
+            if ((lane >> 1) == (k0 >> 1)) {
+#pragma unroll
+                for (int q = 0; q < GMAX / 4; ++q) colk[r][lane & 1][wave][q] = cur[q];
             }
+            __syncthreads();
+            const double p00 = rowk[r][0][k0], p01 = rowk[r][0][k0 + 1], p11 = rowk[r][1][k0 + 1];
+            const double det = __builtin_fma(p00, p11, -p01 * p01);
+            // both pivots of the pair are positive iff p00 > 0 and det > 0 (the second one is det / p00)
+            if (!(p00 > 0.0) || !(det > 0.0)) {          // uniform: every thread read the same values
+                if (tid == 0) bad = 1;
+                stop = true;
+                break;
+            }
+            // 1 / det by Newton steps from the hardware estimate: the quotient sits on the chain of all steps
+            double idet = __builtin_amdgcn_rcp(det);
+            idet = __builtin_fma(__builtin_fma(-det, idet, 1.0), idet, idet);
+            idet = __builtin_fma(__builtin_fma(-det, idet, 1.0), idet, idet);
+            const double q00 = p11 * idet, q01 = -p01 * idet, q11 = p00 * idet;      // P^-1 (symmetric)
+            const double r0 = rowk[r][0][lane], r1 = rowk[r][1][lane];
+            // this column's entries of the new rows K; for the columns of K themselves the columns of P^-1
+            const bool j0 = lane == k0, j1 = lane == k0 + 1, jK = j0 || j1;
+            const double s0 = j0 ? q00 : j1 ? q01 : __builtin_fma(q00, r0, q01 * r1);
+            const double s1 = j0 ? q01 : j1 ? q11 : __builtin_fma(q01, r0, q11 * r1);
 #pragma unroll
             for (int q = 0; q < GMAX / 4; ++q) {
-                const int i = wave + 4 * q;
-                double v;
-                if (i == k) v = (j == k) ? ip : rj;
-                else if (j == k) v = -ck[q] * ip;
-                else v = cur[q] - ck[q] * rj;
-                if (i < g) Bm[i][j] = v;
+                const double c0v = colk[r][0][wave][q], c1v = colk[r][1][wave][q];
+                double v = __builtin_fma(-c1v, s1, __builtin_fma(-c0v, s0, jK ? 0.0 : cur[q]));
+                if (q == 0 && (wave >> 1) == r) v = (wave & 1) ? s1 : s0;          // rows K themselves
+                cur[q] = v;
             }
         }
-        __syncthreads();
+        const double first = cur[0];
+#pragma unroll
+        for (int q = 0; q + 1 < GMAX / 4; ++q) cur[q] = cur[q + 1];
+        cur[GMAX / 4 - 1] = first;
+        ++nrot;
     }
+#pragma unroll
+    for (int q = 0; q < GMAX / 4; ++q) Bm[wave + 4 * ((q + nrot) & 15)][lane] = cur[q];
     __syncthreads();
     if (bad) {
-        if (tid == 0) atomicCAS(P.status, 0, 1 + step);
+        if (tid == 0 && part_idx == 0) atomicCAS(P.status, 0, 1 + step);
         return;
     }
-    double *Bout = P.Binv + (size_t)s * g * g;
-    for (int i = wave; i < g; i += 4)
-        if (lane < g) Bout[i * g + lane] = Bm[i][lane];
+    if (part_idx == 0) {
+        double *Bout = P.Binv + (size_t)s * g * g;
+#pragma unroll
+        for (int q = 0; q < GMAX / 4; ++q) {
+            const int i = wave + 4 * ((q + nrot) & 15);
+            if (i < g && lane < g) Bout[i * g + lane] = cur[q];
+        }
+    }
 
     // ---- <B, G>: each lane holds G[16 ta + 4 v + q4][16 tb + cl16]
     double part = 0.0;
@@ -449,7 +510,7 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
         if (tid < o) red[tid] += red[tid + o];
         __syncthreads();
     }
-    if (tid == 0) P.score[s] = red[0];
+    if (tid == 0) P.score[s * SCORE_PARTS + part_idx] = red[0];
 }
 
 // Second (and last) launch of a step.  Every workgroup finds the cheapest live structure p itself from the
@@ -460,23 +521,48 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
 // Rows and columns of the selected structure and of earlier removed ones are left alone (they are zeroed at
 // the end), so the rows Hd[S,:] and the columns Hd[:,S] read here are the pre-step ones for every workgroup.
 constexpr int G_ROWS = 16;
+constexpr int G_CT = 2;             // 16-column tiles per wavefront: a workgroup covers 64 G_CT columns
+constexpr int G_COLS = 4 * 16 * G_CT;
 __global__ __launch_bounds__(256) void group_update_kernel(PruneState P, BatchShift Bsh, int step) {
     P = layer_state(P, Bsh, blockIdx.y);
-    __shared__ double Bs[GMAX][GMAX];         // B of the selected structure
-    __shared__ double As[G_ROWS][GMAX + 1];   // this tile's rows restricted to the columns of S
-    __shared__ double Cs[G_ROWS][GMAX];       // this tile's rows of C_H or C_W
+    __shared__ double Bs[GMAX][GMAX + 1];     // B of the selected structure, zero beyond g
+    __shared__ double As[G_ROWS][GMAX + 1];   // this tile's rows restricted to the columns of S, zero beyond g
+    __shared__ double Cs[G_ROWS][GMAX + 1];   // this tile's rows of C_H or C_W
     __shared__ double sh_s[4];
     __shared__ int sh_i[4];
-    if (*P.status != 0) return;
     const int g = P.g, d = P.d, m = P.m, tid = threadIdx.x;
+    // A kernel this short is a chain of memory round trips: everything that can be asked for at once is (the
+    // status word with the scores here; all operands of the tile once p is known, further down).
+    const int status = *P.status;
     double best = 0.0;
     int p = -1;
-    for (int q = tid; q < P.G; q += 256) {
-        if (P.dead_step[q] < step) continue;
-        const double v = P.score[q];
-        if (better(v, q, best, p)) { best = v; p = q; }
+    if (P.G <= 64) {
+        // every wavefront finds the minimum for itself: no barrier
+        const int q = tid & 63;
+        if (q < P.G) {
+            const int ds = P.dead_step[q];
+            double v = 0.0;
+#pragma unroll
+            for (int e = 0; e < SCORE_PARTS; ++e) v += P.score[q * SCORE_PARTS + e];      // fixed order
+            if (ds >= step) { best = v; p = q; }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            const double so = __shfl_xor(best, o);
+            const int io = __shfl_xor(p, o);
+            if (better(so, io, best, p)) { best = so; p = io; }
+        }
+    } else {
+        for (int q = tid; q < P.G; q += 256) {
+            const int ds = P.dead_step[q];
+            double v = 0.0;
+#pragma unroll
+            for (int e = 0; e < SCORE_PARTS; ++e) v += P.score[q * SCORE_PARTS + e];      // fixed order
+            if (ds >= step && better(v, q, best, p)) { best = v; p = q; }
+        }
+        block_argmin<256>(best, p, sh_s, sh_i);
     }
-    block_argmin<256>(best, p, sh_s, sh_i);
+    if (status != 0) return;
     if (p < 0) {                                   // nothing left to remove: the request was impossible
         if (blockIdx.x == 0 && tid == 0) *P.status = 1 + step;
         return;
@@ -488,63 +574,102 @@ __global__ __launch_bounds__(256) void group_update_kernel(PruneState P, BatchSh
     }
     const int c0 = p * g;
     const double *B = P.Binv + (size_t)p * g * g;
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int i = wave; i < g; i += 4)             // element mapping without divisions: column = lane (g <= 64)
-        if (lane < g) Bs[i][lane] = B[i * g + lane];
-    const int ncc = (d + 255) / 256;
+    const int lane = tid & 63, wave = tid >> 6, q4 = lane >> 4, cl16 = lane & 15;
+    double bload[GMAX / 4];
+#pragma unroll
+    for (int q = 0; q < GMAX / 4; ++q) {           // element mapping without divisions: column = lane (g <= 64)
+        const int i = wave + 4 * q;
+        bload[q] = (i < g && lane < g) ? B[i * g + lane] : 0.0;
+    }
+    bool b_stored = false;
+    const int ncc = (d + G_COLS - 1) / G_COLS;
     const int n_h_tiles = ((d + G_ROWS - 1) / G_ROWS) * ncc;
     const int n_w_tiles = ((m + G_ROWS - 1) / G_ROWS) * ncc;
     for (int tile = blockIdx.x; tile < n_h_tiles + n_w_tiles; tile += gridDim.x) {
         const bool is_h = tile < n_h_tiles;
         const int tt = is_h ? tile : tile - n_h_tiles;
-        const int i0 = (tt / ncc) * G_ROWS, j = (tt % ncc) * 256 + tid;
+        const int i0 = (tt / ncc) * G_ROWS, jw = (tt % ncc) * G_COLS + 16 * G_CT * wave;     // this wavefront's columns
         const int rows = is_h ? d : m;
-        const int sj = (j < d) ? j / g : 0;
-        const bool live = (j < d) && sj != p && P.dead_step[sj] >= step;
-        __syncthreads();
-        if (lane < g) {
+        double aload[G_ROWS / 4];
 #pragma unroll
-            for (int q = 0; q < G_ROWS / 4; ++q) {
-                const int ii = wave + 4 * q, i = i0 + ii;
-                double v = 0.0;
-                if (i < rows) v = is_h ? P.Hd[(size_t)i * d + c0 + lane] : (double)P.W[(size_t)i * d + c0 + lane];
-                As[ii][lane] = v;
+        for (int q = 0; q < G_ROWS / 4; ++q) {
+            const int i = i0 + wave + 4 * q;
+            aload[q] = 0.0;
+            if (i < rows && lane < g) aload[q] = is_h ? P.Hd[(size_t)i * d + c0 + lane] : (double)P.W[(size_t)i * d + c0 + lane];
+        }
+        // The column tiles of this wavefront: which columns take part, and the old values of its elements
+        // (element v of tile ct: row i0 + 4 v + q4, column jw + 16 ct + cl16), fetched ahead of the products.
+        bool live[G_CT];
+        double old[G_CT][4];
+#pragma unroll
+        for (int ct = 0; ct < G_CT; ++ct) {
+            const int j = jw + 16 * ct + cl16;
+            const int sj = (j < d) ? j / g : 0;
+            live[ct] = (j < d) && sj != p && P.dead_step[sj] >= step;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + 4 * v + q4;
+                old[ct][v] = 0.0;
+                if (live[ct] && i < rows) old[ct][v] = is_h ? P.Hd[(size_t)i * d + j] : (double)P.W[(size_t)i * d + j];
             }
         }
-        __syncthreads();
-        if (lane < g) {
-            double sum[G_ROWS / 4];
+        // the rows of the selected structure over this wavefront's columns: B operands of the second product
+        double rv[G_CT][GMAX / 4];
 #pragma unroll
-            for (int q = 0; q < G_ROWS / 4; ++q) sum[q] = 0.0;
-            for (int a = 0; a < g; ++a) {
-                const double bv = Bs[a][lane];
+        for (int ct = 0; ct < G_CT; ++ct) {
+            const int j = jw + 16 * ct + cl16;
 #pragma unroll
-                for (int q = 0; q < G_ROWS / 4; ++q) sum[q] += As[wave + 4 * q][a] * bv;
+            for (int ks = 0; ks < GMAX / 4; ++ks) {
+                const int bb = 4 * ks + q4;
+                rv[ct][ks] = (live[ct] && bb < g) ? P.Hd[(size_t)(c0 + bb) * d + j] : 0.0;
             }
-#pragma unroll
-            for (int q = 0; q < G_ROWS / 4; ++q) Cs[wave + 4 * q][lane] = sum[q];
         }
-        __syncthreads();
-        double acc[G_ROWS];
+        lds_barrier();                  // the previous tile's readers of As, Bs and Cs are done
+        if (!b_stored) {
 #pragma unroll
-        for (int ii = 0; ii < G_ROWS; ++ii) acc[ii] = 0.0;
-        if (live) {
-            for (int b = 0; b < g; ++b) {
-                const double r = P.Hd[(size_t)(c0 + b) * d + j];
+            for (int q = 0; q < GMAX / 4; ++q) Bs[wave + 4 * q][lane] = bload[q];
+            b_stored = true;
+        }
 #pragma unroll
-                for (int ii = 0; ii < G_ROWS; ++ii) acc[ii] += Cs[ii][b] * r;
-            }
+        for (int q = 0; q < G_ROWS / 4; ++q) As[wave + 4 * q][lane] = aload[q];
+        lds_barrier();
+        // C = A B, 16 x 64: wavefront w forms columns 16 w .. 16 w + 15 (lane supplies A[row cl16][k q4] and
+        // B[k q4][col cl16] of each k group of four; accumulator v is C[row 4 v + q4][col cl16])
+        {
+            doublex4 c = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-            for (int ii = 0; ii < G_ROWS; ++ii) {
-                const int i = i0 + ii;
+            for (int ks = 0; ks < GMAX / 4; ++ks)
+                c = __builtin_amdgcn_mfma_f64_16x16x4f64(As[cl16][4 * ks + q4], Bs[4 * ks + q4][16 * wave + cl16], c, 0, 0, 0);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) Cs[4 * v + q4][16 * wave + cl16] = c[v];
+        }
+        lds_barrier();
+        // acc = C R with R = Hd[S, columns]: sixteen k groups, the A operand shared by the column tiles
+        double ca[GMAX / 4];
+#pragma unroll
+        for (int ks = 0; ks < GMAX / 4; ++ks) ca[ks] = Cs[cl16][4 * ks + q4];
+        doublex4 acc[G_CT];
+#pragma unroll
+        for (int ct = 0; ct < G_CT; ++ct) {
+            acc[ct] = doublex4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int ks = 0; ks < GMAX / 4; ++ks)
+                acc[ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(ca[ks], rv[ct][ks], acc[ct], 0, 0, 0);
+        }
+#pragma unroll
+        for (int ct = 0; ct < G_CT; ++ct) {
+            if (!live[ct]) continue;
+            const int j = jw + 16 * ct + cl16;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = i0 + 4 * v + q4;
                 if (i >= rows) continue;
                 if (is_h) {
                     const int si = i / g;
                     if (si == p || P.dead_step[si] < step) continue;
-                    P.Hd[(size_t)i * d + j] -= acc[ii];
+                    P.Hd[(size_t)i * d + j] = old[ct][v] - acc[ct][v];
                 } else {
-                    float *w = P.W + (size_t)i * d + j;
-                    *w = (float)((double)(*w) - acc[ii]);
+                    P.W[(size_t)i * d + j] = (float)(old[ct][v] - acc[ct][v]);
                 }
             }
         }
@@ -599,7 +724,7 @@ static PruneLayout prune_layout(int d_row, int d_col, int g, int n_snap, void *w
         s.cand_score = c.take<double>((size_t)s.ncc);
         s.cand_idx = c.take<int>((size_t)s.ncc);
     } else {
-        s.score = c.take<double>((size_t)s.G);
+        s.score = c.take<double>((size_t)s.G * SCORE_PARTS);
         s.Binv = c.take<double>((size_t)s.G * g * g);
         s.dead_step = c.take<int>((size_t)s.G);
     }
@@ -638,12 +763,12 @@ static int upload_snapshot_schedule(PruneLayout &l, PruneState &P, int G, int n_
 static int launch_group_steps(const PruneState &P, const BatchShift &B, int layers, int n_remove, int n_snap,
                               hipStream_t st) {
     const int fill = 1024;
-    const int ncc = (P.d + 255) / 256;
+    const int ncc = (P.d + G_COLS - 1) / G_COLS;
     const int tiles = ((P.d + G_ROWS - 1) / G_ROWS + (P.m + G_ROWS - 1) / G_ROWS) * ncc;
     hipLaunchKernelGGL(group_init_kernel, dim3(fill, layers), dim3(256), 0, st, P, B);
     for (int t = 0; t < n_remove; ++t) {
         if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill, layers), dim3(256), 0, st, P, B, t);
-        hipLaunchKernelGGL(group_score_kernel, dim3(P.G, layers), dim3(256), 0, st, P, B, t);
+        hipLaunchKernelGGL(group_score_kernel, dim3(P.G, SCORE_PARTS, layers), dim3(256), 0, st, P, B, t);
         hipLaunchKernelGGL(group_update_kernel, dim3(tiles, layers), dim3(256), 0, st, P, B, t);
     }
     if (n_snap > 0) hipLaunchKernelGGL(group_snapshot_kernel, dim3(fill, layers), dim3(256), 0, st, P, B, n_remove);
