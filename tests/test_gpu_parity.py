@@ -183,6 +183,11 @@ def test_prune_single_columns_partial(z, oracle):
     (17, 60, 2, 300, "normal", 3),
     (24, 64, 4, 256, "gelu", 4),
     (8, 64, 64, 256, "normal", 5),              # one structure = the whole layer
+    (20, 63, 3, 300, "normal", 6),              # odd size: the last pivot pair of a block is half padding
+    (12, 60, 6, 300, "gelu", 7),                # not a multiple of four
+    (33, 99, 33, 500, "gelu", 8),               # odd and across matrix-core tiles
+    (50, 144, 48, 700, "scaled_normal", 9),     # three tiles of sixteen
+    (1100, 128, 64, 600, "normal", 10),         # more rows than one pass of the Gram product per workgroup
 ])
 def test_prune_groups_remove_all(z, oracle, m, d, g, n, kind, seed):
     spec = workloads.small(m, d, g, n, x_kind=kind, seed=seed)
