@@ -331,9 +331,21 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
     }
 }
 
+// The large merges of the triangular inverse have 48 to 128 output tiles for 256 compute units: their k range
+// is shared by several workgroups.  Accumulator sets (one per workgroup) the workspace provides for that:
+constexpr int MERGE_PARTIAL_SETS = 512;
+static int merge_splits(int M, int N, int64_t K, int batch) {
+    const int tiles = ((M + gemm::BM - 1) / gemm::BM) * ((N + gemm::BN - 1) / gemm::BN) * batch;
+    if (tiles > 128 || K < 512) return 1;
+    int n = MERGE_PARTIAL_SETS / tiles;
+    if (n > 8) n = 8;
+    if (n > K / 128) n = (int)(K / 128);
+    return n < 1 ? 1 : n;
+}
+
 struct HinvLayout {
     int dp;
-    float *A, *T, *S, *dinv, *ldiag, *loff;
+    float *A, *T, *S, *dinv, *ldiag, *loff, *partial;
     double *lambda;
     int *info;
     size_t bytes;
@@ -350,6 +362,7 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.dinv = c.take<float>((size_t)(l.dp / NB) * NB * NB);
     l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored 64 x 64 diagonal blocks
     l.loff = c.take<float>((size_t)(l.dp / PW) * NB * NB);    // the block below the first one in every 128 x 128
+    l.partial = c.take<float>((size_t)MERGE_PARTIAL_SETS * 64 * gemm::THREADS);   // split-K accumulators of the merges
     l.lambda = c.take<double>(1);
     l.info = c.take<int>(1);
     l.bytes = c.off;
@@ -426,7 +439,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
             m1.M = rs; m1.N = s; m1.K = s;
             m1.alpha = 1.f; m1.beta = 0.f; m1.flags = F_KSTART_N;
             m1.strideA = m1.strideB = m1.strideC = stride;
-            ZIPLM_HIP_TRY((launch<K_CONTIG, R_CONTIG, true, false>(m1, batch, st)));
+            m1.partial = l.partial;
+            ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(m1, batch, merge_splits(m1.M, m1.N, m1.K, batch), st)));
             // T21 = -T22 S21     (T22 lower triangular: k ends with the tile row)
             Args m2 = {};
             m2.A = l.T + (int64_t)(a + s) * dp + (a + s); m2.lda = dp;
@@ -435,7 +449,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
             m2.M = rs; m2.N = s; m2.K = rs;
             m2.alpha = -1.f; m2.beta = 0.f; m2.flags = F_KEND_M;
             m2.strideA = m2.strideB = m2.strideC = stride;
-            ZIPLM_HIP_TRY((launch<K_CONTIG, R_CONTIG, true, false>(m2, batch, st)));
+            m2.partial = l.partial;
+            ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(m2, batch, merge_splits(m2.M, m2.N, m2.K, batch), st)));
         }
     }
 

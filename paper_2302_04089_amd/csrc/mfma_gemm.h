@@ -50,6 +50,7 @@ enum Flags : unsigned {
     F_KEND_M = 16u,        // k ends at (tile_row + 1) * 128 (A is lower triangular: A(m, k) = 0 for k > m)
     F_TRI_GRID = 32u,      // blockIdx.x enumerates the lower-triangular tile list instead of a 2-D grid
     F_PARTIAL = 64u,       // split-K: write raw accumulators to `partial`, no epilogue
+    F_SPLIT_TILE_RANGE = 128u,   // with F_PARTIAL: the splits share each tile's own k range (after the flags above)
 };
 // The DOT variant of the kernel writes no output matrix: it sums (alpha * acc + dot_lambda * C) * C over the tile,
 // C read-only, in fp64, into dot_partial[tile].
@@ -256,7 +257,14 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     if (g.flags & F_KSTART_N) kb = (int64_t)tn * BN;
     if (g.flags & F_KSTART_MAXMN) kb = (int64_t)(tm > tn ? tm : tn) * BM;
     if (g.flags & F_KEND_M) { int64_t e = (int64_t)(tm + 1) * BM; ke = e < ke ? e : ke; }
-    if (g.flags & F_PARTIAL) {
+    if (g.flags & F_SPLIT_TILE_RANGE) {
+        // whole slices per split; the last splits of a short range may get nothing and write zeros
+        const int64_t slices = ke > kb ? (ke - kb + BK - 1) / BK : 0;
+        const int64_t per = (slices + gridDim.y - 1) / gridDim.y * BK;
+        const int64_t b2 = kb + split * per, e2 = b2 + per;
+        kb = b2 < ke ? b2 : ke;
+        ke = e2 < ke ? e2 : ke;
+    } else if (g.flags & F_PARTIAL) {
         kb = (int64_t)split * g.k_chunk;
         int64_t e = kb + g.k_chunk;
         ke = e < g.K ? e : g.K;
@@ -297,7 +305,7 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     }
 
     if (g.flags & F_PARTIAL) {
-        float *dst = g.partial + ((int64_t)split * gridDim.x + tile_linear) * (64 * THREADS);
+        float *dst = g.partial + (((int64_t)blockIdx.z * gridDim.y + split) * gridDim.x + tile_linear) * (64 * THREADS);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -375,7 +383,7 @@ static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, i
         float part[SU][16];
 #pragma unroll
         for (int u = 0; u < SU; ++u) {
-            const float *src = g.partial + ((int64_t)(s0 + u) * ntiles + tile_linear) * (64 * THREADS);
+            const float *src = g.partial + (((int64_t)blockIdx.z * nsplit + s0 + u) * ntiles + tile_linear) * (64 * THREADS);
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 part[u][e] = (s0 + u < nsplit) ? src[((e >> 2) * 16 + 4 * q + (e & 3)) * THREADS + tid] : 0.f;
@@ -388,6 +396,7 @@ static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, i
         }
     }
     const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
+    g.C += (int64_t)blockIdx.z * g.strideC;
     switch (q) {
         case 0: reduce_epilogue<0>(sum, g, tm, tn, mirror, wm, wn, lane); break;
         case 1: reduce_epilogue<1>(sum, g, tm, tn, mirror, wm, wn, lane); break;
@@ -406,6 +415,23 @@ inline hipError_t launch(Args g, int batch, hipStream_t stream) {
     if (g.flags & F_TRI_GRID) grid = dim3(tiles_m * (tiles_m + 1) / 2, 1, batch);
     else grid = dim3(tiles_m * tiles_n, 1, batch);
     hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD, DOT>), grid, dim3(THREADS), 0, stream, g);
+    return hipGetLastError();
+}
+
+// A product whose tile list alone cannot fill the chip: `nsplit` workgroups share every tile's k range, a
+// second launch adds their accumulators in split order and applies the epilogue.  `partial` must hold
+// nsplit * tiles * batch accumulator sets of 64 * THREADS floats.
+template <int AMODE, int BMODE, bool VEC, bool KGUARD>
+inline hipError_t launch_splitk(Args g, int batch, int nsplit, hipStream_t stream) {
+    if (nsplit <= 1) return launch<AMODE, BMODE, VEC, KGUARD>(g, batch, stream);
+    if (g.M <= 0 || g.N <= 0 || batch <= 0) return hipSuccess;
+    const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    g.tiles_n = tiles_n;
+    const int tiles = (g.flags & F_TRI_GRID) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
+    g.flags |= F_PARTIAL | F_SPLIT_TILE_RANGE;
+    hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD>), dim3(tiles, nsplit, batch), dim3(THREADS), 0, stream, g);
+    g.flags &= ~(F_PARTIAL | F_SPLIT_TILE_RANGE);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(tiles, 4, batch), dim3(THREADS), 0, stream, g, nsplit, tiles);
     return hipGetLastError();
 }
 
