@@ -245,6 +245,7 @@ def main():
         "loop_hbm_gbs": loop_gbs,
         "us_per_loop_step": (loop_ms if column_specs else mean["loop"]) * 1e3 / n_steps_loop,
         "hbm_triad_gbs": triad_gbs,
+        "head_loops_ms": (mean["loop"] - loop_ms) if (column_specs and len(column_specs) < len(problems)) else None,
         "roofline": {"kernel": "greedy loop", "bound": "hbm", "achieved": loop_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": loop_gbs / HBM_PEAK_GBS if column_specs else None,
                      "frac_of_triad": loop_gbs / triad_gbs if column_specs else None,
