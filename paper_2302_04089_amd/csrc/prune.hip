@@ -13,9 +13,10 @@
 // Rows of Hd that belong to removed columns are skipped; removed columns are masked per lane.
 //
 // Larger structures (2 <= group_size <= 64): two ordinary launches per step,
-//     score  (one workgroup per live structure: block inverse in LDS, Gram contraction)
+//     score  (eight workgroups per live structure: block inverse in registers, Gram contraction of an eighth
+//             of the rows on the fp64 matrix cores)
 //     update (every workgroup picks the cheapest structure itself from the scores and forms the coefficients
-//             C_H = Hd[:,S] B, C_W = W[:,S] B of its own rows on the fly),
+//             C_H = Hd[:,S] B, C_W = W[:,S] B of its own rows on the fly; both products on the fp64 matrix cores),
 // because on this machine a dependent launch costs more than the arithmetic of a step.
 #include <hip/hip_cooperative_groups.h>
 
