@@ -18,15 +18,17 @@
  *     feed-forward neuron, d_head = 64 consecutive columns for an attention head ("Pruned
  *     structures", Section 3.1).
  *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns every buffer.
- *     The library allocates no device memory: scratch space is passed in as `workspace`
- *     (256-byte aligned, size from the matching *_workspace_bytes call) and may be reused or
- *     freed as soon as the work enqueued by the call has finished.
+ *     Scratch space is passed in as `workspace` (256-byte aligned, size from the matching
+ *     *_workspace_bytes call) and may be reused or freed as soon as the work enqueued by the
+ *     call has finished.  The library allocates no device memory, with one exception: the
+ *     per-device exchange area of the single-column loop (see ziplm_structured_obs_prune).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *     on that stream and return without waiting, except where a *_host output is requested.
  *   - Return value: ZIPLM_OK or a negative ziplm_status.  Argument errors are detected before
  *     anything is enqueued and leave all buffers untouched.  No exception crosses this boundary.
- *   - Calls on different streams with disjoint buffers are independent; the library keeps no
- *     state between calls.
+ *   - Calls on different streams with disjoint buffers are independent; apart from that
+ *     exchange area (and the order it imposes on single-column loops of one device) the library
+ *     keeps no state between calls.
  */
 #ifndef ZIPLM_H
 #define ZIPLM_H
@@ -120,6 +122,14 @@ size_t ziplm_hinv_workspace_bytes(int d_col);
  * The state is held in fp64 for Hinv and fp32 for W inside the call; scores are reduced in
  * fp64.  Ties in the argmin go to the lowest structure index.  Eq. 3 and Eq. 4 of one step use
  * the rows of Hinv as they were before that step.
+ *
+ * Memory the library owns: the single-column loop (group_size == 1) exchanges its candidates
+ * between workgroups through 32 MiB of uncached device memory, allocated per device on the first
+ * such call and kept until the process ends (it is never freed).  Calls on different streams of
+ * one device use it one after the other (each waits on the stream for the previous one's loop).
+ * With ZIPLM_EXCHANGE_IN_WORKSPACE=1 in the environment, when d_row is too large for it, or when
+ * the allocation fails, the exchange goes through the caller's workspace instead: same results,
+ * about 3% slower.  Everything else lives in the caller's buffers.
  */
 int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int group_size,
                                int n_remove, int32_t *order_out, double *err_out,

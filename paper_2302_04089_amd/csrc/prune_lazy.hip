@@ -41,6 +41,9 @@
 // exactly like the pending ones of the current block.  All waits are bounded: on a time-out the waiter raises status = -1 and
 // leaves; the others then time out or see the flag, and the grid drains.
 #include <stdio.h>
+#include <stdlib.h>
+
+#include <mutex>
 
 #include "common.h"
 
@@ -877,6 +880,53 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     return l;
 }
 
+// ------------------------------------------------------------------------------------------------
+// Exchange area: the candidate slots and the winner's payload, the two things other workgroups wait for.
+// In uncached device memory a store becomes visible to the other XCDs' loads sooner than through the write
+// path of the L2 (3% of the whole loop).  Such memory cannot be returned while the process lives (buffers
+// allocated after it was freed have been seen holding wrong values), so there is one area per device,
+// allocated on first use and kept; a layer whose payload does not fit, a failed allocation, or
+// ZIPLM_EXCHANGE_IN_WORKSPACE=1 fall back to the caller's workspace, which always has room for it.
+// Launches on different streams share the area: each waits for the previous one's event before it clears it.
+// ------------------------------------------------------------------------------------------------
+struct ExchangeArea {
+    void *ptr = nullptr;
+    bool tried = false, used = false;
+    hipEvent_t last = nullptr;
+};
+constexpr size_t EXCHANGE_BYTES = (size_t)32 << 20;
+constexpr int EXCHANGE_MAX_DEVICES = 64;
+static ExchangeArea g_exchange[EXCHANGE_MAX_DEVICES];
+static std::mutex g_exchange_mutex;
+
+static size_t exchange_bytes_needed(const Plan &p) {
+    return align_up(sizeof(unsigned long long) * (size_t)2 * p.nb) + align_up(sizeof(unsigned long long) * (size_t)2 * p.nb * p.pay_words);
+}
+
+// Caller holds g_exchange_mutex.  nullptr: use the workspace.
+static ExchangeArea *exchange_area_for(const Plan &p) {
+    const char *e = getenv("ZIPLM_EXCHANGE_IN_WORKSPACE");
+    if (e && e[0] == '1') return nullptr;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= EXCHANGE_MAX_DEVICES) return nullptr;
+    if (exchange_bytes_needed(p) > EXCHANGE_BYTES) return nullptr;
+    ExchangeArea &a = g_exchange[dev];
+    if (!a.tried) {
+        a.tried = true;
+        void *q = nullptr;
+        if (hipExtMallocWithFlags(&q, EXCHANGE_BYTES, hipDeviceMallocUncached) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        if (hipEventCreateWithFlags(&a.last, hipEventDisableTiming) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;             // the memory stays allocated: it must not be freed
+        }
+        a.ptr = q;
+    }
+    return a.ptr ? &a : nullptr;
+}
+
 }  // namespace lazy
 
 // Entry points used by prune.hip ------------------------------------------------------------------
@@ -904,8 +954,19 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
         ZIPLM_HIP_TRY(hipMemcpyAsync(l.snap_steps, snap_steps_host, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st));
         ZIPLM_HIP_TRY(hipStreamSynchronize(st));
     }
-    const size_t zero_bytes = reinterpret_cast<char *>(l.snap_steps) - reinterpret_cast<char *>(S.slots);
-    ZIPLM_HIP_TRY(hipMemsetAsync(S.slots, 0, zero_bytes, st));
+    std::lock_guard<std::mutex> guard(g_exchange_mutex);       // held until the launch and its event are enqueued
+    ExchangeArea *xa = exchange_area_for(p);
+    // zero-initialised: slots, payload, barrier epochs, status (contiguous in the workspace, in this order)
+    char *zero_from = reinterpret_cast<char *>(S.slots);
+    if (xa) {
+        if (xa->used) ZIPLM_HIP_TRY(hipStreamWaitEvent(st, xa->last, 0));
+        Carver cx(xa->ptr);
+        S.slots = cx.take<unsigned long long>((size_t)2 * p.nb);
+        S.pay = cx.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
+        ZIPLM_HIP_TRY(hipMemsetAsync(xa->ptr, 0, cx.off, st));
+        zero_from = reinterpret_cast<char *>(S.bar);
+    }
+    ZIPLM_HIP_TRY(hipMemsetAsync(zero_from, 0, reinterpret_cast<char *>(l.snap_steps) - zero_from, st));
     const void *fn = p.w_in_lds ? reinterpret_cast<const void *>(prune_lazy_kernel<true>)
                                 : reinterpret_cast<const void *>(prune_lazy_kernel<false>);
     static bool attr_set[2] = {false, false};
@@ -919,6 +980,10 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
     if (per_cu < 1 || p.nb > per_cu * device_cu_count()) return ZIPLM_ERR_DEVICE;
     void *args[] = {&S};
     ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(const_cast<void *>(fn), dim3(p.nb), dim3(LT), args, (unsigned)p.lds_bytes, st));
+    if (xa) {
+        ZIPLM_HIP_TRY(hipEventRecord(xa->last, st));
+        xa->used = true;
+    }
 #ifdef ZIPLM_LAZY_TIMING
     {
         unsigned long long tm[8];

@@ -314,6 +314,49 @@ def test_prune_eager_fallback_kernel(z, oracle, monkeypatch):
     _run_prune_case(z, oracle, spec, 300, [0, 150, 300])
 
 
+def test_exchange_area_in_workspace_gives_identical_results(z, oracle, monkeypatch):
+    """The candidate slots and the winners' payloads live in a per-device uncached area by default and in the
+    caller's workspace with ZIPLM_EXCHANGE_IN_WORKSPACE=1: same arithmetic, bit-identical results."""
+    spec = workloads.small(48, 320, 1, 1300, x_kind="gelu", seed=41)
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    outs = []
+    for flag in ("0", "1"):
+        monkeypatch.setenv("ZIPLM_EXCHANGE_IN_WORKSPACE", flag)
+        Wd, Hd = dev(W32), dev(Hi32)
+        o, e, sn = z.ziplm_structured_obs_prune(Wd, Hd, 1, 320, snapshot_steps=[160])
+        outs.append((o.cpu(), e.cpu(), Wd.cpu(), Hd.cpu(), sn.cpu()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+    compare_run(oracle, W32, Hi32, 1, 320, outs[0][0].numpy(), outs[0][1].numpy(), snap_steps=[160])
+
+
+def test_prune_calls_on_two_streams_share_the_exchange_area(z, oracle):
+    """Asynchronous calls on two streams use the same per-device exchange area one after the other: every
+    result equals that of the same call made alone."""
+    specs = [workloads.small(40, 288, 1, 1200, x_kind="gelu", seed=51),
+             workloads.small(24, 416, 1, 1700, x_kind="normal", seed=52)]
+    inputs = [_oracle_inputs(oracle, sp) for sp in specs]
+    alone = []
+    for sp, (X, W32, H, Hi32) in zip(specs, inputs):
+        Wd, Hd = dev(W32), dev(Hi32)
+        o, e, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, sp.d_col)
+        alone.append((o.cpu(), e.cpu()))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    results = []
+    for rep in range(3):
+        for k in (0, 1):
+            X, W32, H, Hi32 = inputs[k]
+            with torch.cuda.stream(streams[k]):
+                Wd, Hd = dev(W32), dev(Hi32)
+                o, e, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, specs[k].d_col, stream=streams[k], check=False)
+                results.append((k, o, e, Wd, Hd))
+    torch.cuda.synchronize()
+    for k, o, e, Wd, Hd in results:
+        assert torch.equal(o.cpu(), alone[k][0]) and torch.equal(e.cpu(), alone[k][1])
+        assert float(Wd.abs().max()) == 0.0
+
+
 # ------------------------------------------------------------------------------------------ module error, prior
 
 @pytest.mark.parametrize("m,d,n,kind,lam_rel", [
