@@ -401,8 +401,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
     unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
     int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet
     unsigned long long *cand_key = reinterpret_cast<unsigned long long *>(smem + L.misc + 64);   // best owned column
-    unsigned long long *gkey_min = reinterpret_cast<unsigned long long *>(smem + L.misc + 72);   // arg-min of the exchange
-    unsigned long long *gkey_max = reinterpret_cast<unsigned long long *>(smem + L.misc + 80);
+    unsigned long long *gkey_min = reinterpret_cast<unsigned long long *>(smem + L.misc + 80);   // arg-min of the exchange; the pair
+    unsigned long long *gkey_max = reinterpret_cast<unsigned long long *>(smem + L.misc + 88);   // is 16-byte aligned: one read
     double *misc_d = reinterpret_cast<double *>(smem + L.misc + 32);  // [1] pivot, [2] 1 / pivot
 
     const int j0 = b * cpb;
@@ -613,7 +613,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             if (fail) misc[0] = 1;
             if (err) misc[2] = 1;
             __syncthreads();
-            const unsigned long long kmin = *gkey_min, kmax = *gkey_max;
+            typedef unsigned long long ullx2 __attribute__((ext_vector_type(2)));
+            const ullx2 kmm = *reinterpret_cast<const ullx2 *>(gkey_min);
+            const unsigned long long kmin = kmm[0], kmax = kmm[1];
             p = (kmin == KEY_EMPTY) ? IDX_NONE : (int)(kmin & 0xffffu);
             // next step's publication threshold: the largest of the per-wavefront minima (each over 64
             // workgroups); with a single wavefront of candidates everybody keeps publishing
@@ -643,8 +645,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             if (bg_active && tid >= LT - 3 * BMAX && tid < LT - 2 * BMAX) {
                 const int kk = tid - (LT - 3 * BMAX);
                 unsigned hi, lo;
+                const double rp = rpivprev[kk];          // asked for ahead of the wait, not behind it
                 if (!ll_wait2(pw + m + 2 * BMAX + 2 + 2 * kk, tag, hi, lo, S.status)) fail = true;
-                else cprev[kk] = dmake(hi, lo) * rpivprev[kk];
+                else cprev[kk] = dmake(hi, lo) * rp;
             }
 #ifdef ZIPLM_LAZY_TIMING
             if (b == 1 && tid == 64 && owner != b) {      // was the payload there at the first look?
@@ -661,8 +664,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             if (tid >= LT - BMAX && tid - (LT - BMAX) < k) {
                 const int kk = tid - (LT - BMAX);
                 unsigned hi, lo;
+                const double rp = rpivs[kk];
                 if (!ll_wait2(pw + m + 2 * kk, tag, hi, lo, S.status)) fail = true;
-                else cvec[kk] = dmake(hi, lo) * rpivs[kk];
+                else cvec[kk] = dmake(hi, lo) * rp;
             }
             if (tid == LT - BMAX - 1) {
                 unsigned hi, lo;
@@ -702,6 +706,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 my_live &= ~(1u << r);
                 continue;
             }
+            const double diag_old = diag[jl];        // asked for here, needed after the column's pass
             double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
             if (unflushed) term += cprev[lane] * uprev[jl * BMAX + lane];
             const double u = hstale[jl] - wave_sum(term);
@@ -723,9 +728,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             }
             s = wave_sum(s);
             if (lane == 0) {
-                uloc[jl * BMAX + k] = u;
-                __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const double dj = diag[jl] - u * f;
+                const double dj = diag_old - u * f;
                 // s / dj by Newton steps from the hardware reciprocal estimate plus one correction of the quotient: a
                 // third of the instructions of a full division, on the path that decides when the next slot goes out
                 double rd = __builtin_amdgcn_rcp(dj);
@@ -733,17 +736,23 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 rd = __builtin_fma(__builtin_fma(-dj, rd, 1.0), rd, rd);
                 double sc = s * rd;
                 sc = __builtin_fma(__builtin_fma(-dj, sc, s), rd, sc);
+                // LDS serves one wavefront's operations in order, so the three below go out back to back and cost one
+                // round trip: the read returns the workgroup's minimum if this report turns out to be the last one
+                // (every other column's minimum was issued ahead of its count)
+                atomicMin(cand_key, (dj > 0.0) ? cand_key_of(sc, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
+                const int reported = atomicAdd(&misc[6], 1);
+                const unsigned long long knext = *reinterpret_cast<volatile unsigned long long *>(cand_key);
+                // bookkeeping nobody waits for
+                uloc[jl * BMAX + k] = u;
                 diag[jl] = dj;
                 norm[jl] = s;
                 score[jl] = sc;
-                atomicMin(cand_key, (dj > 0.0) ? cand_key_of(sc, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
-                if (atomicAdd(&misc[6], 1) == participants - 1 && more_steps) {
-                    // LDS serves one wavefront's operations in order: every column's minimum is in
-                    const unsigned long long knext = *reinterpret_cast<volatile unsigned long long *>(cand_key);
+                if (reported == participants - 1 && more_steps) {
                     const unsigned tag4_next = (tag4 == 15u) ? 1u : tag4 + 1u;
                     __hip_atomic_store(S.slots + (size_t)((t + 1) & 1) * nb + b, knext | tag4_next, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 }
+                __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         // bookkeeping that nobody needs before the next step, after the columns (thread 0 belongs to a column wavefront)
