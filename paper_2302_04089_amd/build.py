@@ -14,7 +14,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, 
          "-Wno-unused-command-line-argument"]
 # hinv.hip keeps 64-entry rows in registers inside doubly nested, fully unrolled loops; past the default size limit
 # of "#pragma unroll" the compiler would leave the outer loop rolled and put those rows in scratch memory
-FILE_FLAGS = {"hinv.hip": ["-mllvm", "-pragma-unroll-threshold=1000000"]}
+# prune_lazy.hip: its LDS atomics are issued by one lane on purpose; the compiler's wave-level rewrite of atomic adds
+# (lane count, one atomic, broadcast) puts a wait and a dozen instructions on the step's critical chain
+FILE_FLAGS = {"hinv.hip": ["-mllvm", "-pragma-unroll-threshold=1000000"],
+              "prune_lazy.hip": ["-mllvm", "-amdgpu-atomic-optimizer-strategy=None"]}
 
 
 def build(verbose=False):

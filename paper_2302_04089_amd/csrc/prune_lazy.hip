@@ -741,7 +741,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
                 // (every other column's minimum was issued ahead of its count)
                 atomicMin(cand_key, (dj > 0.0) ? cand_key_of(sc, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
                 const int reported = atomicAdd(&misc[6], 1);
-                const unsigned long long knext = *reinterpret_cast<volatile unsigned long long *>(cand_key);
+                // (an atomic load, not a volatile one: the latter is compiled to a flat load with system scope, which
+                // also waits for the stores to global memory still in flight)
+                const unsigned long long knext = __hip_atomic_load(cand_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 // bookkeeping nobody waits for
                 uloc[jl * BMAX + k] = u;
                 diag[jl] = dj;
