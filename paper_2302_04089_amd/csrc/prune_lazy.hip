@@ -629,56 +629,88 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
         // exchange are looked at after step 3 (p is a valid column or "none" whatever they say).
         if (p < 0) { error_step = 1 + t; break; }              // same inputs in every workgroup: uniform
         const int owner = (int)(((unsigned long long)(unsigned)p * cpb_magic) >> 32);      // p / cpb
-        if (tid == 0) { *cand_key = KEY_NONE; misc[6] = 0; }   // every thread read the key before the barrier of the exchange
+        // The thread index is made opaque for this stretch: predicates on it are then recomputed (one compare) where
+        // they are used instead of being kept across the whole step loop in scalar register pairs, of which the
+        // kernel has none to spare -- they were spilled to vector lanes and read back two lanes per predicate.
+        int tid3 = tid;
+        asm volatile("" : "+v"(tid3));
+        if (tid3 == 0) { *cand_key = KEY_NONE; misc[6] = 0; }   // every thread read the key before the barrier of the exchange
         if (owner == b && !published) publish_payload(p);
 
         // ---------------------------------------------------------- 3. winner's payload + stale column p
         {
             const unsigned long long *pw = S.pay + ((size_t)par * nb + owner) * S.pay_words;
             bool fail = false;
-            // column p of the stored matrix restricted to my rows (= my slice of row p, by symmetry)
-            if (tid < cp) hstale[tid] = P[(size_t)p * cp + tid];
-            if (tid == 0) {
-                const int ct = p >> 4;
-                misc[4] = (bg_active && (ct / NBG) >= seq_done[NPOLL + ct % NBG]) ? 1 : 0;
-            }
-            if (bg_active && tid >= LT - 3 * BMAX && tid < LT - 2 * BMAX) {
-                const int kk = tid - (LT - 3 * BMAX);
-                unsigned hi, lo;
-                const double rp = rpivprev[kk];          // asked for ahead of the wait, not behind it
-                if (!ll_wait2(pw + m + 2 * BMAX + 2 + 2 * kk, tag, hi, lo, S.status)) fail = true;
-                else cprev[kk] = dmake(hi, lo) * rp;
-            }
+            // The first N3 wavefronts do all of this step.  After the barrier of the exchange the sixteen wavefronts
+            // share four instruction issuers: the last ones reach this point a quarter of a microsecond after the
+            // first, so whatever the step waits for is given to those that arrive first, and every thread asks for
+            // everything it needs (up to three words of the W column, one pair of words of the pending rows or the
+            // diagonal, its entry of the stale column) before it waits for any of it.
+            constexpr int N3 = 6, T3 = 64 * N3, WQ = 3;
+            if (tid3 < T3) {
+                const int kk_hist = tid3 - BMAX, kk_prev = tid3 - 2 * BMAX;
+                const bool r_hist = kk_hist >= 0 && kk_hist < k;
+                const bool r_prev = bg_active && kk_prev >= 0 && kk_prev < BMAX;
+                const bool r_diag = tid3 == 3 * BMAX;
+                const unsigned long long *pa = r_hist ? pw + m + 2 * kk_hist
+                                             : r_prev ? pw + m + 2 * BMAX + 2 + 2 * kk_prev
+                                             : r_diag ? pw + m + 2 * BMAX : nullptr;
+                double hv = 0.0;
+                // column p of the stored matrix restricted to my rows (= my slice of row p, by symmetry)
+                if (tid3 < cp) hv = P[(size_t)p * cp + tid3];
+                unsigned long long a0 = 0, a1 = 0, w0[WQ];
+                if (pa) {
+                    a0 = __hip_atomic_load(pa, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    a1 = __hip_atomic_load(pa + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int q = 0; q < WQ; ++q) {
+                    const int i = tid3 + q * T3;
+                    w0[q] = (i < m) ? __hip_atomic_load(pw + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+                }
+                double rp = 0.0;                  // reciprocal pivot of my pending row: asked for ahead of the waits
+                if (r_hist) rp = rpivs[kk_hist];
+                if (r_prev) rp = rpivprev[kk_prev];
+                if (tid3 == 0) {
+                    const int ct = p >> 4;
+                    misc[4] = (bg_active && (ct / NBG) >= seq_done[NPOLL + ct % NBG]) ? 1 : 0;
+                }
 #ifdef ZIPLM_LAZY_TIMING
-            if (b == 1 && tid == 64 && owner != b) {      // was the payload there at the first look?
-                const unsigned long long v0 = __hip_atomic_load(pw + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                S.timing[8 + 1024] += 1;
-                S.timing[8 + 1025] += ((unsigned)(v0 & 0xffffffffu) == tag) ? 1 : 0;
-            }
+                if (b == 1 && tid3 == 64 && owner != b) {      // was the payload there at the first look?
+                    S.timing[8 + 1024] += 1;
+                    S.timing[8 + 1025] += ((unsigned)(w0[0] & 0xffffffffu) == tag) ? 1 : 0;
+                }
 #endif
-            for (int i = tid; i < m; i += LT) {
-                unsigned v;
-                if (!ll_wait(pw + i, tag, v, S.status)) { fail = true; break; }
-                wcol[i] = __uint_as_float(v);
-            }
-            if (tid >= LT - BMAX && tid - (LT - BMAX) < k) {
-                const int kk = tid - (LT - BMAX);
-                unsigned hi, lo;
-                const double rp = rpivs[kk];
-                if (!ll_wait2(pw + m + 2 * kk, tag, hi, lo, S.status)) fail = true;
-                else cvec[kk] = dmake(hi, lo) * rp;
-            }
-            if (tid == LT - BMAX - 1) {
-                unsigned hi, lo;
-                if (!ll_wait2(pw + m + 2 * BMAX, tag, hi, lo, S.status)) fail = true;
-                else {
-                    // reciprocal by two Newton steps from the hardware estimate: short enough not to hold up the barrier
-                    const double pv = dmake(hi, lo);
-                    double r = __builtin_amdgcn_rcp(pv);
-                    r = __builtin_fma(__builtin_fma(-pv, r, 1.0), r, r);
-                    r = __builtin_fma(__builtin_fma(-pv, r, 1.0), r, r);
-                    misc_d[1] = pv;
-                    misc_d[2] = r;
+                if (tid3 < cp) hstale[tid3] = hv;
+                if (pa) {
+                    unsigned hi = (unsigned)(a0 >> 32), lo = (unsigned)(a1 >> 32);
+                    const bool there = (unsigned)(a0 & 0xffffffffu) == tag && (unsigned)(a1 & 0xffffffffu) == tag;
+                    if (!there && !ll_wait2(pa, tag, hi, lo, S.status)) fail = true;
+                    const double val = dmake(hi, lo);
+                    if (r_hist) cvec[kk_hist] = val * rp;
+                    else if (r_prev) cprev[kk_prev] = val * rp;
+                    else {
+                        // reciprocal by two Newton steps from the hardware estimate: short enough not to hold up the barrier
+                        double r = __builtin_amdgcn_rcp(val);
+                        r = __builtin_fma(__builtin_fma(-val, r, 1.0), r, r);
+                        r = __builtin_fma(__builtin_fma(-val, r, 1.0), r, r);
+                        misc_d[1] = val;
+                        misc_d[2] = r;
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < WQ; ++q) {
+                    const int i = tid3 + q * T3;
+                    if (i < m) {
+                        unsigned v = (unsigned)(w0[q] >> 32);
+                        if ((unsigned)(w0[q] & 0xffffffffu) != tag && !ll_wait(pw + i, tag, v, S.status)) fail = true;
+                        wcol[i] = __uint_as_float(v);
+                    }
+                }
+                for (int i = tid3 + WQ * T3; i < m && !fail; i += T3) {        // layers with more than 1152 rows
+                    unsigned v;
+                    if (!ll_wait(pw + i, tag, v, S.status)) { fail = true; break; }
+                    wcol[i] = __uint_as_float(v);
                 }
             }
             if (fail) misc[0] = 1;
