@@ -404,17 +404,22 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
 #pragma unroll
         for (int q = 0; q < GR / 4; ++q) Wt[wave + 4 * q][lane] = wv[q];
         lds_barrier();
-        const int nks = (min(GR, r_end - i0) + 3) / 4;
+        // k groups of four rows, in whole blocks of eight (rows past the end were staged as zeros): a loop around
+        // matrix-core instructions is only unrolled when its trip count is known to be a multiple of the factor
+        const int nks8 = (min(GR, r_end - i0) + 31) / 32;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
             const int tile = wave + 4 * x;
             if (tile < nt * nt) {                       // wave-uniform
                 const int ta = tile / nt, tb = tile % nt;
-#pragma unroll 8
-                for (int ks = 0; ks < nks; ++ks) {
-                    const double av = (double)Wt[4 * ks + q4][16 * ta + cl16];
-                    const double bv = (double)Wt[4 * ks + q4][16 * tb + cl16];
-                    acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[x], 0, 0, 0);
+                for (int k8 = 0; k8 < nks8; ++k8) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int ks = 8 * k8 + e;
+                        const double av = (double)Wt[4 * ks + q4][16 * ta + cl16];
+                        const double bv = (double)Wt[4 * ks + q4][16 * tb + cl16];
+                        acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc[x], 0, 0, 0);
+                    }
                 }
             }
         }
