@@ -13,8 +13,8 @@
 // Rows of Hd that belong to removed columns are skipped; removed columns are masked per lane.
 //
 // Larger structures (2 <= group_size <= 64): two ordinary launches per step,
-//     score  (eight workgroups per live structure: block inverse in registers, Gram contraction of an eighth
-//             of the rows on the fp64 matrix cores)
+//     score  (eight workgroups per live structure: block inverse and Gram contraction of an eighth of the
+//             rows, both on the fp64 matrix cores)
 //     update (every workgroup picks the cheapest structure itself from the scores and forms the coefficients
 //             C_H = Hd[:,S] B, C_W = W[:,S] B of its own rows on the fly; both products on the fp64 matrix cores),
 // because on this machine a dependent launch costs more than the arithmetic of a step.
@@ -335,25 +335,63 @@ __global__ __launch_bounds__(256) void group_init_kernel(PruneState P, BatchShif
 
 typedef double doublex4 __attribute__((ext_vector_type(4)));
 
-// SCORE_PARTS workgroups per structure s, each with its own share of the rows of W:
-//   G = W[rows,S]^T W[rows,S]  (g x g, fp64) on the fp64 matrix cores (v_mfma_f64_16x16x4_f64: lane l supplies
-//       A[row l%16][k l/16] and B[k l/16][col l%16], accumulator v holds D[row 4v + l/16][col l%16]), the
-//       rows of W streamed through LDS 64 at a time, four 16 x 16 tiles of G per wavefront.  The whole Gram
-//       matrix of a 768 x 64 structure is 3072 such instructions, 20 us on the four SIMDs of one compute
-//       unit: that, not memory, is why the rows are shared out;
-//   B = (Hd[S,S])^-1 by Gauss-Jordan elimination in registers (the pivots of a positive definite block are its
-//       successive Schur complements, all > 0; no pivoting), repeated by every part: same inputs, same
-//       operations, same B everywhere; part 0 stores it for the update launch;
-//   score_s[part] = sum_{i in rows} w_i B w_i^T = <B, G>; the update launch adds the parts in index order.
+// Inverse of a symmetric positive definite 4 x 4 block by 2 x 2 blocks (Schur complement of the leading block).
+// Only the upper triangle of p is read.  Returns false if one of the four successive pivots is not positive
+// (they are p00, det A / p00, s00, det S / s00 with A the leading block and S the Schur complement).
+__device__ __forceinline__ double rcp_newton(double x) {
+    double r = __builtin_amdgcn_rcp(x);
+    r = __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+    return __builtin_fma(__builtin_fma(-x, r, 1.0), r, r);
+}
+__device__ __forceinline__ bool spd4_inverse(const double (&p)[4][4], double (&q)[4][4]) {
+    const double det_a = __builtin_fma(p[0][0], p[1][1], -p[0][1] * p[0][1]);
+    const double ia = rcp_newton(det_a);
+    const double a00 = p[1][1] * ia, a01 = -p[0][1] * ia, a11 = p[0][0] * ia;          // A^-1
+    // T = A^-1 B with B = p[0..1][2..3]
+    const double t00 = __builtin_fma(a00, p[0][2], a01 * p[1][2]), t01 = __builtin_fma(a00, p[0][3], a01 * p[1][3]);
+    const double t10 = __builtin_fma(a01, p[0][2], a11 * p[1][2]), t11 = __builtin_fma(a01, p[0][3], a11 * p[1][3]);
+    // S = D - B^T T
+    const double s00 = p[2][2] - __builtin_fma(p[0][2], t00, p[1][2] * t10);
+    const double s01 = p[2][3] - __builtin_fma(p[0][2], t01, p[1][2] * t11);
+    const double s11 = p[3][3] - __builtin_fma(p[0][3], t01, p[1][3] * t11);
+    const double det_s = __builtin_fma(s00, s11, -s01 * s01);
+    const double is = rcp_newton(det_s);
+    const double i00 = s11 * is, i01 = -s01 * is, i11 = s00 * is;                      // S^-1
+    q[2][2] = i00; q[2][3] = q[3][2] = i01; q[3][3] = i11;
+    q[0][2] = q[2][0] = -__builtin_fma(t00, i00, t01 * i01);                            // -T S^-1
+    q[0][3] = q[3][0] = -__builtin_fma(t00, i01, t01 * i11);
+    q[1][2] = q[2][1] = -__builtin_fma(t10, i00, t11 * i01);
+    q[1][3] = q[3][1] = -__builtin_fma(t10, i01, t11 * i11);
+    q[0][0] = a00 - __builtin_fma(q[0][2], t00, q[0][3] * t01);                          // A^-1 + T S^-1 T^T
+    q[0][1] = q[1][0] = a01 - __builtin_fma(q[0][2], t10, q[0][3] * t11);
+    q[1][1] = a11 - __builtin_fma(q[1][2], t10, q[1][3] * t11);
+    return p[0][0] > 0.0 && det_a > 0.0 && s00 > 0.0 && det_s > 0.0;
+}
+
+// SCORE_PARTS workgroups per structure s, each with its own share of the rows of W.  Both g x g matrices of a
+// workgroup live in the accumulator layout of v_mfma_f64_16x16x4_f64 (lane l supplies A[row l%16][k l/16] and
+// B[k l/16][col l%16]; accumulator v holds D[row 4v + l/16][col l%16]): wavefront w holds tile row w, i.e.
+// element v of tile tb is entry [16 w + 4 v + l/16][16 tb + l%16].
+//   G = W[rows,S]^T W[rows,S]  (fp64) from the rows of W staged in LDS, 128 at a time.  The whole Gram matrix of
+//       a 768 x 64 structure is 3072 matrix instructions, 20 us on the four SIMDs of one compute unit: that,
+//       not memory, is why the rows are shared out;
+//   B = (Hd[S,S])^-1 by the symmetric sweep, four pivots at a time: with K the pivots and Q = M[K,K]^-1,
+//           M[K,K] <- -Q,  M[K,j] <- Q M[K,j],  M[i,K] <- (Q M[K,i])^T,  M[i,j] <- M[i,j] - M[i,K] Q M[K,j],
+//       which ends at -B after g / 4 steps.  The matrix stays symmetric, so all a step needs from other
+//       wavefronts are the four rows K; they go through LDS (the four pivots of a step are exactly the rows
+//       one accumulator element of one wavefront holds), every thread inverts the 4 x 4 pivot block itself, and
+//       the rank-4 update of a tile is ONE matrix instruction.  An elimination that kept a column per thread
+//       and eliminated pivot by pivot was bound by LDS traffic (32 broadcast values per thread and pivot pair).
+//       The pivots of a positive definite block are its successive Schur complements, all > 0: no pivoting;
+//       a non-positive one is the error path.  Every part repeats the inversion (same inputs, same operations,
+//       same B); part 0 stores B for the update launch;
+//   score_s[part] = sum_{i in rows} w_i B w_i^T = <B, G>, straight from the two register sets; the update
+//       launch adds the parts in index order.
 __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShift B, int step) {
     P = layer_state(P, B, blockIdx.z);
     constexpr int GR = 128;                      // rows of W per pass of the Gram product
-    // the Gram product's staging area and the inverse's final home are never live together
-    __shared__ __attribute__((aligned(16))) unsigned char stage[sizeof(float) * GR * (GMAX + 4)];
-    static_assert(sizeof(stage) >= sizeof(double) * GMAX * (GMAX + 1), "the inverse must fit the staging area");
-    float (*Wt)[GMAX + 4] = reinterpret_cast<float (*)[GMAX + 4]>(stage);
-    double (*Bm)[GMAX + 1] = reinterpret_cast<double (*)[GMAX + 1]>(stage);
-    __shared__ __attribute__((aligned(16))) double rowk[2][2][GMAX], colk[2][2][4][GMAX / 4];
+    __shared__ __attribute__((aligned(16))) float Wt[GR][GMAX + 4];
+    __shared__ __attribute__((aligned(16))) double Rk[2][4][GMAX];     // the four pivot rows of a step, two buffers
     __shared__ double red[256];
     __shared__ int bad;
     const int s = blockIdx.x, tid = threadIdx.x, g = P.g, d = P.d;
@@ -367,14 +405,16 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
     // of the inverse Hessian and the first rows of W are all asked for before any of them is looked at.
     const int status = *P.status;
     const int ds = P.dead_step[s];
-    // The g x g block lives in registers: this thread holds column `lane`, rows wave + 4 q; beyond g the matrix
-    // is continued by the identity, which the elimination leaves alone.
-    double cur[GMAX / 4];
+    // The g x g block in accumulator layout; beyond g the matrix is continued by the identity, which the
+    // elimination leaves alone.
+    doublex4 bacc[4];
 #pragma unroll
-    for (int q = 0; q < GMAX / 4; ++q) {
-        const int i = wave + 4 * q;
-        cur[q] = (i < g && lane < g) ? P.Hd[(size_t)(c0 + i) * d + c0 + lane] : (i == lane ? 1.0 : 0.0);
-    }
+    for (int tb = 0; tb < 4; ++tb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            const int i = 16 * wave + 4 * v + q4, j = 16 * tb + cl16;
+            bacc[tb][v] = (i < g && j < g) ? P.Hd[(size_t)(c0 + i) * d + c0 + j] : (i == j ? 1.0 : 0.0);
+        }
     float wv[GR / 4];                            // rows wave + 4 q of the pass, column `lane` of the structure
     auto load_rows = [&](int i0) {
 #pragma unroll
@@ -391,7 +431,7 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
     }
     if (tid == 0) bad = 0;
 
-    // ---- Gram matrix: tiles (ta, tb) of 16 x 16, tile index = wave + 4 * x, x < 4 (g <= 64)
+    // ---- Gram matrix: this wavefront's tile row, tiles (wave, x), x < 4 (g <= 64)
     const int nt = (g + 15) / 16;
     doublex4 acc[4];
 #pragma unroll
@@ -409,9 +449,8 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
         const int nks8 = (min(GR, r_end - i0) + 31) / 32;
 #pragma unroll
         for (int x = 0; x < 4; ++x) {
-            const int tile = wave + 4 * x;
-            if (tile < nt * nt) {                       // wave-uniform
-                const int ta = tile / nt, tb = tile % nt;
+            if (wave < nt && x < nt) {                  // wave-uniform
+                const int ta = wave, tb = x;
                 for (int k8 = 0; k8 < nks8; ++k8) {
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
@@ -424,65 +463,62 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
             }
         }
     }
-    lds_barrier();          // Wt is dead from here on: its memory becomes Bm at the end of the elimination
-
-    // ---- B = A^-1 in place, two pivots at a time (block Gauss-Jordan).  With K = {k0, k0 + 1}, P = A[K,K]:
-    //     A[K,K] <- P^-1,  A[K,j] <- P^-1 A[K,j],  A[i,K] <- -A[i,K] P^-1,  A[i,j] <- A[i,j] - A[i,K] (P^-1 A[K,j]).
-    // A step needs rows K (one value per lane each, held by two wavefronts) and columns K (sixteen values per
-    // wavefront each, held by lanes k0 and k0 + 1): they go through LDS, and that round trip, not the arithmetic,
-    // is what a step costs, hence two pivots per trip.  The buffers alternate, so one barrier per step is enough
-    // (a wavefront writes a buffer again only after the barrier of the next step, which every wavefront reaches
-    // after its reads of this one).  After every two steps the sixteen registers rotate by one, so that the rows
-    // handed out are always register 0 of wavefronts 0,1 or 2,3 and the loop needs neither full unrolling nor
-    // indexed registers: register q holds row wave + 4 ((q + nrot) % 16).
-    int nrot = 0;
+    // ---- -B by the symmetric sweep, four pivots per step
     bool stop = false;
-    for (int kq = 0; 4 * kq < g && !stop; ++kq) {
+    for (int ta = 0; ta < 4 && !stop; ++ta) {
 #pragma unroll
-        for (int r = 0; r < 2; ++r) {
-            const int k0 = 4 * kq + 2 * r;
-            if (k0 >= g) break;
-            if ((wave >> 1) == r) rowk[r][wave & 1][lane] = cur[0];
-            if ((lane >> 1) == (k0 >> 1)) {
+        for (int v = 0; v < 4; ++v) {
+            const int k0 = 16 * ta + 4 * v;          // pivots k0 .. k0 + 3: element v of tile row ta, one per q4
+            if (k0 >= g) { stop = true; break; }
+            const int buf = v & 1;
+            if (wave == ta) {
 #pragma unroll
-                for (int q = 0; q < GMAX / 4; ++q) colk[r][lane & 1][wave][q] = cur[q];
+                for (int tb = 0; tb < 4; ++tb) Rk[buf][q4][16 * tb + cl16] = bacc[tb][v];
             }
-            __syncthreads();
-            const double p00 = rowk[r][0][k0], p01 = rowk[r][0][k0 + 1], p11 = rowk[r][1][k0 + 1];
-            const double det = __builtin_fma(p00, p11, -p01 * p01);
-            // both pivots of the pair are positive iff p00 > 0 and det > 0 (the second one is det / p00)
-            if (!(p00 > 0.0) || !(det > 0.0)) {          // uniform: every thread read the same values
+            // one barrier per step: a buffer is written again two steps later, behind the barrier of the step in
+            // between, which every wavefront reaches after its reads of this one
+            lds_barrier();
+            double pv[4][4], qv[4][4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+#pragma unroll
+                for (int f = 0; f < 4; ++f) pv[e][f] = Rk[buf][e][k0 + f];
+            if (!spd4_inverse(pv, qv)) {            // uniform: every thread read the same block
                 if (tid == 0) bad = 1;
                 stop = true;
                 break;
             }
-            // 1 / det by Newton steps from the hardware estimate: the quotient sits on the chain of all steps
-            double idet = __builtin_amdgcn_rcp(det);
-            idet = __builtin_fma(__builtin_fma(-det, idet, 1.0), idet, idet);
-            idet = __builtin_fma(__builtin_fma(-det, idet, 1.0), idet, idet);
-            const double q00 = p11 * idet, q01 = -p01 * idet, q11 = p00 * idet;      // P^-1 (symmetric)
-            const double r0 = rowk[r][0][lane], r1 = rowk[r][1][lane];
-            // this column's entries of the new rows K; for the columns of K themselves the columns of P^-1
-            const bool j0 = lane == k0, j1 = lane == k0 + 1, jK = j0 || j1;
-            const double s0 = j0 ? q00 : j1 ? q01 : __builtin_fma(q00, r0, q01 * r1);
-            const double s1 = j0 ? q01 : j1 ? q11 : __builtin_fma(q01, r0, q11 * r1);
+            // row q4 of Q for this lane
+            double qrow[4];
 #pragma unroll
-            for (int q = 0; q < GMAX / 4; ++q) {
-                const double c0v = colk[r][0][wave][q], c1v = colk[r][1][wave][q];
-                double v = __builtin_fma(-c1v, s1, __builtin_fma(-c0v, s0, jK ? 0.0 : cur[q]));
-                if (q == 0 && (wave >> 1) == r) v = (wave & 1) ? s1 : s0;          // rows K themselves
-                cur[q] = v;
+            for (int f = 0; f < 4; ++f) qrow[f] = (q4 == 0) ? qv[0][f] : (q4 == 1) ? qv[1][f] : (q4 == 2) ? qv[2][f] : qv[3][f];
+            // B operands: S = Q M[K,:] restricted to this lane's k (= q4) and columns; for the columns of K minus Q
+            const bool col_in_k = (cl16 >> 2) == v;          // within tile column ta
+            const int cf = cl16 & 3;
+            const double minus_q = -((cf == 0) ? qrow[0] : (cf == 1) ? qrow[1] : (cf == 2) ? qrow[2] : qrow[3]);
+            double sop[4];
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) {
+                const int j = 16 * tb + cl16;
+                double acc_s = qrow[0] * Rk[buf][0][j];
+                acc_s = __builtin_fma(qrow[1], Rk[buf][1][j], acc_s);
+                acc_s = __builtin_fma(qrow[2], Rk[buf][2][j], acc_s);
+                acc_s = __builtin_fma(qrow[3], Rk[buf][3][j], acc_s);
+                sop[tb] = (tb == ta && col_in_k) ? minus_q : acc_s;
+            }
+            // A operand: column K_q4 of this wavefront's rows = row K_q4 at those columns (symmetry)
+            const double aop = -Rk[buf][q4][16 * wave + cl16];
+#pragma unroll
+            for (int tb = 0; tb < 4; ++tb) {
+                doublex4 base = bacc[tb];
+                if (tb == ta && col_in_k) base = doublex4{0.0, 0.0, 0.0, 0.0};
+                base = __builtin_amdgcn_mfma_f64_16x16x4f64(aop, sop[tb], base, 0, 0, 0);
+                if (wave == ta) base[v] = sop[tb];          // rows K themselves
+                bacc[tb] = base;
             }
         }
-        const double first = cur[0];
-#pragma unroll
-        for (int q = 0; q + 1 < GMAX / 4; ++q) cur[q] = cur[q + 1];
-        cur[GMAX / 4 - 1] = first;
-        ++nrot;
     }
-#pragma unroll
-    for (int q = 0; q < GMAX / 4; ++q) Bm[wave + 4 * ((q + nrot) & 15)][lane] = cur[q];
-    __syncthreads();
+    lds_barrier();
     if (bad) {
         if (tid == 0 && part_idx == 0) atomicCAS(P.status, 0, 1 + step);
         return;
@@ -490,26 +526,20 @@ __global__ __launch_bounds__(256) void group_score_kernel(PruneState P, BatchShi
     if (part_idx == 0) {
         double *Bout = P.Binv + (size_t)s * g * g;
 #pragma unroll
-        for (int q = 0; q < GMAX / 4; ++q) {
-            const int i = wave + 4 * ((q + nrot) & 15);
-            if (i < g && lane < g) Bout[i * g + lane] = cur[q];
-        }
-    }
-
-    // ---- <B, G>: each lane holds G[16 ta + 4 v + q4][16 tb + cl16]
-    double part = 0.0;
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        const int tile = wave + 4 * x;
-        if (tile < nt * nt) {
-            const int ta = tile / nt, tb = tile % nt;
+        for (int tb = 0; tb < 4; ++tb)
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                const int a = 16 * ta + 4 * v + q4, c = 16 * tb + cl16;
-                if (a < g && c < g) part += Bm[a][c] * acc[x][v];
+                const int i = 16 * wave + 4 * v + q4, j = 16 * tb + cl16;
+                if (i < g && j < g) Bout[i * g + j] = -bacc[tb][v];
             }
-        }
     }
+
+    // ---- <B, G>: both in the same layout; G is zero beyond g
+    double part = 0.0;
+#pragma unroll
+    for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) part -= bacc[x][v] * acc[x][v];
     red[tid] = part;
     __syncthreads();
     for (int o = 128; o > 0; o >>= 1) {
