@@ -224,8 +224,10 @@ __global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1
     }
     __syncthreads();
 
-    // ---- matrix cores: D22 -= L21 L21^T (lower 32 x 32 tiles) and Xs[:, 64:128] -= Xs[:, 0:64] L21^T
-    for (int tile = wave; tile < 11; tile += 4) {
+    // ---- matrix cores: D22 -= L21 L21^T (lower 32 x 32 tiles 0-2) and Xs[:, 64:128] -= Xs[:, 0:64] L21^T (tiles 3-10).
+    // Only the first three are needed by the factorisation of D22 that follows: they and one more go first, the other
+    // seven are done by wavefronts 1-3 while wavefront 0 factors.
+    auto downdate_tile = [&](int tile) {
         if (tile < 3) {
             const int ti = (tile == 0) ? 0 : 1, tj = (tile == 2) ? 1 : 0;
             tile_downdate(&S.Lm[0][0], PITCH_B, 32 * ti, &S.Lm[0][0], PITCH_B, 32 * tj, &S.D22[0][0], PITCH_B, 32 * ti, 32 * tj, lane);
@@ -233,11 +235,14 @@ __global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1
             const int q = tile - 3, rt = q >> 1, ct = q & 1;
             tile_downdate(&S.Xs[0][0], PITCH_X, 32 * rt, &S.Lm[0][0], PITCH_B, 32 * ct, &S.Xs[0][0], PITCH_X, 32 * rt, NB + 32 * ct, lane);
         }
-    }
+    };
+    downdate_tile(wave);
     __syncthreads();
 
-    // ---- second diagonal block in registers
-    if (wave == 0) {
+    // ---- second diagonal block in registers || the remaining coupling tiles
+    if (wave != 0) {
+        for (int tile = 3 + wave; tile < 11; tile += 3) downdate_tile(tile);
+    } else {
         float a[NB];
 #pragma unroll
         for (int c = 0; c < NB; ++c) a[c] = S.D22[lane][c];
@@ -331,12 +336,12 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
     }
 }
 
-// The large merges of the triangular inverse have 48 to 128 output tiles for 256 compute units: their k range
+// The large merges of the triangular inverse have 48 to 256 output tiles for 256 compute units (two workgroups fit on each): their k range
 // is shared by several workgroups.  Accumulator sets (one per workgroup) the workspace provides for that:
 constexpr int MERGE_PARTIAL_SETS = 512;
 static int merge_splits(int M, int N, int64_t K, int batch) {
     const int tiles = ((M + gemm::BM - 1) / gemm::BM) * ((N + gemm::BN - 1) / gemm::BN) * batch;
-    if (tiles > 128 || K < 512) return 1;
+    if (tiles > 256 || K < 512) return 1;
     int n = MERGE_PARTIAL_SETS / tiles;
     if (n > 8) n = 8;
     if (n > K / 128) n = (int)(K / 128);
