@@ -165,6 +165,7 @@ def _run_prune_case(z, oracle, spec, n_remove, snaps):
     (256, 1024, 2048, "normal", 2),     # config-1 shape
     (33, 700, 3000, "gelu", 3),         # two column chunks, ragged rows
     (1, 40, 200, "normal", 4),          # single output row: classic OBS
+    (1300, 192, 800, "normal", 5),      # a column of W longer than the payload phase fetches in its first look
 ])
 def test_prune_single_columns_remove_all(z, oracle, m, d, n, kind, seed):
     spec = workloads.small(m, d, 1, n, x_kind=kind, seed=seed)
