@@ -98,21 +98,35 @@ __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, f
 
 // x L^T = a for one row held in registers, column by column: x_j = a_j / L[j][j], then a_c -= x_j L[c][j] for
 // every c > j (independent multiply-adds).  Lt[j][c] = L[c][j] and the reciprocals of the diagonal are in LDS;
-// rows of Lt are read with 128-bit broadcast reads.
+// rows of Lt are read with 128-bit broadcast reads, and the whole row j + 1 is asked for before row j is used:
+// with one read in flight at a time (what the compiler makes of the plain loop) every read's latency is exposed,
+// five hundred times per row.
 __device__ __forceinline__ void solve_row_in_registers(float (&x)[NB], const float (*Lt)[NB], const float *rdiag) {
+    gemm::floatx4 lcur[NB / 4], lnext[NB / 4];
+    float rcur = rdiag[0], rnext = 0.f;
+#pragma unroll
+    for (int c4 = 0; c4 < NB / 4; ++c4) lcur[c4] = *reinterpret_cast<const gemm::floatx4 *>(&Lt[0][4 * c4]);
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-        const float xj = x[j] * rdiag[j];
+        if (j + 1 < NB) {
+            rnext = rdiag[j + 1];
+#pragma unroll
+            for (int c4 = 0; c4 < NB / 4; ++c4)
+                if (4 * c4 + 3 > j + 1) lnext[c4] = *reinterpret_cast<const gemm::floatx4 *>(&Lt[j + 1][4 * c4]);
+        }
+        const float xj = x[j] * rcur;
         x[j] = xj;
 #pragma unroll
         for (int c4 = 0; c4 < NB / 4; ++c4) {
             if (4 * c4 + 3 > j) {
-                const gemm::floatx4 l = *reinterpret_cast<const gemm::floatx4 *>(&Lt[j][4 * c4]);
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (4 * c4 + e > j) x[4 * c4 + e] -= xj * l[e];
+                    if (4 * c4 + e > j) x[4 * c4 + e] -= xj * lcur[c4][e];
             }
         }
+        rcur = rnext;
+#pragma unroll
+        for (int c4 = 0; c4 < NB / 4; ++c4) lcur[c4] = lnext[c4];
     }
 }
 
