@@ -65,14 +65,19 @@ __device__ __forceinline__ float lane_bcast(float v, int lane) {
 // is the factor, *my_rdiag = 1 / l_(lane,lane), and *first_bad the first column with a non-positive pivot (or -1;
 // such a pivot is replaced by 1 so that the arithmetic stays finite).  Column j of the factor is also written
 // to Lt[j][lane] (LDS): the transposed factor, whose row j the substitution below reads contiguously.
-// Branch-free on purpose: one straight-line block.  The broadcasts of a column are issued sixteen at a time
-// into sixteen scalar registers before the multiply-adds that consume them: issued in pairs, every
-// multiply-add would wait for its own broadcast.
+// Branch-free on purpose: one straight-line block.  Every lane needs the whole column j of the factor: it is
+// written to LDS anyway (the transposed factor) and read back as broadcast 128-bit words, four entries per read;
+// only the entry the next pivot waits for (column j + 1) travels through a register broadcast, so that the chain
+// pivot -> reciprocal root -> scaled column -> next pivot never waits for LDS.  (Sixty-three register broadcasts
+// per column, the earlier form, cost two thirds of the routine's time.)
 __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
     first_bad = -1;
     my_rdiag = 1.f;
+    gemm::floatx4 lprev[NB / 4], lcur[NB / 4];      // column j - 1 and column j of the factor, as read back from LDS
+    float aprev = 0.f;                              // this lane's entry of column j - 1
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
+        // the chain: pivot, reciprocal root, scaled column, and the one update the next pivot waits for
         float piv = lane_bcast(a[j], j);
         const bool bad = !(piv > 0.f);                    // uniform
         first_bad = (bad && first_bad < 0) ? j : first_bad;
@@ -81,19 +86,26 @@ __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, f
         my_rdiag = (lane == j) ? r : my_rdiag;            // 1 / l_jj
         a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
         Lt[j][lane] = a[j];
+        if (j + 1 < NB) a[j + 1] -= a[j] * lane_bcast(a[j], j + 1);
+        // column j back from LDS (in flight during the multiply-adds below) ...
 #pragma unroll
-        for (int g = 0; g < NB / 16; ++g) {               // constant trip counts: everything unrolls
-            float bc[16];
+        for (int c4 = 0; c4 < NB / 4; ++c4)
+            if (4 * c4 + 3 > j + 1) lcur[c4] = *reinterpret_cast<const gemm::floatx4 *>(&Lt[j][4 * c4]);
+        __builtin_amdgcn_sched_barrier(0);
+        // ... while column j - 1, asked for one step ago, updates the columns from j + 1 on
+        if (j > 0) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                if (16 * g + e > j) bc[e] = lane_bcast(a[j], 16 * g + e);
-            __builtin_amdgcn_sched_barrier(0);
+            for (int c4 = 0; c4 < NB / 4; ++c4)
 #pragma unroll
-            for (int e = 0; e < 16; ++e)
-                if (16 * g + e > j) a[16 * g + e] -= a[j] * bc[e];
-            __builtin_amdgcn_sched_barrier(0);
+                for (int e = 0; e < 4; ++e)
+                    if (4 * c4 + e > j) a[4 * c4 + e] -= aprev * lprev[c4][e];
         }
+        __builtin_amdgcn_sched_barrier(0);
+        aprev = a[j];
+#pragma unroll
+        for (int c4 = 0; c4 < NB / 4; ++c4) lprev[c4] = lcur[c4];
     }
+    // (column NB - 1 has nothing left to update)
 }
 
 // x L^T = a for one row held in registers, column by column: x_j = a_j / L[j][j], then a_c -= x_j L[c][j] for
