@@ -209,29 +209,39 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
                                          int M, int N, int tm, int tn, float alpha, float beta,
                                          bool mirror, int wm, int wn, int lane) {
     const int r = lane & 31, half = lane >> 5;
+    // All old values of the thread's four 32 x 32 blocks are requested before the first store: stores to C and
+    // loads from C cannot be reordered by the compiler, and block by block this was four memory round trips
+    // at the end of every workgroup (a quarter of a K = 128 trailing update).
+    float old[2][2][V1 - V0], old_t[2][2][V1 - V0];
+    if (beta != 0.f) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = tn * BN + wn * 64 + j * 32 + r;
+                const int row_base = tm * BM + wm * 64 + i * 32 + 4 * half;
+#pragma unroll
+                for (int v = V0; v < V1; ++v) {
+                    const int row = row_base + 8 * (v >> 2) + (v & 3);
+                    const bool ok = row < M && col < N;
+                    old[i][j][v - V0] = ok ? C[(int64_t)row * ldc + col] : 0.f;
+                    old_t[i][j][v - V0] = (ok && mirror) ? C[(int64_t)col * ldc + row] : 0.f;
+                }
+            }
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int col = tn * BN + wn * 64 + j * 32 + r;
             const int row_base = tm * BM + wm * 64 + i * 32 + 4 * half;
-            float old[V1 - V0], old_t[V1 - V0];
-            if (beta != 0.f) {
-#pragma unroll
-                for (int v = V0; v < V1; ++v) {
-                    const int row = row_base + 8 * (v >> 2) + (v & 3);
-                    const bool ok = row < M && col < N;
-                    old[v - V0] = ok ? C[(int64_t)row * ldc + col] : 0.f;
-                    old_t[v - V0] = (ok && mirror) ? C[(int64_t)col * ldc + row] : 0.f;
-                }
-            }
 #pragma unroll
             for (int v = V0; v < V1; ++v) {
                 const int row = row_base + 8 * (v >> 2) + (v & 3);
                 if (row < M && col < N) {
                     float val = alpha * acc[i][j][v];
                     float vt = val;
-                    if (beta != 0.f) { val += beta * old[v - V0]; vt += beta * old_t[v - V0]; }
+                    if (beta != 0.f) { val += beta * old[i][j][v - V0]; vt += beta * old_t[i][j][v - V0]; }
                     C[(int64_t)row * ldc + col] = val;
                     // symmetric output (M == N): transposed element of a strictly-lower tile
                     if (mirror) C[(int64_t)col * ldc + row] = vt;
