@@ -390,10 +390,11 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.A = c.take<float>(n2);
     l.T = c.take<float>(n2);
     l.S = c.take<float>(n2);
+    // split-K accumulators of the merges; directly behind S, which is free again when the last product runs
+    l.partial = c.take<float>((size_t)MERGE_PARTIAL_SETS * 64 * gemm::THREADS);
     l.dinv = c.take<float>((size_t)(l.dp / NB) * NB * NB);
     l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored 64 x 64 diagonal blocks
     l.loff = c.take<float>((size_t)(l.dp / PW) * NB * NB);    // the block below the first one in every 128 x 128
-    l.partial = c.take<float>((size_t)MERGE_PARTIAL_SETS * 64 * gemm::THREADS);   // split-K accumulators of the merges
     l.lambda = c.take<double>(1);
     l.info = c.take<int>(1);
     l.bytes = c.off;
@@ -493,7 +494,18 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     f.M = d_col; f.N = d_col; f.K = dp;
     f.alpha = 1.f; f.beta = 0.f;
     f.flags = F_TRI_GRID | F_MIRROR | F_KSTART_MAXMN;
-    ZIPLM_HIP_TRY((launch<R_CONTIG, R_CONTIG, true, false>(f, 1, st)));
+    {
+        // All tiles fit the chip at once, so the launch lasts as long as its longest tile: the one at (0, 0) runs
+        // over the whole k range.  Every tile's k range is shared by up to four workgroups; their accumulators
+        // go to S and the merges' buffer behind it (S is free by now).
+        const int tm = (d_col + BM - 1) / BM, tiles = tm * (tm + 1) / 2;
+        const size_t sets = ((char *)l.partial - (char *)l.S) / (sizeof(float) * 64 * THREADS) + MERGE_PARTIAL_SETS;
+        int nsplit = (int)(sets / (size_t)tiles);
+        if (nsplit > 4) nsplit = 4;
+        if (dp < 1024) nsplit = 1;
+        f.partial = l.S;
+        ZIPLM_HIP_TRY((launch_splitk<R_CONTIG, R_CONTIG, true, false>(f, 1, nsplit < 1 ? 1 : nsplit, st)));
+    }
 
     if (lambda_out_host || info_host) {
         double lam = 0.0;
