@@ -598,8 +598,11 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
             }
             if (bg_active && wave >= NPOLL) {
                 int seq = seq_done[wave], part = bgpart[wave];     // written before the previous barrier
+                // ahead of the polling wavefronts in the instruction arbiter: their loop only burns issue slots
+                __builtin_amdgcn_s_setprio(3);
                 bg_unit(seq, part);
                 if (lane == 0) { seq_done[wave] = seq; bgpart[wave] = part; }
+                __builtin_amdgcn_s_setprio(0);
             }
             const int nwaves_used = min(NW, (nb + 63) / 64);
             if (wave < nwaves_used) {
