@@ -103,17 +103,27 @@ def main():
     hess_ms_all = []
     result = {}
 
-    # configuration 5: the twelve head problems share one shape and go through the batched call (their loops are
-    # latency bound launch sequences; layers do not interact)
-    heads = [q for q in problems if q.spec.group_size > 1] if args.config == 5 else []
-    if heads:
-        hs = heads[0].spec
-        hW = torch.empty((len(heads), hs.d_row, hs.d_col), dtype=torch.float32, device="cuda")
-        hHi = torch.empty((len(heads), hs.d_col, hs.d_col), dtype=torch.float32, device="cuda")
-        ws_b = torch.empty(ziplm.ziplm_prune_batch_workspace_bytes(len(heads), hs.d_row, hs.d_col, hs.group_size, 0),
-                           dtype=torch.uint8, device="cuda")
-        for i, q in enumerate(heads):
-            q.W, q.Hi = hW[i], hHi[i]            # views into the stacks
+    # configuration 5: the twelve problems of either kind share one shape and go through the batched call (the
+    # loops are latency bound; layers do not interact, so several of them run side by side)
+    class Stack:
+        pass
+
+    stacks = []
+    if args.config == 5:
+        for g in sorted({q.spec.group_size for q in problems}):
+            sk = Stack()
+            sk.members = [q for q in problems if q.spec.group_size == g]
+            sk.spec = hs = sk.members[0].spec
+            n = len(sk.members)
+            sk.W = torch.empty((n, hs.d_row, hs.d_col), dtype=torch.float32, device="cuda")
+            sk.Hi = torch.empty((n, hs.d_col, hs.d_col), dtype=torch.float32, device="cuda")
+            sk.ws = torch.empty(ziplm.ziplm_prune_batch_workspace_bytes(n, hs.d_row, hs.d_col, hs.group_size, 0),
+                                dtype=torch.uint8, device="cuda")
+            for i, q in enumerate(sk.members):
+                q.W, q.Hi = sk.W[i], sk.Hi[i]            # views into the stacks
+                q.ws_p = None
+            stacks.append(sk)
+    stacked = {id(q) for sk in stacks for q in sk.members}
 
     def one_step(record):
         marks = []
@@ -127,20 +137,20 @@ def main():
             e[1].record()
             ziplm.ziplm_hinv(q.H, spec.damp_rel, out=q.Hi, workspace=q.ws_i, check=False)
             e[2].record()
-            if q in heads:
-                e[3] = e[2]                      # pruned below, all heads problems together
+            if id(q) in stacked:
+                e[3] = e[2]                      # pruned below, all problems of one shape together
             else:
                 q.order, q.err, _ = ziplm.ziplm_structured_obs_prune(q.W, q.Hi, spec.group_size, spec.n_groups,
                                                                      workspace=q.ws_p, check=False)
                 e[3].record()
             marks.append(e)
-        if heads:
+        for sk in stacks:
             eb = [ev(), ev()]
             eb[0].record()
-            order_b, err_b, _ = ziplm.ziplm_structured_obs_prune_batch(hW, hHi, hs.group_size, hs.n_groups,
-                                                                       workspace=ws_b, check=False)
+            order_b, err_b, _ = ziplm.ziplm_structured_obs_prune_batch(sk.W, sk.Hi, sk.spec.group_size, sk.spec.n_groups,
+                                                                       workspace=sk.ws, check=False)
             eb[1].record()
-            for i, q in enumerate(heads):
+            for i, q in enumerate(sk.members):
                 q.order, q.err = order_b[i], err_b[i]
             marks.append(eb)
         if record:
@@ -166,10 +176,13 @@ def main():
     for marks in result["events"]:
         tot = [0.0, 0.0, 0.0]
         cols = 0.0
-        if heads:
-            tot[2] += marks[-1][0].elapsed_time(marks[-1][1])
+        for sk, eb in zip(stacks, marks[len(problems):]):
+            dt = eb[0].elapsed_time(eb[1])
+            tot[2] += dt
+            if sk.spec.group_size == 1:
+                cols += dt
         for q, e in zip(problems, marks):
-            dt = [e[i].elapsed_time(e[i + 1]) for i in range(2)] + [0.0 if q in heads else e[2].elapsed_time(e[3])]
+            dt = [e[i].elapsed_time(e[i + 1]) for i in range(2)] + [0.0 if id(q) in stacked else e[2].elapsed_time(e[3])]
             tot = [a + b for a, b in zip(tot, dt)]
             if q.spec.group_size == 1:
                 cols += dt[2]
@@ -217,7 +230,7 @@ def main():
     if args.config == 5:
         workload = ("config 5: GPT-2-small-shaped sweep, 12 layers x (attention out-proj W 768x768 in 12 heads of 64 "
                     "columns, N(0,1) inputs + FFN down-proj W 768x3072 single columns, GELU inputs), 32768 tokens each, "
-                    "damp 0.01, remove everything; value = all 24 problems, the twelve head loops in one batched call")
+                    "damp 0.01, remove everything; value = all 24 problems, the twelve loops of either kind in one batched call")
         n_steps_loop = sum(sp.n_groups for sp in column_specs)      # the 12 x 3072 single-column removals
     else:
         spec = specs[0]

@@ -141,8 +141,8 @@ size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_s
 
 /*
  * The same loop for several layers of one shape in one sequence of launches (Section 3.2: every layer
- * is treated independently).  Meant for many small problems, such as the attention output projections
- * of all layers of a model, whose per-layer launch sequences are latency bound; layers do not interact.
+ * is treated independently).  Meant for the layers of a model: their loops are latency bound, whether a
+ * sequence of small launches (heads) or one persistent launch (single columns); layers do not interact.
  *
  *   W        n_layers matrices d_row x d_col, layer l at W + l*stride_w (stride_w >= d_row*d_col), in/out
  *   Hinv     n_layers matrices d_col x d_col, layer l at Hinv + l*stride_hinv, in/out
@@ -151,9 +151,17 @@ size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_s
  *   info_host   optional host int[n_layers], as in the single-layer call; the return value is
  *            ZIPLM_ERR_NOT_PD / ZIPLM_ERR_DEVICE if any layer reported it (the other layers are complete)
  *
- * 2 <= group_size <= 64 in this build (single columns: ZIPLM_ERR_UNSUPPORTED, call the single-layer
- * function once per layer).  Every layer starts with all structures alive.  Results are identical to
- * n_layers single-layer calls.
+ * 1 <= group_size <= 64 in this build.  Every layer starts with all structures alive.
+ * group_size >= 2: one sequence of launches covers all layers; results are identical to n_layers
+ * single-layer calls.
+ * group_size == 1: the layers are taken up to four at a time; the loops of one such set run side by side
+ * in one launch, each on its share of the compute units, and the sets follow one another on the stream
+ * (a single loop is bound by the hand-off between its workgroups, so four loops on a quarter of the device
+ * each finish in 60% of the time of four loops one after another).  The columns are spread over fewer
+ * workgroups than in the single-layer call, so the deferred eliminations are summed in another order: same
+ * removal order wherever the scores differ by more than rounding, W, Hinv and err equal to rounding, not bit
+ * for bit.  With info_host the call waits for the stream after every set.  The exchange area of the
+ * single-layer call is used here as well.
  */
 int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_layers, int64_t stride_w,
                                      int64_t stride_hinv, int d_row, int d_col, int group_size,

@@ -30,9 +30,12 @@ namespace ziplm {
 int device_cu_count();
 bool lazy_columns_feasible(int d_row, int d_col);
 size_t lazy_columns_workspace_bytes(int d_row, int d_col, int n_snap);
-int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remove, int32_t *order_out,
-                        double *err_out, const uint8_t *alive_in, int n_snap, const int32_t *snap_steps_host,
-                        float *W_snap, void *workspace, hipStream_t st, int **status_dev_out);
+int lazy_columns_pack(int n_layers, int d_row, int d_col);
+size_t lazy_columns_pack_workspace_bytes(int pack, int d_row, int d_col, int n_snap);
+int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64_t stride_hinv, int d_row, int d_col,
+                        int n_remove, int32_t *order_out, double *err_out, const uint8_t *alive_in, int n_snap,
+                        const int32_t *snap_steps_host, float *W_snap, void *workspace, hipStream_t st,
+                        int **status_dev_out);
 
 // The eager single-column kernel is kept as the fallback for shapes the deferred-update kernel
 // cannot hold in LDS, and can be forced with ZIPLM_PRUNE_EAGER=1 for cross-checking.
@@ -842,8 +845,8 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
 
     if (group_size == 1 && use_lazy_columns(d_row, d_col)) {
         int *status_dev = nullptr;
-        const int rc = lazy_columns_launch(W, Hinv, d_row, d_col, n_remove, order_out, err_out, alive_in, n_snap,
-                                           snapshot_steps_host, W_snap, workspace, st, &status_dev);
+        const int rc = lazy_columns_launch(W, Hinv, 1, 0, 0, d_row, d_col, n_remove, order_out, err_out, alive_in,
+                                           n_snap, snapshot_steps_host, W_snap, workspace, st, &status_dev);
         if (rc != ZIPLM_OK) return rc;
         if (info_host) {
             int status = 0;
@@ -897,7 +900,19 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
 
 
 extern "C" size_t ziplm_prune_batch_workspace_bytes(int n_layers, int d_row, int d_col, int group_size, int n_snap) {
-    if (n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size < 2 || group_size > ziplm::GMAX || d_col % group_size) return 0;
+    if (n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size < 1 || group_size > ziplm::GMAX || d_col % group_size) return 0;
+    if (group_size == 1) {
+        // single columns: the launches of a batch run one after the other and share the workspace
+        if (!ziplm::use_lazy_columns(d_row, d_col)) return ziplm_prune_workspace_bytes(d_row, d_col, 1, n_snap);
+        size_t need = 0;
+        for (int done = 0; done < n_layers;) {
+            const int pack = ziplm::lazy_columns_pack(n_layers - done, d_row, d_col);
+            const size_t b = ziplm::lazy_columns_pack_workspace_bytes(pack, d_row, d_col, n_snap);
+            need = b > need ? b : need;
+            done += pack;
+        }
+        return need;
+    }
     return (size_t)n_layers * ziplm::prune_layout(d_row, d_col, group_size, n_snap, nullptr).bytes;
 }
 
@@ -916,10 +931,50 @@ extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_lay
     if (n_snap < 0 || (n_snap > 0 && (!snapshot_steps_host || !W_snap))) return ZIPLM_ERR_INVALID_ARG;
     for (int q = 0; q < n_snap; ++q)
         if (snapshot_steps_host[q] < 0 || snapshot_steps_host[q] > n_remove) return ZIPLM_ERR_INVALID_ARG;
-    if (group_size < 2 || group_size > GMAX) return ZIPLM_ERR_UNSUPPORTED;    // single columns: one launch per layer
+    if (group_size > GMAX) return ZIPLM_ERR_UNSUPPORTED;
     const size_t need = ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap);
     if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (group_size == 1) {
+        // Single columns: a few layers per launch, each on its share of the compute units; the launches follow
+        // one another on the stream and reuse the workspace.
+        int worst = ZIPLM_OK;
+        const size_t snap_stride = (size_t)n_snap * d_row * d_col;
+        for (int done = 0; done < n_layers;) {
+            float *Wl = W + (size_t)done * stride_w, *Hl = Hinv + (size_t)done * stride_hinv;
+            int32_t *ol = order_out ? order_out + (size_t)done * n_remove : nullptr;
+            double *el = err_out ? err_out + (size_t)done * n_remove : nullptr;
+            float *sl = W_snap ? W_snap + (size_t)done * snap_stride : nullptr;
+            if (!use_lazy_columns(d_row, d_col)) {
+                const int rc = ziplm_structured_obs_prune(Wl, Hl, d_row, d_col, 1, n_remove, ol, el, nullptr, n_snap,
+                                                          snapshot_steps_host, sl, info_host ? info_host + done : nullptr,
+                                                          workspace, workspace_bytes, stream);
+                if (rc == ZIPLM_ERR_DEVICE || (rc == ZIPLM_ERR_NOT_PD && worst == ZIPLM_OK)) worst = rc;
+                else if (rc != ZIPLM_OK && rc != ZIPLM_ERR_NOT_PD) return rc;
+                done += 1;
+                continue;
+            }
+            const int pack = lazy_columns_pack(n_layers - done, d_row, d_col);
+            int *status_dev[16] = {};
+            const int rc = lazy_columns_launch(Wl, Hl, pack, stride_w, stride_hinv, d_row, d_col, n_remove, ol, el, nullptr,
+                                               n_snap, snapshot_steps_host, sl, workspace, st, status_dev);
+            if (rc != ZIPLM_OK) return rc;
+            if (info_host) {
+                // the next launch reuses the status words
+                ZIPLM_HIP_TRY(hipStreamSynchronize(st));
+                for (int q = 0; q < pack; ++q) {
+                    int status = 0;
+                    ZIPLM_HIP_TRY(hipMemcpy(&status, status_dev[q], sizeof(int), hipMemcpyDeviceToHost));
+                    info_host[done + q] = status;
+                    if (status > 0 && worst == ZIPLM_OK) worst = ZIPLM_ERR_NOT_PD;
+                    if (status < 0) worst = ZIPLM_ERR_DEVICE;
+                }
+            }
+            done += pack;
+        }
+        return worst;
+    }
 
     PruneLayout l = prune_layout(d_row, d_col, group_size, n_snap, workspace);
     PruneState &P = l.st;

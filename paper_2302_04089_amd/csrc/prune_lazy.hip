@@ -99,6 +99,16 @@ struct State {
 #endif
 };
 
+// One launch runs the loops of up to MAX_PACK layers of one shape side by side, each on its own nb workgroups
+// (Section 3.2: layers are independent).  A loop is bound by the hand-off between its workgroups, not by
+// arithmetic or bandwidth, so several loops on a share of the compute units each finish sooner than one after
+// another on all of them.  Workgroup x works on layer x / nb; the layers share nothing.
+constexpr int MAX_PACK = 4;
+struct StatePack {
+    State s[MAX_PACK];
+    int nb;                       // workgroups per layer
+};
+
 // ------------------------------------------------------------------------------------------------
 // tagged words
 // ------------------------------------------------------------------------------------------------
@@ -367,15 +377,21 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
 #define TICK(slot) do { } while (0)
 #endif
 
-template <bool W_IN_LDS>
-__global__ __launch_bounds__(LT) void prune_lazy_kernel(State S) {
+// PACKED: several layers share the launch.  The single-layer instantiations address the one State through
+// constant offsets of the kernel argument; with the layer chosen at run time the compiler re-reads fields
+// inside the loop, which costs the single-layer loop 2.5%.
+template <bool W_IN_LDS, bool PACKED>
+__global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
 #ifdef ZIPLM_LAZY_TIMING
     unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     unsigned long long tlast = wall_clock64();
     unsigned long long tlocal = 0, texch = wall_clock64();
 #endif
-    const int b = blockIdx.x, nb = gridDim.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nb = PACKED ? pack.nb : (int)gridDim.x;
+    const int layer = PACKED ? blockIdx.x / nb : 0, b = blockIdx.x - layer * nb;
+    const State &S = pack.s[layer];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int m = S.m, d = S.d, cpb = S.cpb, cp = S.cp;
     const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb);
     double *uloc = reinterpret_cast<double *>(smem + L.uloc);
@@ -886,9 +902,10 @@ struct Plan {
     bool feasible;
 };
 
-static Plan make_plan(int d_row, int d_col) {
+// pack: layers that share the launch; each gets an equal share of the compute units
+static Plan make_plan(int d_row, int d_col, int pack = 1) {
     Plan p = {};
-    const int cus = device_cu_count();
+    const int cus = max(1, device_cu_count() / pack);
     p.cpb = (d_col + cus - 1) / cus;
     p.cp = (p.cpb + RG - 1) / RG * RG;
     p.nb = (d_col + p.cpb - 1) / p.cpb;
@@ -945,17 +962,18 @@ constexpr int EXCHANGE_MAX_DEVICES = 64;
 static ExchangeArea g_exchange[EXCHANGE_MAX_DEVICES];
 static std::mutex g_exchange_mutex;
 
+// per layer
 static size_t exchange_bytes_needed(const Plan &p) {
     return align_up(sizeof(unsigned long long) * (size_t)2 * p.nb) + align_up(sizeof(unsigned long long) * (size_t)2 * p.nb * p.pay_words);
 }
 
 // Caller holds g_exchange_mutex.  nullptr: use the workspace.
-static ExchangeArea *exchange_area_for(const Plan &p) {
+static ExchangeArea *exchange_area_for(const Plan &p, int pack) {
     const char *e = getenv("ZIPLM_EXCHANGE_IN_WORKSPACE");
     if (e && e[0] == '1') return nullptr;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= EXCHANGE_MAX_DEVICES) return nullptr;
-    if (exchange_bytes_needed(p) > EXCHANGE_BYTES) return nullptr;
+    if ((size_t)pack * exchange_bytes_needed(p) > EXCHANGE_BYTES) return nullptr;
     ExchangeArea &a = g_exchange[dev];
     if (!a.tried) {
         a.tried = true;
@@ -983,49 +1001,85 @@ size_t lazy_columns_workspace_bytes(int d_row, int d_col, int n_snap) {
     return lazy::make_layout(d_row, d_col, n_snap, p, nullptr).bytes;
 }
 
-// Enqueues the whole loop.  *status_dev_out receives the device address of the status word.
-int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remove, int32_t *order_out,
-                        double *err_out, const uint8_t *alive_in, int n_snap, const int32_t *snap_steps_host,
-                        float *W_snap, void *workspace, hipStream_t st, int **status_dev_out) {
+// Layers of one shape that one launch takes side by side when n_layers are waiting: as many as the kernel's
+// argument holds, fewer while a layer's share of the compute units cannot hold its state.
+int lazy_columns_pack(int n_layers, int d_row, int d_col) {
+    int pack = n_layers < lazy::MAX_PACK ? n_layers : lazy::MAX_PACK;
+    while (pack > 1 && !lazy::make_plan(d_row, d_col, pack).feasible) --pack;
+    return pack < 1 ? 1 : pack;
+}
+
+// workspace of one launch of `pack` layers
+size_t lazy_columns_pack_workspace_bytes(int pack, int d_row, int d_col, int n_snap) {
+    const lazy::Plan p = lazy::make_plan(d_row, d_col, pack);
+    return (size_t)pack * lazy::make_layout(d_row, d_col, n_snap, p, nullptr).bytes;
+}
+
+// Enqueues the whole loop of `pack` layers (layer l: W + l * stride_w, Hinv + l * stride_hinv, order_out and
+// err_out + l * n_remove, W_snap + l * n_snap * d_row * d_col).  status_dev_out[l] receives the device address
+// of layer l's status word.  alive_in applies to a single layer only.
+int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64_t stride_hinv, int d_row, int d_col,
+                        int n_remove, int32_t *order_out, double *err_out, const uint8_t *alive_in, int n_snap,
+                        const int32_t *snap_steps_host, float *W_snap, void *workspace, hipStream_t st,
+                        int **status_dev_out) {
     using namespace lazy;
-    const Plan p = make_plan(d_row, d_col);
-    Layout l = make_layout(d_row, d_col, n_snap, p, workspace);
-    State &S = l.st;
-    S.W = W; S.Hinv = Hinv; S.m = d_row; S.d = d_col; S.n_remove = n_remove;
-    S.order = order_out; S.err = err_out; S.alive_in = alive_in;
-    S.n_snap = n_snap; S.snap_steps = l.snap_steps; S.W_snap = W_snap;
-    S.cpb = p.cpb; S.cp = p.cp; S.pay_words = p.pay_words;
+    if (pack < 1 || pack > MAX_PACK || (pack > 1 && alive_in)) return ZIPLM_ERR_INVALID_ARG;
+    const Plan p = make_plan(d_row, d_col, pack);
+    if (!p.feasible) return ZIPLM_ERR_UNSUPPORTED;
+    const size_t layer_bytes = make_layout(d_row, d_col, n_snap, p, nullptr).bytes;
+    StatePack pk = {};
+    pk.nb = p.nb;
+    Layout lay[MAX_PACK];
+    for (int q = 0; q < pack; ++q) {
+        lay[q] = make_layout(d_row, d_col, n_snap, p, static_cast<char *>(workspace) + (size_t)q * layer_bytes);
+        State &S = lay[q].st;
+        S.W = W + (size_t)q * stride_w; S.Hinv = Hinv + (size_t)q * stride_hinv;
+        S.m = d_row; S.d = d_col; S.n_remove = n_remove;
+        S.order = order_out ? order_out + (size_t)q * n_remove : nullptr;
+        S.err = err_out ? err_out + (size_t)q * n_remove : nullptr;
+        S.alive_in = alive_in;
+        S.n_snap = n_snap; S.snap_steps = lay[0].snap_steps;
+        S.W_snap = W_snap ? W_snap + (size_t)q * n_snap * d_row * d_col : nullptr;
+        S.cpb = p.cpb; S.cp = p.cp; S.pay_words = p.pay_words;
+    }
     if (n_snap > 0) {
         // pageable source: staged before the call returns
-        ZIPLM_HIP_TRY(hipMemcpyAsync(l.snap_steps, snap_steps_host, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st));
+        ZIPLM_HIP_TRY(hipMemcpyAsync(lay[0].snap_steps, snap_steps_host, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st));
         ZIPLM_HIP_TRY(hipStreamSynchronize(st));
     }
     std::lock_guard<std::mutex> guard(g_exchange_mutex);       // held until the launch and its event are enqueued
-    ExchangeArea *xa = exchange_area_for(p);
-    // zero-initialised: slots, payload, barrier epochs, status (contiguous in the workspace, in this order)
-    char *zero_from = reinterpret_cast<char *>(S.slots);
+    ExchangeArea *xa = exchange_area_for(p, pack);
     if (xa) {
         if (xa->used) ZIPLM_HIP_TRY(hipStreamWaitEvent(st, xa->last, 0));
         Carver cx(xa->ptr);
-        S.slots = cx.take<unsigned long long>((size_t)2 * p.nb);
-        S.pay = cx.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
+        for (int q = 0; q < pack; ++q) {
+            lay[q].st.slots = cx.take<unsigned long long>((size_t)2 * p.nb);
+            lay[q].st.pay = cx.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
+        }
         ZIPLM_HIP_TRY(hipMemsetAsync(xa->ptr, 0, cx.off, st));
-        zero_from = reinterpret_cast<char *>(S.bar);
     }
-    ZIPLM_HIP_TRY(hipMemsetAsync(zero_from, 0, reinterpret_cast<char *>(l.snap_steps) - zero_from, st));
-    const void *fn = p.w_in_lds ? reinterpret_cast<const void *>(prune_lazy_kernel<true>)
-                                : reinterpret_cast<const void *>(prune_lazy_kernel<false>);
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[p.w_in_lds]) {
+    for (int q = 0; q < pack; ++q) {
+        // zero-initialised: slots, payload, barrier epochs, status (contiguous in the workspace, in this order)
+        Layout ws_lay = make_layout(d_row, d_col, n_snap, p, static_cast<char *>(workspace) + (size_t)q * layer_bytes);
+        char *zero_from = reinterpret_cast<char *>(xa ? (void *)ws_lay.st.bar : (void *)ws_lay.st.slots);
+        ZIPLM_HIP_TRY(hipMemsetAsync(zero_from, 0, reinterpret_cast<char *>(ws_lay.snap_steps) - zero_from, st));
+        pk.s[q] = lay[q].st;
+        status_dev_out[q] = lay[q].st.status;
+    }
+    const int variant = (p.w_in_lds ? 1 : 0) + (pack > 1 ? 2 : 0);
+    void (*const kernels[4])(const StatePack) = {prune_lazy_kernel<false, false>, prune_lazy_kernel<true, false>,
+                                                 prune_lazy_kernel<false, true>, prune_lazy_kernel<true, true>};
+    const void *fn = reinterpret_cast<const void *>(kernels[variant]);
+    static bool attr_set[4] = {false, false, false, false};
+    if (!attr_set[variant]) {
         ZIPLM_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set[p.w_in_lds] = true;
+        attr_set[variant] = true;
     }
     int per_cu = 0;
-    if (p.w_in_lds) ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_lazy_kernel<true>, LT, p.lds_bytes));
-    else ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_lazy_kernel<false>, LT, p.lds_bytes));
-    if (per_cu < 1 || p.nb > per_cu * device_cu_count()) return ZIPLM_ERR_DEVICE;
-    void *args[] = {&S};
-    ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(const_cast<void *>(fn), dim3(p.nb), dim3(LT), args, (unsigned)p.lds_bytes, st));
+    ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernels[variant], LT, p.lds_bytes));
+    if (per_cu < 1 || pack * p.nb > per_cu * device_cu_count()) return ZIPLM_ERR_DEVICE;
+    void *args[] = {&pk};
+    ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(const_cast<void *>(fn), dim3(pack * p.nb), dim3(LT), args, (unsigned)p.lds_bytes, st));
     if (xa) {
         ZIPLM_HIP_TRY(hipEventRecord(xa->last, st));
         xa->used = true;
@@ -1034,25 +1088,24 @@ int lazy_columns_launch(float *W, float *Hinv, int d_row, int d_col, int n_remov
     {
         unsigned long long tm[8];
         hipStreamSynchronize(st);
-        hipMemcpy(tm, S.timing, sizeof(tm), hipMemcpyDeviceToHost);
+        hipMemcpy(tm, lay[0].st.timing, sizeof(tm), hipMemcpyDeviceToHost);
         const char *names[8] = {"snapshot+loop top", "candidate+publish", "exchange+argmin", "payload+gather", "row slice + Eq.3",
                                 "flush barrier", "flush update", "(own slot round trip)"};
         for (int q = 0; q < 8; ++q)
             fprintf(stderr, "[lazy timing] %-20s %9.3f ms total  %7.3f us/step\n", names[q], tm[q] * 1e-5,
                     tm[q] * 1e-2 / (n_remove > 0 ? n_remove : 1));
         unsigned long long loc[1024];
-        hipMemcpy(loc, S.timing + 8, sizeof(unsigned long long) * p.nb, hipMemcpyDeviceToHost);
+        hipMemcpy(loc, lay[0].st.timing + 8, sizeof(unsigned long long) * p.nb, hipMemcpyDeviceToHost);
         double mn = 1e30, mx = 0, sum = 0; int imx = 0;
         for (int q = 0; q < p.nb; ++q) { double v = loc[q] * 1e-2 / (n_remove > 0 ? n_remove : 1); sum += v; if (v < mn) mn = v; if (v > mx) { mx = v; imx = q; } }
         fprintf(stderr, "[lazy timing] local us/step (exchange done -> slot published): min %.3f avg %.3f max %.3f (block %d)\n", mn, sum / p.nb, mx, imx);
-        { unsigned long long pr[2]; hipMemcpy(pr, S.timing + 8 + 1024, sizeof(pr), hipMemcpyDeviceToHost);
+        { unsigned long long pr[2]; hipMemcpy(pr, lay[0].st.timing + 8 + 1024, sizeof(pr), hipMemcpyDeviceToHost);
           if (pr[0]) fprintf(stderr, "[lazy timing] winner's payload already visible at the first read of step 3: %.1f%% of %llu steps (workgroup 1)\n", 100.0 * pr[1] / pr[0], pr[0]); }
         { double x[8] = {0}; int c[8] = {0}; for (int q = 0; q < p.nb; ++q) { x[q & 7] += loc[q] * 1e-2 / n_remove; c[q & 7]++; }
           fprintf(stderr, "[lazy timing] local us/step by workgroup index mod 8:"); for (int q = 0; q < 8; ++q) fprintf(stderr, " %.3f", x[q] / (c[q] ? c[q] : 1)); fprintf(stderr, "\n");
           fprintf(stderr, "[lazy timing] local us/step by workgroup index / 32:"); for (int g = 0; g < 8; ++g) { double a = 0; int n = 0; for (int q = 32 * g; q < 32 * g + 32 && q < p.nb; ++q) { a += loc[q] * 1e-2 / n_remove; ++n; } fprintf(stderr, " %.3f", n ? a / n : 0.0); } fprintf(stderr, "\n"); }
     }
 #endif
-    *status_dev_out = S.status;
     return ZIPLM_OK;
 }
 

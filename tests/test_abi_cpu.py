@@ -80,10 +80,16 @@ def test_argument_errors_return_before_any_device_work(L):
     assert pr(one, one, 2, 8, 1, 1, one, one, None, 0, None, None, None, None, 0, None) == -3
     pb = L.ziplm_structured_obs_prune_batch
     assert L.ziplm_prune_batch_workspace_bytes(12, 768, 768, 64, 0) == 12 * L.ziplm_prune_workspace_bytes(768, 768, 64, 0)
-    assert L.ziplm_prune_batch_workspace_bytes(12, 768, 768, 1, 0) == 0          # single columns are not batched
+    # single columns: a batch runs as a sequence of launches of a few layers each, which share the workspace
+    one_layer = L.ziplm_prune_workspace_bytes(768, 3072, 1, 0)
+    assert L.ziplm_prune_batch_workspace_bytes(1, 768, 3072, 1, 0) == one_layer
+    assert 0 < L.ziplm_prune_batch_workspace_bytes(12, 768, 3072, 1, 0) <= 4 * one_layer
+    assert L.ziplm_prune_batch_workspace_bytes(12, 768, 3072, 1, 0) == L.ziplm_prune_batch_workspace_bytes(4, 768, 3072, 1, 0)
     assert pb(one, one, 0, 64, 64, 8, 8, 4, 1, one, one, 0, None, None, None, one, big, None) == -1    # no layers
     assert pb(one, one, 2, 63, 64, 8, 8, 4, 1, one, one, 0, None, None, None, one, big, None) == -1    # stride too small
-    assert pb(one, one, 2, 64, 64, 8, 8, 1, 1, one, one, 0, None, None, None, one, big, None) == -5    # single columns
+    assert pb(one, one, 2, 64, 64, 8, 8, 1, 9, one, one, 0, None, None, None, one, big, None) == -1    # single columns: n_remove > G
+    assert pb(one, one, 2, 64, 64, 8, 8, 1, 1, one, one, 0, None, None, None, None, 0, None) == -3
+    assert pb(one, one, 2, 256 * 256, 256 * 256, 8, 256, 128, 1, one, one, 0, None, None, None, one, big, None) == -5   # group too large
     assert pb(one, one, 2, 64, 64, 8, 8, 4, 3, one, one, 0, None, None, None, one, big, None) == -1    # n_remove > G
     assert pb(one, one, 2, 64, 64, 8, 8, 4, 1, one, one, 0, None, None, None, None, 0, None) == -3
     me = L.ziplm_module_error

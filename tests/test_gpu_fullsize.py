@@ -214,3 +214,38 @@ def test_config5_first_layer_matches_oracle(z, oracle):
     The other layers differ only in their seeds."""
     _pipeline_against_oracle(z, oracle, workloads.config(5, layer=0, kind="attn"), "heads")
     _pipeline_against_oracle(z, oracle, workloads.config(5, layer=0, kind="ffn"), "columns")
+
+
+def test_config5_batched_feed_forward_layers(z, oracle):
+    """Configuration 5, the launch shape the benchmark times for its feed-forward layers: four layers (768 x 3072,
+    32768 tokens each) whose loops share one launch, 64 workgroups per layer.  Every layer: each column removed
+    exactly once, W ends at zero, the step errors add up to the whole-module error.  The first and the last
+    layer of the set also go through the complete protocol against the oracle, with the database grid as
+    snapshots."""
+    layers = 4
+    specs = [workloads.config(5, layer=l, kind="ffn") for l in range(layers)]
+    d, m = specs[0].d_col, specs[0].d_row
+    Wb = torch.empty((layers, m, d), dtype=torch.float32, device="cuda")
+    Hb = torch.empty((layers, d, d), dtype=torch.float32, device="cuda")
+    totals, W32s = [], []
+    for l, spec in enumerate(specs):
+        X = torch.from_numpy(workloads.make_X(spec)).cuda()
+        W32s.append(workloads.make_W(spec))
+        Wb[l].copy_(torch.from_numpy(W32s[l]))
+        H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+        z.ziplm_hessian_accumulate(H, X, scale=2.0)
+        del X
+        _, lam = z.ziplm_hinv(H, spec.damp_rel, out=Hb[l])
+        totals.append(float(z.ziplm_module_error(Wb[l], H, lam)[0]))
+    Hi32s = {l: Hb[l].cpu().numpy() for l in (0, layers - 1)}
+    snaps = z.database_steps(d, "columns")
+    order, err, W_snap = z.ziplm_structured_obs_prune_batch(Wb, Hb, 1, d, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    assert float(Wb.abs().max()) == 0.0 and float(Hb.abs().max()) == 0.0
+    for l in range(layers):
+        assert sorted(order[l].cpu().numpy().tolist()) == list(range(d))
+        assert abs(float(err[l].sum()) / totals[l] - 1.0) <= 1e-4
+    for l in (0, layers - 1):
+        ref = compare_run(oracle, W32s[l], Hi32s[l], 1, d, order[l].cpu().numpy(), err[l].cpu().numpy(), snap_steps=snaps)
+        for q, k in enumerate(snaps):
+            assert rel_fro(W_snap[l, q].cpu().numpy(), ref["W_snap"][q]) <= REL_TOL, "layer %d, W after %d removals" % (l, k)

@@ -463,3 +463,49 @@ def test_prune_batch_equals_single_layer_calls_and_oracle(z, oracle):
     o, e, _ = z.ziplm_structured_obs_prune(Wl, Hl, g, 4)
     torch.cuda.synchronize()
     assert torch.equal(Wl, Wb[2]) and torch.equal(Hl, Hb[2])      # the good layers are complete
+
+
+@pytest.mark.parametrize("m,d,n,layers,seed", [
+    (48, 320, 1500, 6, 41),        # launches of four and of two layers
+    (96, 1100, 3300, 5, 51),       # four layers on 64 workgroups each (more columns than wavefronts), then one alone
+])
+def test_prune_batch_single_columns_matches_oracle(z, oracle, m, d, n, layers, seed):
+    """Single-column layers of one shape in one batched call: several loops run side by side in one launch,
+    each on its share of the compute units.  Every layer goes through the oracle protocol (the partition of
+    the columns over workgroups differs from the single-layer call, so the comparison is with the oracle, not
+    bit for bit with that call), snapshots included."""
+    Ws, His = [], []
+    for l in range(layers):
+        spec = workloads.small(m, d, 1, n, x_kind="gelu" if l % 2 else "normal", seed=seed + l)
+        X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+        Ws.append(W32)
+        His.append(Hi32)
+    Wb, Hb = dev(np.stack(Ws)), dev(np.stack(His))
+    snaps = [0, d // 3, d - 5, d]
+    order_b, err_b, snap_b = z.ziplm_structured_obs_prune_batch(Wb, Hb, 1, d, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    assert float(Wb.abs().max()) == 0.0 and float(Hb.abs().max()) == 0.0
+    for l in range(layers):
+        ref = compare_run(oracle, Ws[l], His[l], 1, d, order_b[l].cpu().numpy(), err_b[l].cpu().numpy(), snap_steps=snaps)
+        for q in (1, 2):
+            assert rel_fro(snap_b[l, q].cpu().numpy(), ref["W_snap"][q]) <= REL_TOL, "layer %d snapshot %d" % (l, q)
+        assert torch.equal(snap_b[l, 0].cpu(), torch.from_numpy(Ws[l])) and float(snap_b[l, 3].abs().max()) == 0.0
+
+    # partial removal: W and Hinv of every layer against the oracle; one indefinite layer reports it alone
+    k = d // 2
+    Wb, Hb = dev(np.stack(Ws)), dev(np.stack(His))
+    order_b, err_b, _ = z.ziplm_structured_obs_prune_batch(Wb, Hb, 1, k)
+    torch.cuda.synchronize()
+    for l in range(layers):
+        ref = compare_run(oracle, Ws[l], His[l], 1, k, order_b[l].cpu().numpy(), err_b[l].cpu().numpy())
+        assert rel_fro(Wb[l].cpu().numpy(), ref["W"]) <= REL_TOL and rel_fro(Hb[l].cpu().numpy(), ref["Hinv"]) <= REL_TOL
+    W2, H2 = dev(np.stack(Ws)), dev(np.stack(His))
+    bad = layers - 2
+    H2[bad, 7, 7] = -1.0
+    with pytest.raises(z.ZiplmError) as ei:
+        z.ziplm_structured_obs_prune_batch(W2, H2, 1, k)
+    assert ei.value.status == z.ERR_NOT_PD
+    assert [i > 0 for i in ei.value.info] == [l == bad for l in range(layers)]
+    for l in range(layers):
+        if l != bad:
+            assert torch.equal(W2[l], Wb[l]) and torch.equal(H2[l], Hb[l])      # the good layers are complete
