@@ -60,7 +60,6 @@ constexpr int LT = 1024;                 // threads per workgroup (16 wavefronts
 constexpr int NW = LT / 64;
 constexpr int BMAX = 64;                 // pending pivot rows between flushes (one lane per row)
 constexpr int RG = 16;                   // owned rows per matrix-core pass (panel rows are padded to this)
-constexpr int NTI = 1;                  // column tiles a wavefront interleaves in a flush
 constexpr int AFRAG = (BMAX / 4) * 64;  // entries of one set of matrix-core A fragments: [k-group][lane]
 constexpr int NPOLL = 4;                // wavefronts that poll the candidate slots (up to 256 workgroups)
 constexpr int NBG = NW - NPOLL;         // wavefronts that apply the previous block's downdates meanwhile
@@ -301,6 +300,14 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
 // Lane l supplies A[row l%16][k l/16] and B[k l/16][col l%16]; its accumulator v holds
 // D[row 4v + l/16][col l%16].  Matrix row i = 4v + q is mapped to owned row g0 + 4q + v, so a lane ends
 // up with four consecutive rows of one column: 32 contiguous bytes of the panel.
+// A panel wider than one row group (several layers share the launch, or d_col above 4096) is taken
+// FLUSH_RGC row groups at a time, so that a tile of pending rows is fetched once for all of them; their A
+// fragments then extend from coefa into the background flush's buffers, which such a panel leaves unused
+// (lds_layout keeps coefa, coefbg and bgacc adjacent: 5 sets of fragments).  Two is what the register budget
+// allows; the instantiation that the single-layer loop of a 768 x 3072 or 1024 x 4096 layer runs (W in LDS,
+// one row group) keeps one, so that its register allocation stays as it was tuned.
+constexpr int FLUSH_KB = 4;              // k-groups whose pending-row entries are requested together
+template <int FLUSH_RGC>
 __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double *__restrict__ Ub,
                                                       const double *uloc, const double *pivs, double *coefa,
                                                       const int *alive_own, const unsigned *alive_bits,
@@ -313,57 +320,49 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
     const int lane = tid & 63, wave = tid >> 6;
     const int q4 = lane >> 4, cl16 = lane & 15;
     const int nks = (k + 3) / 4;
-    for (int g0 = 0; g0 < cp; g0 += RG) {
-        for (int e = tid; e < AFRAG; e += LT) {   // A fragment entry e: k-group e/64, lane e%64
-            const int l = e & 63, kk = 4 * (e >> 6) + (l >> 4);
-            const int arow = g0 + 4 * (l & 3) + ((l & 15) >> 2);
-            coefa[e] = (kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
+    const int ntiles = (d + 15) / 16;
+    for (int g0 = 0; g0 < cp; g0 += RG * FLUSH_RGC) {
+        const int nrgc = min(FLUSH_RGC, (cp - g0) / RG);
+        // A fragment entry: row group e / AFRAG, k-group (e / 64) % 16, lane e % 64; zeros for row groups past the panel
+        for (int e = tid; e < (cp > RG ? FLUSH_RGC : 1) * AFRAG; e += LT) {
+            const int rgc = e / AFRAG, l = e & 63, kk = 4 * ((e >> 6) & (BMAX / 4 - 1)) + (l >> 4);
+            const int arow = g0 + rgc * RG + 4 * (l & 3) + ((l & 15) >> 2);
+            coefa[e] = (rgc < nrgc && kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
         }
         __syncthreads();
-        // a wavefront works on NTI adjacent 16-column tiles at a time, so that 4 * NTI loads of
-        // pending-row entries are in flight before the matrix instructions that consume them
-        const int ntiles = (d + 15) / 16;
-        for (int ct0 = wave * NTI; ct0 < ntiles; ct0 += NW * NTI) {
-            int c[NTI];
-            bool col_ok[NTI];
-            bool any_ok = false;
+        for (int ct = wave; ct < ntiles; ct += NW) {
+            const int c = ct * 16 + cl16;
+            const bool col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
+            if (!__any(col_ok)) continue;
+            doublex4 acc[FLUSH_RGC];
 #pragma unroll
-            for (int x = 0; x < NTI; ++x) {
-                c[x] = (ct0 + x) * 16 + cl16;
-                col_ok[x] = (c[x] < d) && ((alive_bits[c[x] >> 5] >> (c[x] & 31)) & 1u);
-                any_ok = any_ok || col_ok[x];
-            }
-            if (!__any(any_ok)) continue;
-            doublex4 acc[NTI];
+            for (int x = 0; x < FLUSH_RGC; ++x) acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
+            const double *ub = Ub + (size_t)q4 * d + c;
+            for (int h = 0; h < nks; h += FLUSH_KB) {
+                double bv[FLUSH_KB];
 #pragma unroll
-            for (int x = 0; x < NTI; ++x) acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
-            const double *ub = Ub + (size_t)q4 * d;
-            for (int h = 0; h < nks; h += 4) {
-                double bv[NTI][4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
+                for (int e = 0; e < FLUSH_KB; ++e) {
                     const int kk = 4 * (h + e) + q4;
-#pragma unroll
-                    for (int x = 0; x < NTI; ++x)
-                        bv[x][e] = (kk < k && col_ok[x]) ? __hip_atomic_load(ub + (size_t)(h + e) * 4 * d + c[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+                    bv[e] = (kk < k && col_ok) ? __hip_atomic_load(ub + (size_t)(h + e) * 4 * d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
                 }
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
+                for (int e = 0; e < FLUSH_KB; ++e) {
                     if (h + e < nks) {
-                        const double a = coefa[(h + e) * 64 + lane];
 #pragma unroll
-                        for (int x = 0; x < NTI; ++x)
-                            acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, bv[x][e], acc[x], 0, 0, 0);
+                        for (int x = 0; x < FLUSH_RGC; ++x)
+                            if (x == 0 || cp > RG) acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(coefa[x * AFRAG + (h + e) * 64 + lane], bv[e], acc[x], 0, 0, 0);
                     }
                 }
             }
+            if (col_ok) {
 #pragma unroll
-            for (int x = 0; x < NTI; ++x) {
-                if (col_ok[x]) {
-                    doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c[x] * cp + g0 + 4 * q4);
-                    doublex4 cur = *dst;
-                    cur -= acc[x];
-                    *dst = cur;
+                for (int x = 0; x < FLUSH_RGC; ++x) {
+                    if (x < nrgc) {
+                        doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c * cp + g0 + x * RG + 4 * q4);
+                        doublex4 cur = *dst;
+                        cur -= acc[x];
+                        *dst = cur;
+                    }
                 }
             }
         }
@@ -757,6 +756,17 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 my_live &= ~(1u << r);
                 continue;
             }
+            typedef float floatx4 __attribute__((ext_vector_type(4)));
+            // W in the workspace: the column's first 1024 rows are requested before anything else of the column, so
+            // that one round trip to the L2 covers them all and overlaps the reduction of the pivot-row entry
+            // (one request at a time made this phase the longest of the step when several layers share the launch)
+            constexpr int WPRE = 4;
+            floatx4 wpre[WPRE];
+            if (!W_IN_LDS) {
+#pragma unroll
+                for (int q = 0; q < WPRE; ++q)      // no branches between the requests: blocks beyond mp re-read the last one
+                    wpre[q] = *reinterpret_cast<const floatx4 *>(&WT(jl, min(256 * q, mp - 256) + 4 * lane));
+            }
             const double diag_old = diag[jl];        // asked for here, needed after the column's pass
             double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
             if (unflushed) term += cprev[lane] * uprev[jl * BMAX + lane];
@@ -764,9 +774,30 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             const double f = u * rpiv;
             const float nf = -(float)f;
             double s = 0.0;
+            if (!W_IN_LDS) {
+                for (int i0 = 0; i0 < mp; i0 += 256 * WPRE) {
+                    if (i0 > 0) {
+#pragma unroll
+                        for (int q = 0; q < WPRE; ++q)
+                            wpre[q] = *reinterpret_cast<const floatx4 *>(&WT(jl, min(i0 + 256 * q, mp - 256) + 4 * lane));
+                    }
+#pragma unroll
+                    for (int q = 0; q < WPRE; ++q) {
+                        if (i0 + 256 * q < mp) {
+                            const floatx4 c = *reinterpret_cast<const floatx4 *>(&wcol[i0 + 256 * q + 4 * lane]);
+                            floatx4 w = wpre[q];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                w[e] = __builtin_fmaf(c[e], nf, w[e]);
+                                s += (double)w[e] * (double)w[e];
+                            }
+                            *reinterpret_cast<floatx4 *>(&WT(jl, i0 + 256 * q + 4 * lane)) = w;
+                        }
+                    }
+                }
+            } else
             for (int i0 = 0; i0 < mp; i0 += 256) {         // rows beyond m hold zeros and stay zero
                 // four consecutive rows per lane: one 128-bit LDS access per operand
-                typedef float floatx4 __attribute__((ext_vector_type(4)));
                 floatx4 *wp = reinterpret_cast<floatx4 *>(&WT(jl, i0 + 4 * lane));
                 floatx4 w = *wp;
                 const floatx4 c = *reinterpret_cast<const floatx4 *>(&wcol[i0 + 4 * lane]);
@@ -867,7 +898,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 bg_active = true;
                 __syncthreads();
             } else {
-                flush_panel(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits, k, d, cp);
+                flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2)>(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits, k, d, cp);
             }
             k = 0;
             ublk ^= 1;
