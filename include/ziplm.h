@@ -156,8 +156,8 @@ size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_s
  * single-layer calls.
  * group_size == 1: the layers are taken up to four at a time; the loops of one such set run side by side
  * in one launch, each on its share of the compute units, and the sets follow one another on the stream
- * (a single loop is bound by the hand-off between its workgroups, so four loops on a quarter of the device
- * each finish in 60% of the time of four loops one after another).  The columns are spread over fewer
+ * (a single loop is bound by the hand-off between its workgroups, so four loops on a quarter of the device each
+ * finish in 55% of the time of four loops one after another).  The columns are spread over fewer
  * workgroups than in the single-layer call, so the deferred eliminations are summed in another order: same
  * removal order wherever the scores differ by more than rounding, W, Hinv and err equal to rounding, not bit
  * for bit.  With info_host the call waits for the stream after every set.  The exchange area of the
