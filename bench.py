@@ -6,7 +6,8 @@ removes every structure of the layer (Algorithm 1).  Default workload: configura
 BERT-base feed-forward down-projection (W 768 x 3072, 16384 calibration tokens, post-GELU).
 
 Prints ONE JSON line.  `value` is seconds per layer for the whole path (lower is better); with
---config 5 it is seconds for the 24 problems of the 12-layer sweep, one after another.
+--config 5 it is seconds for the 24 problems of the 12-layer sweep (Hessians and inverses of
+the layers on a few streams, then the loops of each kind in one batched call).
 `roofline` describes the greedy-loop kernel against HBM bandwidth with the algorithmic byte
 count  sum over steps of (8 r^2 + 8 d_row r + 4 r), r = live columns;  `roofline_hessian` the
 Hessian kernel against the fp32 matrix-core peak with d (d + 1) n_tok useful flops.
@@ -49,6 +50,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--sweep-streams", type=int, default=3,
+                    help="configuration 5 only: streams the Hessians and inverses of the layers are spread over")
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5 (5: the 24-problem sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
@@ -125,18 +128,27 @@ def main():
             stacks.append(sk)
     stacked = {id(q) for sk in stacks for q in sk.members}
 
+    # configuration 5: Hessians and inverses of different layers go to a few streams in turn (default priority;
+    # the calls are independent on disjoint buffers), so that the latency-bound inverse of one layer runs under the
+    # matrix-core-bound Hessian of another; the batched loops follow on the main stream
+    main = torch.cuda.current_stream()
+    side = [torch.cuda.Stream() for _ in range(args.sweep_streams)] if (stacks and args.sweep_streams > 1) else []
+
     def one_step(record):
         marks = []
-        for q in problems:
+        for s_ in side:
+            s_.wait_stream(main)                 # the previous step's loops still use W and Hinv
+        for i, q in enumerate(problems):
             spec = q.spec
             e = [ev() for _ in range(4)]
-            q.W.copy_(q.W0)
-            q.H.zero_()
-            e[0].record()
-            ziplm.ziplm_hessian_accumulate(q.H, q.X, 2.0, workspace=q.ws_h)
-            e[1].record()
-            ziplm.ziplm_hinv(q.H, spec.damp_rel, out=q.Hi, workspace=q.ws_i, check=False)
-            e[2].record()
+            with torch.cuda.stream(side[(i // 2) % len(side)] if side else main):      # both problems of a layer on one stream
+                q.W.copy_(q.W0)
+                q.H.zero_()
+                e[0].record()
+                ziplm.ziplm_hessian_accumulate(q.H, q.X, 2.0, workspace=q.ws_h)
+                e[1].record()
+                ziplm.ziplm_hinv(q.H, spec.damp_rel, out=q.Hi, workspace=q.ws_i, check=False)
+                e[2].record()
             if id(q) in stacked:
                 e[3] = e[2]                      # pruned below, all problems of one shape together
             else:
@@ -144,6 +156,8 @@ def main():
                                                                      workspace=q.ws_p, check=False)
                 e[3].record()
             marks.append(e)
+        for s_ in side:
+            main.wait_stream(s_)
         for sk in stacks:
             eb = [ev(), ev()]
             eb[0].record()
@@ -230,7 +244,9 @@ def main():
     if args.config == 5:
         workload = ("config 5: GPT-2-small-shaped sweep, 12 layers x (attention out-proj W 768x768 in 12 heads of 64 "
                     "columns, N(0,1) inputs + FFN down-proj W 768x3072 single columns, GELU inputs), 32768 tokens each, "
-                    "damp 0.01, remove everything; value = all 24 problems, the twelve loops of either kind in one batched call")
+                    "damp 0.01, remove everything; value = all 24 problems, the twelve loops of either kind in one batched call; "
+                    "Hessians and inverses of the layers on %d streams in turn (their stage times and the Hessian "
+                    "rate are then measured under overlap; --sweep-streams 1 gives them undisturbed)" % max(1, len(side)))
         n_steps_loop = sum(sp.n_groups for sp in column_specs)      # the 12 x 3072 single-column removals
     else:
         spec = specs[0]
