@@ -358,6 +358,35 @@ def test_prune_calls_on_two_streams_share_the_exchange_area(z, oracle):
         assert float(Wd.abs().max()) == 0.0
 
 
+def test_hessian_and_inverse_on_several_streams_equal_the_sequential_results(z):
+    """Hessians and inverses of different layers issued on three streams at once (as the sweep benchmark does):
+    the calls keep no shared state, so every result is bit-identical to the same call made alone."""
+    shapes = [(768, 5000, "gelu"), (320, 9000, "normal"), (1000, 2100, "scaled_normal"), (200, 777, "gelu"),
+              (640, 4096, "normal"), (96, 12000, "gelu")]
+    Xs = [dev(workloads.make_X(workloads.small(8, d, 1, n, x_kind=kind, seed=70 + i))) for i, (d, n, kind) in enumerate(shapes)]
+    alone = []
+    for X in Xs:
+        H = torch.zeros((X.shape[0], X.shape[0]), dtype=torch.float32, device="cuda")
+        z.ziplm_hessian_accumulate(H, X, scale=2.0)
+        Hi, _ = z.ziplm_hinv(H, 0.01)
+        alone.append((H, Hi))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    for s_ in streams:
+        s_.wait_stream(torch.cuda.current_stream())
+    together = []
+    for rep in range(2):
+        for i, X in enumerate(Xs):
+            with torch.cuda.stream(streams[i % 3]):
+                H = torch.zeros((X.shape[0], X.shape[0]), dtype=torch.float32, device="cuda")
+                z.ziplm_hessian_accumulate(H, X, scale=2.0)
+                Hi, _ = z.ziplm_hinv(H, 0.01, check=False)
+                together.append((i, H, Hi))
+    torch.cuda.synchronize()
+    for i, H, Hi in together:
+        assert torch.equal(H, alone[i][0]) and torch.equal(Hi, alone[i][1]), "layer %d" % i
+
+
 # ------------------------------------------------------------------------------------------ module error, prior
 
 @pytest.mark.parametrize("m,d,n,kind,lam_rel", [
