@@ -497,6 +497,7 @@ def test_prune_batch_equals_single_layer_calls_and_oracle(z, oracle):
 @pytest.mark.parametrize("m,d,n,layers,seed", [
     (48, 320, 1500, 6, 41),        # launches of four and of two layers
     (96, 1100, 3300, 5, 51),       # four layers on 64 workgroups each (more columns than wavefronts), then one alone
+    (32, 200, 900, 7, 61),         # four layers, then three on 85 workgroups each
 ])
 def test_prune_batch_single_columns_matches_oracle(z, oracle, m, d, n, layers, seed):
     """Single-column layers of one shape in one batched call: several loops run side by side in one launch,
