@@ -11,14 +11,15 @@
 
 namespace ziplm {
 
+// compute units of the current device (cached per device; concurrent first calls store the same value)
 int device_cu_count() {
-    static int cached = 0;
-    if (cached > 0) return cached;
+    constexpr int kMaxDevices = 64;
+    static int cached[kMaxDevices] = {};
     int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-        return 256;  // MI355X; used only for sizing when no device is visible
-    cached = n;
+    if (hipGetDevice(&dev) != hipSuccess) return 256;   // MI355X; used only for sizing when no device is visible
+    if (dev >= 0 && dev < kMaxDevices && cached[dev] > 0) return cached[dev];
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+    if (dev >= 0 && dev < kMaxDevices) cached[dev] = n;
     return n;
 }
 

@@ -425,12 +425,9 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     ZIPLM_HIP_TRY(hipGetLastError());
 
     // ---- A = L L^T, right-looking over 128-column panels: one panel launch, one trailing update ----
-    static bool panel_attr_set = false;
-    if (!panel_attr_set) {
-        ZIPLM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                          (int)sizeof(PanelLds)));
-        panel_attr_set = true;
-    }
+    // every time: the attribute belongs to the current device's copy of the kernel, and the call costs microseconds
+    ZIPLM_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void *>(panel_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)sizeof(PanelLds)));
     for (int k0 = 0; k0 < dp; k0 += PW) {
         const int rest = dp - k0 - PW;
         const int pblocks = rest > 0 ? (rest + PANEL_ROWS - 1) / PANEL_ROWS : 1;

@@ -1101,11 +1101,8 @@ int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64
     void (*const kernels[4])(const StatePack) = {prune_lazy_kernel<false, false>, prune_lazy_kernel<true, false>,
                                                  prune_lazy_kernel<false, true>, prune_lazy_kernel<true, true>};
     const void *fn = reinterpret_cast<const void *>(kernels[variant]);
-    static bool attr_set[4] = {false, false, false, false};
-    if (!attr_set[variant]) {
-        ZIPLM_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_set[variant] = true;
-    }
+    // every time: the attribute belongs to the current device's copy of the kernel, and the call costs microseconds
+    ZIPLM_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
     int per_cu = 0;
     ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernels[variant], LT, p.lds_bytes));
     if (per_cu < 1 || pack * p.nb > per_cu * device_cu_count()) return ZIPLM_ERR_DEVICE;
