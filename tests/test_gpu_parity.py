@@ -539,3 +539,26 @@ def test_prune_batch_single_columns_matches_oracle(z, oracle, m, d, n, layers, s
     for l in range(layers):
         if l != bad:
             assert torch.equal(W2[l], Wb[l]) and torch.equal(H2[l], Hb[l])      # the good layers are complete
+
+
+def test_prune_batch_single_columns_on_the_eager_fallback(z, oracle, monkeypatch):
+    """With the eager single-column kernel forced (ZIPLM_PRUNE_EAGER=1) the batched call runs the layers one
+    after the other through that kernel: bit-identical to single-layer calls, and against the oracle."""
+    monkeypatch.setenv("ZIPLM_PRUNE_EAGER", "1")
+    m, d, n, layers = 24, 160, 700, 3
+    Ws, His = [], []
+    for l in range(layers):
+        X, W32, H, Hi32 = _oracle_inputs(oracle, workloads.small(m, d, 1, n, x_kind="gelu", seed=81 + l))
+        Ws.append(W32)
+        His.append(Hi32)
+    Wb, Hb = dev(np.stack(Ws)), dev(np.stack(His))
+    snaps = [0, d // 2, d]
+    order_b, err_b, snap_b = z.ziplm_structured_obs_prune_batch(Wb, Hb, 1, d, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    for l in range(layers):
+        Wl, Hl = dev(Ws[l]), dev(His[l])
+        o, e, sn = z.ziplm_structured_obs_prune(Wl, Hl, 1, d, snapshot_steps=snaps)
+        torch.cuda.synchronize()
+        assert torch.equal(o, order_b[l]) and torch.equal(e, err_b[l]) and torch.equal(sn, snap_b[l])
+        ref = compare_run(oracle, Ws[l], His[l], 1, d, order_b[l].cpu().numpy(), err_b[l].cpu().numpy(), snap_steps=snaps)
+        assert rel_fro(snap_b[l, 1].cpu().numpy(), ref["W_snap"][1]) <= REL_TOL
