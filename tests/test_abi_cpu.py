@@ -122,3 +122,12 @@ def test_database_grid_of_the_paper():
     assert small == sorted(set(small)) and small[-1] <= 8
     with pytest.raises(ValueError):
         ziplm.database_steps(8, "rows")
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The build runs on one GPU; asking the benchmark for more ends with a message, before any device is touched."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert out.returncode == 2 and "one GPU" in out.stderr
