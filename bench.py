@@ -28,7 +28,7 @@ if ROOT not in sys.path:
 # HBM bytes per launch of the greedy-loop kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
 # in profiles/greedy_loop_and_hessian_config3_hbm_counters.md (KiB, already scaled by the copy-kernel factors);
 # --traffic-kib overrides them after a new counter run.
-MEASURED_TRAFFIC_KIB = {3: (3160383.0, 3122699.0)}
+MEASURED_TRAFFIC_KIB = {3: (3158435.0, 3120838.0)}
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
