@@ -23,6 +23,12 @@ int device_cu_count() {
     return n;
 }
 
+// Slices of 32 tokens between two carry-overs of the matrix-core accumulators into the second accumulator set:
+// chains of 128 matrix instructions, whose rounding is 2e-7 of a 256-token chunk sum and averages out over the
+// chunks.  The second set takes one rounding per chunk, so a workgroup gets at most 64 chunks (16384 tokens).
+constexpr int HESSIAN_CHUNK = 8;
+constexpr int64_t HESSIAN_MAX_TOKENS_PER_SPLIT = 64 * HESSIAN_CHUNK * gemm::BK;
+
 struct HessianPlan {
     int tiles;        // lower-triangular tile count
     int nsplit;       // token splits
@@ -37,10 +43,12 @@ static HessianPlan plan_hessian(int d_col, int64_t n_tok) {
     const int slots = 2 * device_cu_count();  // two workgroups fit per compute unit
     // Pick the split count that fills whole rounds of `slots` workgroups best, keeping at least
     // 512 tokens per split; prefer fewer splits when the gain is below 3%.
-    int best = 1;
+    const int min_split = (int)((n_tok + HESSIAN_MAX_TOKENS_PER_SPLIT - 1) / HESSIAN_MAX_TOKENS_PER_SPLIT);
+    int best = min_split;
     double best_eff = 0.0;
-    const int64_t max_split = n_tok / 512 > 0 ? (n_tok / 512 < 64 ? n_tok / 512 : 64) : 1;
-    for (int s = 1; s <= (int)max_split; ++s) {
+    int64_t max_split = n_tok / 512 > 0 ? (n_tok / 512 < 64 ? n_tok / 512 : 64) : 1;
+    if (max_split < min_split) max_split = min_split;
+    for (int s = min_split; s <= (int)max_split; ++s) {
         const int64_t blocks = (int64_t)p.tiles * s;
         const int64_t rounds = (blocks + slots - 1) / slots;
         const double eff = (double)blocks / (double)(rounds * slots);
@@ -60,13 +68,13 @@ template <int MODE, bool VEC>
 static int run_hessian(const gemm::Args &base, const HessianPlan &plan, hipStream_t stream) {
     gemm::Args g = base;
     if (plan.nsplit == 1) {
-        hipLaunchKernelGGL((gemm::gemm_kernel<MODE, MODE, VEC, true>), dim3(plan.tiles, 1, 1),
+        hipLaunchKernelGGL((gemm::gemm_kernel<MODE, MODE, VEC, true, false, HESSIAN_CHUNK>), dim3(plan.tiles, 1, 1),
                            dim3(gemm::THREADS), 0, stream, g);
         ZIPLM_HIP_TRY(hipGetLastError());
         return ZIPLM_OK;
     }
     g.flags |= gemm::F_PARTIAL;
-    hipLaunchKernelGGL((gemm::gemm_kernel<MODE, MODE, VEC, true>), dim3(plan.tiles, plan.nsplit, 1),
+    hipLaunchKernelGGL((gemm::gemm_kernel<MODE, MODE, VEC, true, false, HESSIAN_CHUNK>), dim3(plan.tiles, plan.nsplit, 1),
                        dim3(gemm::THREADS), 0, stream, g);
     ZIPLM_HIP_TRY(hipGetLastError());
     g.flags &= ~gemm::F_PARTIAL;

@@ -250,7 +250,15 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
         }
 }
 
-template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false>
+// CHUNK > 0: two-level accumulation.  A chain of matrix instructions rounds its running sum to fp32 at every link,
+// so the error of a long k range grows like sqrt(links) * 2^-24 of the sum (1e-6 after 3000 tokens, which the
+// greedy loop downstream turns into removal-order differences).  With CHUNK the accumulators are added to a
+// second fp32 set and reset every CHUNK slices (32 * CHUNK values of k): a chain restarts from zero after
+// 16 * CHUNK links, and the second set takes one rounding per chunk instead of one per link, so the error is
+// about (sqrt(16 CHUNK / chunks) + sqrt(chunks)) * 2^-25 of the sum -- 1e-7 for a dozen chunks of 256.  A
+// second set in fp64 does not fit the register file at two workgroups per compute unit; callers bound the
+// number of chunks per launch through the k range they give a workgroup.  The products are unchanged.
+template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false, int CHUNK = 0>
 __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     __shared__ __attribute__((aligned(16))) float lds[2][2][SLAB];
 
@@ -303,6 +311,11 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    float acc2[CHUNK > 0 ? 64 : 1];
+#pragma unroll
+    for (int e = 0; e < (CHUNK > 0 ? 64 : 1); ++e) acc2[e] = 0.f;
+    int in_chunk = 0;
+
     const int64_t nslices = ke > kb ? (ke - kb + BK - 1) / BK : 0;
     Slab<AMODE, VEC, KGUARD> ra;
     Slab<BMODE, VEC, KGUARD> rb;
@@ -337,8 +350,28 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
             ra.store(lds[cur ^ 1][0], tid);
             rb.store(lds[cur ^ 1][1], tid);
         }
+        if (CHUNK > 0 && (++in_chunk == CHUNK || !more)) {      // uniform over the workgroup
+            in_chunk = 0;
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        acc2[(i * 2 + j) * 16 + v] += acc[i][j][v];
+                        acc[i][j][v] = 0.f;
+                    }
+        }
         __syncthreads();
         cur ^= 1;
+    }
+    if (CHUNK > 0) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = acc2[(i * 2 + j) * 16 + v];
     }
 
     if (g.flags & F_PARTIAL) {
