@@ -10,9 +10,15 @@
 //                  A22 -= L21 L21^T on the fp32 matrix cores;
 //   T  = L^-1      diagonal blocks inverted in one batched launch, then bottom-up pairwise merges  T21 = -T22 (L21 T11), all pairs of a level in one
 //                  batched launch;
-//   Hinv = T^T T   lower tiles computed, mirrored to the upper triangle.
+//   X0 = T^T T     lower tiles computed, mirrored to the upper triangle: the inverse as fp32 arithmetic gives it,
+//                  wrong by 1e-5 to 1e-3 relative when H is as ill conditioned as post-GELU inputs make it;
+//   Hinv = X0 + X0 R,  R = I - A X0   one Newton step.  R is formed on the fp64 matrix cores (exact products of the
+//                  fp32 operands, fp64 sums), the correction X0 R on the fp32 ones (R is small, so its rounding is
+//                  second order).  The step squares the error of X0, which leaves the rounding of the fp32
+//                  result: the greedy loop's removal order and late-step errors then follow an fp64 inverse.
 #include "common.h"
 #include "mfma_gemm.h"
+#include "mfma_dgemm.h"
 
 namespace ziplm {
 
@@ -36,10 +42,10 @@ __global__ __launch_bounds__(256) void damp_lambda_kernel(const float *__restric
     }
 }
 
-// A (dp x dp) = [H + lambda I, 0; 0, I]
+// A (dp x dp) = [H + lambda I, 0; 0, I]; lambda == nullptr: [H, 0; 0, I]
 __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ H, int d, float *__restrict__ A,
                                                     int dp, const double *__restrict__ lambda) {
-    const float lam = (float)(*lambda);
+    const float lam = lambda ? (float)(*lambda) : 0.f;
     const int64_t total = (int64_t)dp * dp;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
         const int i = (int)(idx / dp), j = (int)(idx % dp);
@@ -483,25 +489,51 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         }
     }
 
-    // ---- Hinv = T^T T, lower tiles + mirror, written straight into the caller's d_col x d_col ----
+    // ---- X0 = T^T T, lower tiles + mirror, into the buffer of the factor (not needed any more) ----
     Args f = {};
     f.A = l.T; f.lda = dp;
     f.B = l.T; f.ldb = dp;
-    f.C = Hinv; f.ldc = d_col;
-    f.M = d_col; f.N = d_col; f.K = dp;
+    f.C = l.A; f.ldc = dp;
+    f.M = dp; f.N = dp; f.K = dp;
     f.alpha = 1.f; f.beta = 0.f;
     f.flags = F_TRI_GRID | F_MIRROR | F_KSTART_MAXMN;
     {
         // All tiles fit the chip at once, so the launch lasts as long as its longest tile: the one at (0, 0) runs
         // over the whole k range.  Every tile's k range is shared by up to four workgroups; their accumulators
         // go to S and the merges' buffer behind it (S is free by now).
-        const int tm = (d_col + BM - 1) / BM, tiles = tm * (tm + 1) / 2;
+        const int tm = dp / BM, tiles = tm * (tm + 1) / 2;
         const size_t sets = ((char *)l.partial - (char *)l.S) / (sizeof(float) * 64 * THREADS) + MERGE_PARTIAL_SETS;
         int nsplit = (int)(sets / (size_t)tiles);
         if (nsplit > 4) nsplit = 4;
         if (dp < 1024) nsplit = 1;
         f.partial = l.S;
         ZIPLM_HIP_TRY((launch_splitk<R_CONTIG, R_CONTIG, true, false>(f, 1, nsplit < 1 ? 1 : nsplit, st)));
+    }
+
+    // ---- one Newton step: R = I - (H + lambda I) X0 in fp64 (into T), Hinv = X0 + X0 R (lower tiles + mirror) ----
+    // H is copied into a padded matrix (S, free again) so that the residual runs on whole tiles; the padding of H and
+    // of X0 is the identity, so the padded block of R stays apart from the d_col x d_col one.
+    hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp, static_cast<const double *>(nullptr));
+    ZIPLM_HIP_TRY(hipGetLastError());
+    {
+        dgemm::ResidualArgs r = {};
+        r.A = l.S; r.lda = dp;
+        r.X = l.A; r.ldx = dp;
+        r.R = l.T; r.ldr = dp;
+        r.lambda = l.lambda;
+        r.n = dp;
+        ZIPLM_HIP_TRY(dgemm::launch_residual(r, st));
+    }
+    {
+        Args c = {};
+        c.A = l.A; c.lda = dp;          // X0, rows along k
+        c.B = l.T; c.ldb = dp;          // R[k][n]
+        c.C = Hinv; c.ldc = d_col;
+        c.D = l.A; c.ldd = dp;
+        c.M = d_col; c.N = d_col; c.K = dp;
+        c.alpha = 1.f; c.beta = 0.f;
+        c.flags = F_TRI_GRID | F_MIRROR;
+        ZIPLM_HIP_TRY((launch<K_CONTIG, R_CONTIG, true, false>(c, 1, st)));
     }
 
     if (lambda_out_host || info_host) {

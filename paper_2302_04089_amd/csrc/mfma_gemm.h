@@ -73,6 +73,11 @@ struct Args {
     // DOT variant
     double *dot_partial;   // [tiles]
     float dot_lambda;
+    // optional addend: with D set the result is alpha * acc + D (beta and the old C are ignored); with F_MIRROR the
+    // transposed element receives the same value (tiles on the diagonal mirror their lower half), so C is exactly
+    // symmetric.  Not combined with split-K.
+    const float *D;
+    int64_t ldd;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -207,8 +212,36 @@ __device__ __forceinline__ void tri_decode(int t, int &tm, int &tn) {
 template <int V0 = 0, int V1 = 16>
 __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__restrict__ C, int64_t ldc,
                                          int M, int N, int tm, int tn, float alpha, float beta,
-                                         bool mirror, int wm, int wn, int lane) {
+                                         bool mirror, int wm, int wn, int lane,
+                                         const float *__restrict__ D = nullptr, int64_t ldd = 0, bool sym_diag = false) {
     const int r = lane & 31, half = lane >> 5;
+    if (D) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int col = tn * BN + wn * 64 + j * 32 + r;
+                const int row_base = tm * BM + wm * 64 + i * 32 + 4 * half;
+                float add[V1 - V0];
+#pragma unroll
+                for (int v = V0; v < V1; ++v) {
+                    const int row = row_base + 8 * (v >> 2) + (v & 3);
+                    add[v - V0] = (row < M && col < N) ? D[(int64_t)row * ldd + col] : 0.f;
+                }
+#pragma unroll
+                for (int v = V0; v < V1; ++v) {
+                    const int row = row_base + 8 * (v >> 2) + (v & 3);
+                    // a tile on the diagonal of a symmetric output keeps its lower half and mirrors it: the
+                    // product need not be symmetric to the last bit, the output must be
+                    if (row < M && col < N && (!sym_diag || row >= col)) {
+                        const float val = alpha * acc[i][j][v] + add[v - V0];
+                        C[(int64_t)row * ldc + col] = val;
+                        if (mirror || sym_diag) C[(int64_t)col * ldc + row] = val;
+                    }
+                }
+            }
+        return;
+    }
     // All old values of the thread's four 32 x 32 blocks are requested before the first store: stores to C and
     // loads from C cannot be reordered by the compiler, and block by block this was four memory round trips
     // at the end of every workgroup (a quarter of a K = 128 trailing update).
@@ -413,7 +446,8 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
         return;
     }
     const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
-    epilogue(acc, C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
+    epilogue(acc, C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane,
+             g.D ? g.D + (int64_t)blockIdx.z * g.strideC : nullptr, g.ldd, (g.flags & F_MIRROR) && tm == tn);
 }
 
 template <int Q>
@@ -422,7 +456,7 @@ __device__ __forceinline__ void reduce_epilogue(const float (&sum)[16], const Ar
     floatx16 acc[2][2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e >> 3][(e >> 2) & 1][4 * Q + (e & 3)] = sum[e];
-    epilogue<4 * Q, 4 * Q + 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane);
+    epilogue<4 * Q, 4 * Q + 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane, g.D, g.ldd);
 }
 
 // Second pass of a split-K product: sums the raw accumulators of all splits in split order and

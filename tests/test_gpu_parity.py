@@ -148,8 +148,11 @@ def test_hinv_matches_oracle(z, oracle, d, n, kind):
     out, lam = z.ziplm_hinv(dev(H32), 0.01)
     got = out.cpu().numpy()
     assert lam == pytest.approx(lam_ref, rel=1e-6)
-    assert_columns_close(got, ref, "Hinv")
-    assert np.abs(np.diag(got) / np.diag(ref) - 1).max() <= REL_TOL
+    # the Newton step on the fp64 matrix cores leaves the rounding of the fp32 result and little else: the bar is
+    # far below the loop's 1e-4 because the greedy loop downstream amplifies errors of the inverse
+    worst = assert_columns_close(got, ref, "Hinv", tol=5e-6)
+    assert np.abs(np.diag(got) / np.diag(ref) - 1).max() <= 5e-6
+    print("d=%d: worst column of Hinv off by %.2e" % (d, worst))
     assert np.array_equal(got, got.T)
     # in place
     Hd = dev(H32)
