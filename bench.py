@@ -97,6 +97,10 @@ def main():
         q.ws_p = torch.empty(ziplm.ziplm_prune_workspace_bytes(m, d, g, 0), dtype=torch.uint8, device="cuda")
         problems.append(q)
     gen_s = time.time() - t0
+    # one exchange area (uncached device memory, kept for the life of the process) for every single-column loop
+    xbytes = max([ziplm.ziplm_prune_exchange_bytes(12 if args.config == 5 else 1, q.spec.d_row, q.spec.d_col, q.spec.group_size)
+                  for q in problems])
+    exchange = ziplm.ziplm_exchange_alloc(xbytes) if xbytes > 0 else None
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -153,7 +157,8 @@ def main():
                 e[3] = e[2]                      # pruned below, all problems of one shape together
             else:
                 q.order, q.err, _ = ziplm.ziplm_structured_obs_prune(q.W, q.Hi, spec.group_size, spec.n_groups,
-                                                                     workspace=q.ws_p, check=False)
+                                                                     workspace=q.ws_p, check=False,
+                                                                     exchange=exchange if spec.group_size == 1 else None)
                 e[3].record()
             marks.append(e)
         for s_ in side:
@@ -162,7 +167,8 @@ def main():
             eb = [ev(), ev()]
             eb[0].record()
             order_b, err_b, _ = ziplm.ziplm_structured_obs_prune_batch(sk.W, sk.Hi, sk.spec.group_size, sk.spec.n_groups,
-                                                                       workspace=sk.ws, check=False)
+                                                                       workspace=sk.ws, check=False,
+                                                                       exchange=exchange if sk.spec.group_size == 1 else None)
             eb[1].record()
             for i, q in enumerate(sk.members):
                 q.order, q.err = order_b[i], err_b[i]

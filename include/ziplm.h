@@ -20,15 +20,18 @@
  *   - Pointers are DEVICE pointers unless the name ends in _host.  The caller owns every buffer.
  *     Scratch space is passed in as `workspace` (256-byte aligned, size from the matching
  *     *_workspace_bytes call) and may be reused or freed as soon as the work enqueued by the
- *     call has finished.  The library allocates no device memory, with one exception: the
- *     per-device exchange area of the single-column loop (see ziplm_structured_obs_prune).
+ *     call has finished.  No entry point allocates or frees device memory except
+ *     ziplm_exchange_alloc, whose only purpose is to allocate.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *     on that stream and return without waiting, except where a *_host output is requested.
  *   - Return value: ZIPLM_OK or a negative ziplm_status.  Argument errors are detected before
  *     anything is enqueued and leave all buffers untouched.  No exception crosses this boundary.
- *   - Calls on different streams with disjoint buffers are independent; apart from that
- *     exchange area (and the order it imposes on single-column loops of one device) the library
- *     keeps no state between calls.
+ *   - The library keeps no state between calls and reads no environment variable.  Calls on
+ *     different streams are independent as long as every buffer they write (outputs, workspace,
+ *     exchange area) is theirs alone.  One rule per device: a greedy loop over single columns
+ *     (group_size == 1) is one persistent launch that takes a workgroup slot on every compute unit, so
+ *     two such loops never run side by side; enqueue them on one stream or order them with events.
+ *     The runtime would run them one after the other anyway, but in an order of its choosing.
  */
 #ifndef ZIPLM_H
 #define ZIPLM_H
@@ -84,13 +87,17 @@ size_t ziplm_hessian_workspace_bytes(int d_col, int64_t n_tok);
  *
  *   lambda = damp_rel * mean(diag H);   Hinv = (H + lambda I)^-1
  *
- * computed as H + lambda I = L L^T (blocked Cholesky), T = L^-1, Hinv = T^T T.  H and Hinv are
+ * computed as H + lambda I = L L^T (blocked Cholesky), T = L^-1, X0 = T^T T in fp32, followed by
+ * one Newton step Hinv = X0 + X0 (I - (H + lambda I) X0) whose residual is formed on the fp64
+ * matrix cores: the result is the fp64 inverse of the fp32 H rounded to fp32, as long as fp32
+ * arithmetic gets X0 to within a few 1e-4 (conditioning up to about 1e4).  H and Hinv are
  * d_col x d_col fp32 with leading dimension d_col; H is only read, and Hinv may alias H.  Both
- * triangles of Hinv are written.
+ * triangles of Hinv are written, bit-identical.
  * lambda_out_host / info_host (host pointers, each may be NULL): if either is given the call
  * waits for the stream and stores lambda and, in *info_host, 0 or 1 + the index of the first
- * non-positive pivot.  Returns ZIPLM_ERR_NOT_PD in that case when info was requested; without
- * info_host a failed factorisation is not reported and Hinv is meaningless.
+ * non-positive pivot; the call then returns ZIPLM_ERR_NOT_PD.  A failed factorisation is also
+ * marked on the device, for callers that do not wait: every diagonal entry of Hinv is set to
+ * NaN, which ziplm_structured_obs_prune reports as ZIPLM_ERR_NOT_PD at its first step.
  */
 int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel, float *lambda_out_host,
                int *info_host, void *workspace, size_t workspace_bytes, void *stream);
@@ -115,29 +122,48 @@ size_t ziplm_hinv_workspace_bytes(int d_col);
  *   n_snap, snapshot_steps_host, W_snap   optional per-layer database (Section 3.2): after
  *            snapshot_steps_host[i] removals (0..n_remove, host int32 array, read before the
  *            call returns) the masked W is copied to W_snap + i*d_row*d_col.
- *   info_host   optional host int: when given, the call waits for the stream and stores 0, or
- *            1 + the step at which a block of Hinv was not positive definite (-> return
- *            ZIPLM_ERR_NOT_PD), or -1 if the device loop timed out (-> ZIPLM_ERR_DEVICE).
+ *   info_host   optional host int: when given, the call waits for the stream and stores the device's
+ *            status word: 0; or 1 + the step at which a block of Hinv was not positive definite
+ *            (-> ZIPLM_ERR_NOT_PD); or -1 if a device-side wait gave up after its 4 s limit
+ *            (-> ZIPLM_ERR_DEVICE); or -(2 + t) if no live structure was left at step t, i.e. n_remove
+ *            exceeds the structures alive under alive_in (-> ZIPLM_ERR_INVALID_ARG, the one argument
+ *            error that only the device can see).  After any of the three, order_out and err_out hold
+ *            the steps completed so far; W and Hinv are unchanged (single columns) or partly updated
+ *            (larger structures), and must not be used.
+ *   exchange, exchange_bytes   optional separate area for the words the loop's workgroups wait on
+ *            (group_size == 1 only; size from ziplm_prune_exchange_bytes, 256-byte aligned).  NULL: they
+ *            live in the workspace.  Results are identical either way; in uncached device memory
+ *            (ziplm_exchange_alloc) a store reaches the other workgroups' loads sooner, which makes the
+ *            loop about 3% faster.  The area is scratch like the workspace: cleared on entry, and two
+ *            calls in flight must not share it.
  *
  * The state is held in fp64 for Hinv and fp32 for W inside the call; scores are reduced in
  * fp64.  Ties in the argmin go to the lowest structure index.  Eq. 3 and Eq. 4 of one step use
  * the rows of Hinv as they were before that step.
- *
- * Memory the library owns: the single-column loop (group_size == 1) exchanges its candidates
- * between workgroups through 32 MiB of uncached device memory, allocated per device on the first
- * such call and kept until the process ends (it is never freed).  Calls on different streams of
- * one device use it one after the other (each waits on the stream for the previous one's loop).
- * With ZIPLM_EXCHANGE_IN_WORKSPACE=1 in the environment, when d_row is too large for it, or when
- * the allocation fails, the exchange goes through the caller's workspace instead: same results,
- * about 3% slower.  Everything else lives in the caller's buffers.
  */
 int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int group_size,
                                int n_remove, int32_t *order_out, double *err_out,
                                const uint8_t *alive_in, int n_snap,
                                const int32_t *snapshot_steps_host, float *W_snap,
-                               int *info_host, void *workspace, size_t workspace_bytes,
-                               void *stream);
+                               int *info_host, void *exchange, size_t exchange_bytes,
+                               void *workspace, size_t workspace_bytes, void *stream);
 size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap);
+
+/*
+ * Size of a separate exchange area for ziplm_structured_obs_prune (n_layers = 1) or
+ * ziplm_structured_obs_prune_batch; 0 when the loop has no use for one (group_size > 1, or a shape
+ * that runs on the eager kernel).
+ */
+size_t ziplm_prune_exchange_bytes(int n_layers, int d_row, int d_col, int group_size);
+
+/*
+ * Allocates `bytes` of uncached device memory on the current device for use as an exchange area and
+ * stores its address in *exchange_out (host pointer).  The caller owns it.  It is meant to be kept
+ * for the life of the process and reused by every call: memory of this kind must not be returned to
+ * the driver once a kernel has read it (later allocations have been seen holding wrong values), so
+ * the library offers no call that frees it.
+ */
+int ziplm_exchange_alloc(size_t bytes, void **exchange_out);
 
 /*
  * The same loop for several layers of one shape in one sequence of launches (Section 3.2: every layer
@@ -160,17 +186,45 @@ size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_s
  * finish in 55% of the time of four loops one after another).  The columns are spread over fewer
  * workgroups than in the single-layer call, so the deferred eliminations are summed in another order: same
  * removal order wherever the scores differ by more than rounding, W, Hinv and err equal to rounding, not bit
- * for bit.  With info_host the call waits for the stream after every set.  The exchange area of the
- * single-layer call is used here as well.
+ * for bit.  With info_host the call waits for the stream after every set.  exchange: as in the
+ * single-layer call, sized by ziplm_prune_exchange_bytes(n_layers, ...).
  */
 int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_layers, int64_t stride_w,
                                      int64_t stride_hinv, int d_row, int d_col, int group_size,
                                      int n_remove, int32_t *order_out, double *err_out, int n_snap,
                                      const int32_t *snapshot_steps_host, float *W_snap,
-                                     int *info_host, void *workspace, size_t workspace_bytes,
-                                     void *stream);
+                                     int *info_host, void *exchange, size_t exchange_bytes,
+                                     void *workspace, size_t workspace_bytes, void *stream);
 size_t ziplm_prune_batch_workspace_bytes(int n_layers, int d_row, int d_col, int group_size,
                                          int n_snap);
+
+/*
+ * The same greedy loop over single columns (Algorithm 1 with |S| = 1) on the eager kernel: every step
+ * reads and writes the whole live state, the O(d_col^2) elimination of Eq. 4 included, exactly as the
+ * algorithm is printed.  ziplm_structured_obs_prune uses it for shapes whose per-workgroup state does
+ * not fit on chip; this entry point runs it for any shape -- a cross-check of the deferred-update
+ * kernel and the baseline its time is quoted against.  Arguments as in ziplm_structured_obs_prune
+ * with group_size = 1 and no exchange area.
+ */
+int ziplm_structured_obs_prune_eager(float *W, float *Hinv, int d_row, int d_col, int n_remove,
+                                     int32_t *order_out, double *err_out, const uint8_t *alive_in,
+                                     int n_snap, const int32_t *snapshot_steps_host, float *W_snap,
+                                     int *info_host, void *workspace, size_t workspace_bytes,
+                                     void *stream);
+size_t ziplm_prune_eager_workspace_bytes(int d_row, int d_col, int n_snap);
+
+/*
+ * Self-test of the single-column loop's bounded waits.  The loop's workgroups wait for one another's
+ * candidates (Algorithm 1: the argmin of a step needs every score); every such wait gives up after
+ * 4 s, raises the status word, and the launch drains.  This call runs the loop of
+ * ziplm_structured_obs_prune (group_size 1, every column to be removed, workspace of that call) with
+ * one workgroup held back, so that the others wait for a candidate that never comes.  It takes a
+ * little over 4 s and is expected to return ZIPLM_ERR_DEVICE with *info_host = -1 and W, Hinv
+ * unchanged; ZIPLM_ERR_UNSUPPORTED for shapes that run on the eager kernel.
+ */
+int ziplm_selftest_bounded_wait(float *W, float *Hinv, int d_row, int d_col, int32_t *order_out,
+                                double *err_out, int *info_host, void *workspace,
+                                size_t workspace_bytes, void *stream);
 
 /*
  * Error of dropping a whole module ("Pruned structures", Section 3.1: besides heads and
@@ -202,8 +256,8 @@ size_t ziplm_module_error_workspace_bytes(int d_row, int d_col);
  * layer-wise error of the pruned layer because every intermediate W is the least-squares optimum
  * on its support.  total: one device double, the whole-module error from ziplm_module_error (with
  * the same lambda the pruner's Hinv was built with); a fully dropped layer gets 1.
- * prior_out: device double[n].  n == 0 is a no-op.  *total must be positive (not checked: the
- * value is on the device).
+ * prior_out: device double[n].  n == 0 is a no-op.  *total must be positive and finite; the value
+ * is on the device, so a violation cannot be returned as a status: every prior_out[t] is then NaN.
  */
 int ziplm_prior(const double *err, int n, const double *total, double *prior_out, void *stream);
 

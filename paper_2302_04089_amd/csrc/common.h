@@ -29,6 +29,11 @@ struct Carver {
     }
 };
 
+// Zero-fills `bytes` bytes (a multiple of 16, 16-byte aligned) with a small kernel on `stream`.  Used instead of
+// hipMemsetAsync for the library's flags and counters: a fill kernel is an ordinary graph node if the caller
+// captures the stream, a memset node is not always replayed correctly.
+int zero_fill(void *p, size_t bytes, hipStream_t stream);
+
 inline bool workspace_ok(const void *ws, size_t have, size_t need) {
     if (need == 0) return true;
     return ws != nullptr && (reinterpret_cast<uintptr_t>(ws) % kAlign) == 0 && have >= need;

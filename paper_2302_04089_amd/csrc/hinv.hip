@@ -368,6 +368,13 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
     }
 }
 
+// A failed factorisation (info != 0) must not pass for an inverse with callers that never look at info: the
+// diagonal of Hinv becomes NaN, which the greedy loop reports as a non-positive pivot at its first step.
+__global__ __launch_bounds__(256) void poison_on_failure_kernel(float *__restrict__ Hinv, int d, const int *__restrict__ info) {
+    if (*info == 0) return;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < d; i += gridDim.x * 256) Hinv[(int64_t)i * d + i] = __builtin_nanf("");
+}
+
 // The large merges of the triangular inverse have 48 to 256 output tiles for 256 compute units (two workgroups fit on each): their k range
 // is shared by several workgroups.  Accumulator sets (one per workgroup) the workspace provides for that:
 constexpr int MERGE_PARTIAL_SETS = 512;
@@ -535,6 +542,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         c.flags = F_TRI_GRID | F_MIRROR;
         ZIPLM_HIP_TRY((launch<K_CONTIG, R_CONTIG, true, false>(c, 1, st)));
     }
+    hipLaunchKernelGGL(poison_on_failure_kernel, dim3((d_col + 255) / 256 < 64 ? (d_col + 255) / 256 : 64), dim3(256), 0, st, Hinv, d_col, l.info);
+    ZIPLM_HIP_TRY(hipGetLastError());
 
     if (lambda_out_host || info_host) {
         double lam = 0.0;

@@ -49,9 +49,11 @@ static __global__ __launch_bounds__(PRIOR_THREADS) void prior_kernel(const doubl
     __syncthreads();
     double run = chunk_sum[tid];
     const double denom = *total;
+    // a whole-module error that is not positive and finite makes every prior NaN: the caller sees it at once
+    const bool usable = denom > 0.0 && denom < __builtin_inf();
     for (int t = t0; t < t1; ++t) {
         run += err[t];
-        prior[t] = sqrt(run / denom);
+        prior[t] = usable ? sqrt(run / denom) : __builtin_nan("");
     }
 }
 

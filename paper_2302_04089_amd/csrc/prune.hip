@@ -20,7 +20,6 @@
 // because on this machine a dependent launch costs more than the arithmetic of a step.
 #include <hip/hip_cooperative_groups.h>
 
-#include <stdlib.h>
 #include <type_traits>
 
 #include "common.h"
@@ -32,17 +31,22 @@ bool lazy_columns_feasible(int d_row, int d_col);
 size_t lazy_columns_workspace_bytes(int d_row, int d_col, int n_snap);
 int lazy_columns_pack(int n_layers, int d_row, int d_col);
 size_t lazy_columns_pack_workspace_bytes(int pack, int d_row, int d_col, int n_snap);
+size_t lazy_columns_pack_exchange_bytes(int pack, int d_row, int d_col);
 int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64_t stride_hinv, int d_row, int d_col,
                         int n_remove, int32_t *order_out, double *err_out, const uint8_t *alive_in, int n_snap,
-                        const int32_t *snap_steps_host, float *W_snap, void *workspace, hipStream_t st,
-                        int **status_dev_out);
+                        const int32_t *snap_steps_host, float *W_snap, void *workspace, void *exchange,
+                        hipStream_t st, int **status_dev_out, int stall_wg);
 
-// The eager single-column kernel is kept as the fallback for shapes the deferred-update kernel
-// cannot hold in LDS, and can be forced with ZIPLM_PRUNE_EAGER=1 for cross-checking.
-static bool use_lazy_columns(int d_row, int d_col) {
-    const char *e = getenv("ZIPLM_PRUNE_EAGER");
-    if (e && e[0] == '1') return false;
-    return lazy_columns_feasible(d_row, d_col);
+// Single columns go to the deferred-update kernel whenever its per-workgroup state fits LDS; the eager kernel
+// below (one full read-modify-write of the state per step) covers the other shapes and has an entry point of its own.
+static bool use_lazy_columns(int d_row, int d_col) { return lazy_columns_feasible(d_row, d_col); }
+
+// What the device's status word means to the caller.
+static int status_to_return_code(int status) {
+    if (status > 0) return ZIPLM_ERR_NOT_PD;          // 1 + step with a non-positive pivot
+    if (status == -1) return ZIPLM_ERR_DEVICE;        // a bounded wait gave up
+    if (status < -1) return ZIPLM_ERR_INVALID_ARG;    // -(2 + step): no live structure left at that step
+    return ZIPLM_OK;
 }
 
 constexpr int PT = 512;        // threads per workgroup of the persistent kernel (= columns per tile)
@@ -68,7 +72,7 @@ struct PruneState {
     const int *snap_next;     // [n_snap] next snapshot at the same step, or -1
     float *W_snap;
     unsigned *bar;       // barrier arrival counter
-    int *status;         // 0 ok, >0: 1 + step with a non-positive pivot, -1: barrier timed out
+    int *status;         // 0 ok, >0: 1 + step with a non-positive pivot, -1: barrier timed out, < -1: -(2 + step) with nothing left alive
     // group path
     double *score;       // [G][SCORE_PARTS]
     double *Binv;        // [G][g*g]
@@ -254,7 +258,7 @@ __global__ __launch_bounds__(PT) void prune_columns_kernel(PruneState P) {
         }
         const int st = __hip_atomic_load(P.status, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (p < 0 || st != 0) {     // uniform over the grid: status was written before the barrier
-            if (gtid == 0 && st == 0) *P.status = 1 + t;
+            if (gtid == 0 && st == 0) *P.status = -(2 + t);      // nothing alive: more removals asked for than live columns
             break;
         }
         if (gtid == 0) {
@@ -603,7 +607,7 @@ __global__ __launch_bounds__(256) void group_update_kernel(PruneState P, BatchSh
     }
     if (status != 0) return;
     if (p < 0) {                                   // nothing left to remove: the request was impossible
-        if (blockIdx.x == 0 && tid == 0) *P.status = 1 + step;
+        if (blockIdx.x == 0 && tid == 0) *P.status = -(2 + step);
         return;
     }
     if (blockIdx.x == 0 && tid == 0) {
@@ -818,19 +822,12 @@ static int launch_group_steps(const PruneState &P, const BatchShift &B, int laye
 
 }  // namespace ziplm
 
-extern "C" size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap) {
-    if (d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size) return 0;
-    if (group_size == 1 && ziplm::use_lazy_columns(d_row, d_col))
-        return ziplm::lazy_columns_workspace_bytes(d_row, d_col, n_snap);
-    return ziplm::prune_layout(d_row, d_col, group_size, n_snap, nullptr).bytes;
-}
+namespace ziplm {
 
-extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int group_size,
-                                          int n_remove, int32_t *order_out, double *err_out,
-                                          const uint8_t *alive_in, int n_snap,
-                                          const int32_t *snapshot_steps_host, float *W_snap, int *info_host,
-                                          void *workspace, size_t workspace_bytes, void *stream) {
-    using namespace ziplm;
+// Arguments shared by the single-layer entry points, validated before anything is enqueued.
+static int check_prune_args(const float *W, const float *Hinv, int d_row, int d_col, int group_size, int n_remove,
+                            const int32_t *order_out, const double *err_out, int n_snap,
+                            const int32_t *snapshot_steps_host, const float *W_snap) {
     if (!W || !Hinv || d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size) return ZIPLM_ERR_INVALID_ARG;
     const int G = d_col / group_size;
     if (n_remove < 0 || n_remove > G) return ZIPLM_ERR_INVALID_ARG;
@@ -839,40 +836,36 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
     for (int q = 0; q < n_snap; ++q)
         if (snapshot_steps_host[q] < 0 || snapshot_steps_host[q] > n_remove) return ZIPLM_ERR_INVALID_ARG;
     if (group_size > GMAX) return ZIPLM_ERR_UNSUPPORTED;
-    const size_t need = ziplm_prune_workspace_bytes(d_row, d_col, group_size, n_snap);
-    if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    return ZIPLM_OK;
+}
 
-    if (group_size == 1 && use_lazy_columns(d_row, d_col)) {
-        int *status_dev = nullptr;
-        const int rc = lazy_columns_launch(W, Hinv, 1, 0, 0, d_row, d_col, n_remove, order_out, err_out, alive_in,
-                                           n_snap, snapshot_steps_host, W_snap, workspace, st, &status_dev);
-        if (rc != ZIPLM_OK) return rc;
-        if (info_host) {
-            int status = 0;
-            ZIPLM_HIP_TRY(hipStreamSynchronize(st));
-            ZIPLM_HIP_TRY(hipMemcpy(&status, status_dev, sizeof(int), hipMemcpyDeviceToHost));
-            *info_host = status;
-            if (status > 0) return ZIPLM_ERR_NOT_PD;
-            if (status < 0) return ZIPLM_ERR_DEVICE;
-        }
-        return ZIPLM_OK;
-    }
+static int report_status(const int *status_dev, int *info_host, hipStream_t st) {
+    if (!info_host) return ZIPLM_OK;
+    int status = 0;
+    ZIPLM_HIP_TRY(hipStreamSynchronize(st));
+    ZIPLM_HIP_TRY(hipMemcpy(&status, status_dev, sizeof(int), hipMemcpyDeviceToHost));
+    *info_host = status;
+    return status_to_return_code(status);
+}
 
+// Eager single-column kernel and the two-launch group path on a validated request.
+static int launch_eager_or_groups(float *W, float *Hinv, int d_row, int d_col, int group_size, int n_remove,
+                                  int32_t *order_out, double *err_out, const uint8_t *alive_in, int n_snap,
+                                  const int32_t *snapshot_steps_host, float *W_snap, int *info_host, void *workspace,
+                                  hipStream_t st) {
+    const int G = d_col / group_size;
     PruneLayout l = prune_layout(d_row, d_col, group_size, n_snap, workspace);
     PruneState &P = l.st;
     P.W = W; P.Hinv = Hinv; P.n_remove = n_remove;
     P.order = order_out; P.err = err_out; P.alive_in = alive_in; P.W_snap = W_snap;
-
     {
         const int rc = upload_snapshot_schedule(l, P, G, n_snap, snapshot_steps_host, st);
         if (rc != ZIPLM_OK) return rc;
     }
     // bar and status are adjacent 256-byte slots
-    ZIPLM_HIP_TRY(hipMemsetAsync(P.bar, 0, 2 * kAlign, st));
-
-    // the device counts removals against the structures that are alive; an impossible request
-    // (n_remove above the live count) shows up as "no candidate" -> status = 1 + step
+    if (zero_fill(P.bar, 2 * kAlign, st) != ZIPLM_OK) return ZIPLM_ERR_DEVICE;
+    // the device counts removals against the structures that are alive; a request for more than that shows up
+    // as "no candidate" -> status = -(2 + step)
     if (group_size == 1) {
         int per_cu = 0;
         ZIPLM_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, prune_columns_kernel, PT, 0));
@@ -886,18 +879,111 @@ extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int 
         const int rc = launch_group_steps(P, none, 1, n_remove, n_snap, st);
         if (rc != ZIPLM_OK) return rc;
     }
+    return report_status(P.status, info_host, st);
+}
 
-    if (info_host) {
-        int status = 0;
-        ZIPLM_HIP_TRY(hipStreamSynchronize(st));
-        ZIPLM_HIP_TRY(hipMemcpy(&status, P.status, sizeof(int), hipMemcpyDeviceToHost));
-        *info_host = status;
-        if (status > 0) return ZIPLM_ERR_NOT_PD;
-        if (status < 0) return ZIPLM_ERR_DEVICE;
+}  // namespace ziplm
+
+extern "C" size_t ziplm_prune_workspace_bytes(int d_row, int d_col, int group_size, int n_snap) {
+    if (d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size) return 0;
+    if (group_size == 1 && ziplm::use_lazy_columns(d_row, d_col))
+        return ziplm::lazy_columns_workspace_bytes(d_row, d_col, n_snap);
+    return ziplm::prune_layout(d_row, d_col, group_size, n_snap, nullptr).bytes;
+}
+
+extern "C" size_t ziplm_prune_exchange_bytes(int n_layers, int d_row, int d_col, int group_size) {
+    if (n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size != 1 || !ziplm::use_lazy_columns(d_row, d_col)) return 0;
+    size_t need = 0;
+    for (int done = 0; done < n_layers;) {
+        const int pack = ziplm::lazy_columns_pack(n_layers - done, d_row, d_col);
+        const size_t b = ziplm::lazy_columns_pack_exchange_bytes(pack, d_row, d_col);
+        need = b > need ? b : need;
+        done += pack;
     }
+    return need;
+}
+
+extern "C" int ziplm_exchange_alloc(size_t bytes, void **exchange_out) {
+    if (!exchange_out || bytes == 0) return ZIPLM_ERR_INVALID_ARG;
+    *exchange_out = nullptr;
+    void *q = nullptr;
+    if (hipExtMallocWithFlags(&q, ziplm::align_up(bytes), hipDeviceMallocUncached) != hipSuccess) {
+        (void)hipGetLastError();
+        return ZIPLM_ERR_DEVICE;
+    }
+    *exchange_out = q;
     return ZIPLM_OK;
 }
 
+// exchange == NULL: the slots and payloads live in the workspace.  Otherwise it must be aligned and large enough.
+static int check_exchange(const void *exchange, size_t exchange_bytes, size_t need) {
+    if (!exchange) return ZIPLM_OK;
+    return ziplm::workspace_ok(exchange, exchange_bytes, need) ? ZIPLM_OK : ZIPLM_ERR_WORKSPACE;
+}
+
+extern "C" int ziplm_structured_obs_prune(float *W, float *Hinv, int d_row, int d_col, int group_size,
+                                          int n_remove, int32_t *order_out, double *err_out,
+                                          const uint8_t *alive_in, int n_snap,
+                                          const int32_t *snapshot_steps_host, float *W_snap, int *info_host,
+                                          void *exchange, size_t exchange_bytes,
+                                          void *workspace, size_t workspace_bytes, void *stream) {
+    using namespace ziplm;
+    const int bad = check_prune_args(W, Hinv, d_row, d_col, group_size, n_remove, order_out, err_out, n_snap,
+                                     snapshot_steps_host, W_snap);
+    if (bad != ZIPLM_OK) return bad;
+    const size_t need = ziplm_prune_workspace_bytes(d_row, d_col, group_size, n_snap);
+    if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    if (group_size == 1 && use_lazy_columns(d_row, d_col)) {
+        if (check_exchange(exchange, exchange_bytes, lazy_columns_pack_exchange_bytes(1, d_row, d_col)) != ZIPLM_OK)
+            return ZIPLM_ERR_WORKSPACE;
+        int *status_dev = nullptr;
+        const int rc = lazy_columns_launch(W, Hinv, 1, 0, 0, d_row, d_col, n_remove, order_out, err_out, alive_in,
+                                           n_snap, snapshot_steps_host, W_snap, workspace, exchange, st, &status_dev, -1);
+        if (rc != ZIPLM_OK) return rc;
+        return report_status(status_dev, info_host, st);
+    }
+    return launch_eager_or_groups(W, Hinv, d_row, d_col, group_size, n_remove, order_out, err_out, alive_in, n_snap,
+                                  snapshot_steps_host, W_snap, info_host, workspace, st);
+}
+
+extern "C" size_t ziplm_prune_eager_workspace_bytes(int d_row, int d_col, int n_snap) {
+    if (d_row <= 0 || d_col <= 0) return 0;
+    return ziplm::prune_layout(d_row, d_col, 1, n_snap, nullptr).bytes;
+}
+
+extern "C" int ziplm_structured_obs_prune_eager(float *W, float *Hinv, int d_row, int d_col, int n_remove,
+                                                int32_t *order_out, double *err_out, const uint8_t *alive_in,
+                                                int n_snap, const int32_t *snapshot_steps_host, float *W_snap,
+                                                int *info_host, void *workspace, size_t workspace_bytes,
+                                                void *stream) {
+    using namespace ziplm;
+    const int bad = check_prune_args(W, Hinv, d_row, d_col, 1, n_remove, order_out, err_out, n_snap,
+                                     snapshot_steps_host, W_snap);
+    if (bad != ZIPLM_OK) return bad;
+    if (!workspace_ok(workspace, workspace_bytes, ziplm_prune_eager_workspace_bytes(d_row, d_col, n_snap)))
+        return ZIPLM_ERR_WORKSPACE;
+    return launch_eager_or_groups(W, Hinv, d_row, d_col, 1, n_remove, order_out, err_out, alive_in, n_snap,
+                                  snapshot_steps_host, W_snap, info_host, workspace, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int ziplm_selftest_bounded_wait(float *W, float *Hinv, int d_row, int d_col, int32_t *order_out,
+                                           double *err_out, int *info_host, void *workspace,
+                                           size_t workspace_bytes, void *stream) {
+    using namespace ziplm;
+    const int bad = check_prune_args(W, Hinv, d_row, d_col, 1, d_col, order_out, err_out, 0, nullptr, nullptr);
+    if (bad != ZIPLM_OK) return bad;
+    if (!info_host) return ZIPLM_ERR_INVALID_ARG;
+    if (!use_lazy_columns(d_row, d_col)) return ZIPLM_ERR_UNSUPPORTED;
+    if (!workspace_ok(workspace, workspace_bytes, ziplm_prune_workspace_bytes(d_row, d_col, 1, 0))) return ZIPLM_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int *status_dev = nullptr;
+    const int rc = lazy_columns_launch(W, Hinv, 1, 0, 0, d_row, d_col, d_col, order_out, err_out, nullptr, 0, nullptr,
+                                       nullptr, workspace, nullptr, st, &status_dev, 0);
+    if (rc != ZIPLM_OK) return rc;
+    return report_status(status_dev, info_host, st);
+}
 
 extern "C" size_t ziplm_prune_batch_workspace_bytes(int n_layers, int d_row, int d_col, int group_size, int n_snap) {
     if (n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size < 1 || group_size > ziplm::GMAX || d_col % group_size) return 0;
@@ -920,21 +1006,26 @@ extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_lay
                                                 int64_t stride_hinv, int d_row, int d_col, int group_size,
                                                 int n_remove, int32_t *order_out, double *err_out, int n_snap,
                                                 const int32_t *snapshot_steps_host, float *W_snap, int *info_host,
+                                                void *exchange, size_t exchange_bytes,
                                                 void *workspace, size_t workspace_bytes, void *stream) {
     using namespace ziplm;
-    if (!W || !Hinv || n_layers <= 0 || d_row <= 0 || d_col <= 0 || group_size <= 0 || d_col % group_size)
-        return ZIPLM_ERR_INVALID_ARG;
+    if (n_layers <= 0) return ZIPLM_ERR_INVALID_ARG;
+    const int bad = check_prune_args(W, Hinv, d_row, d_col, group_size, n_remove, order_out, err_out, n_snap,
+                                     snapshot_steps_host, W_snap);
+    if (bad != ZIPLM_OK) return bad;
     if (stride_w < (int64_t)d_row * d_col || stride_hinv < (int64_t)d_col * d_col) return ZIPLM_ERR_INVALID_ARG;
     const int G = d_col / group_size;
-    if (n_remove < 0 || n_remove > G) return ZIPLM_ERR_INVALID_ARG;
-    if (n_remove > 0 && (!order_out || !err_out)) return ZIPLM_ERR_INVALID_ARG;
-    if (n_snap < 0 || (n_snap > 0 && (!snapshot_steps_host || !W_snap))) return ZIPLM_ERR_INVALID_ARG;
-    for (int q = 0; q < n_snap; ++q)
-        if (snapshot_steps_host[q] < 0 || snapshot_steps_host[q] > n_remove) return ZIPLM_ERR_INVALID_ARG;
-    if (group_size > GMAX) return ZIPLM_ERR_UNSUPPORTED;
     const size_t need = ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap);
     if (!workspace_ok(workspace, workspace_bytes, need)) return ZIPLM_ERR_WORKSPACE;
+    if (check_exchange(exchange, exchange_bytes, ziplm_prune_exchange_bytes(n_layers, d_row, d_col, group_size)) != ZIPLM_OK)
+        return ZIPLM_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // the worst status over the layers: a device failure outranks an impossible request outranks a bad pivot
+    auto worse = [](int a, int b) {
+        auto rank = [](int rc) { return rc == ZIPLM_ERR_DEVICE ? 3 : rc == ZIPLM_ERR_INVALID_ARG ? 2 : rc == ZIPLM_ERR_NOT_PD ? 1 : 0; };
+        return rank(b) > rank(a) ? b : a;
+    };
 
     if (group_size == 1) {
         // Single columns: a few layers per launch, each on its share of the compute units; the launches follow
@@ -947,18 +1038,18 @@ extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_lay
             double *el = err_out ? err_out + (size_t)done * n_remove : nullptr;
             float *sl = W_snap ? W_snap + (size_t)done * snap_stride : nullptr;
             if (!use_lazy_columns(d_row, d_col)) {
-                const int rc = ziplm_structured_obs_prune(Wl, Hl, d_row, d_col, 1, n_remove, ol, el, nullptr, n_snap,
-                                                          snapshot_steps_host, sl, info_host ? info_host + done : nullptr,
-                                                          workspace, workspace_bytes, stream);
-                if (rc == ZIPLM_ERR_DEVICE || (rc == ZIPLM_ERR_NOT_PD && worst == ZIPLM_OK)) worst = rc;
-                else if (rc != ZIPLM_OK && rc != ZIPLM_ERR_NOT_PD) return rc;
+                const int rc = launch_eager_or_groups(Wl, Hl, d_row, d_col, 1, n_remove, ol, el, nullptr, n_snap,
+                                                      snapshot_steps_host, sl, info_host ? info_host + done : nullptr,
+                                                      workspace, st);
+                if (rc != ZIPLM_OK && rc != ZIPLM_ERR_NOT_PD && rc != ZIPLM_ERR_DEVICE && rc != ZIPLM_ERR_INVALID_ARG) return rc;
+                worst = worse(worst, rc);
                 done += 1;
                 continue;
             }
             const int pack = lazy_columns_pack(n_layers - done, d_row, d_col);
             int *status_dev[16] = {};
             const int rc = lazy_columns_launch(Wl, Hl, pack, stride_w, stride_hinv, d_row, d_col, n_remove, ol, el, nullptr,
-                                               n_snap, snapshot_steps_host, sl, workspace, st, status_dev);
+                                               n_snap, snapshot_steps_host, sl, workspace, exchange, st, status_dev, -1);
             if (rc != ZIPLM_OK) return rc;
             if (info_host) {
                 // the next launch reuses the status words
@@ -967,8 +1058,7 @@ extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_lay
                     int status = 0;
                     ZIPLM_HIP_TRY(hipMemcpy(&status, status_dev[q], sizeof(int), hipMemcpyDeviceToHost));
                     info_host[done + q] = status;
-                    if (status > 0 && worst == ZIPLM_OK) worst = ZIPLM_ERR_NOT_PD;
-                    if (status < 0) worst = ZIPLM_ERR_DEVICE;
+                    worst = worse(worst, status_to_return_code(status));
                 }
             }
             done += pack;
@@ -989,7 +1079,7 @@ extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_lay
         if (rc != ZIPLM_OK) return rc;
     }
     for (int q = 0; q < n_layers; ++q)     // bar and status of every layer
-        ZIPLM_HIP_TRY(hipMemsetAsync(reinterpret_cast<char *>(P.bar) + (size_t)q * l.bytes, 0, 2 * kAlign, st));
+        if (zero_fill(reinterpret_cast<char *>(P.bar) + (size_t)q * l.bytes, 2 * kAlign, st) != ZIPLM_OK) return ZIPLM_ERR_DEVICE;
     {
         const int rc = launch_group_steps(P, B, n_layers, n_remove, n_snap, st);
         if (rc != ZIPLM_OK) return rc;
@@ -1002,8 +1092,7 @@ extern "C" int ziplm_structured_obs_prune_batch(float *W, float *Hinv, int n_lay
             ZIPLM_HIP_TRY(hipMemcpy(&status, reinterpret_cast<char *>(P.status) + (size_t)q * l.bytes, sizeof(int),
                                     hipMemcpyDeviceToHost));
             info_host[q] = status;
-            if (status > 0 && worst == ZIPLM_OK) worst = ZIPLM_ERR_NOT_PD;
-            if (status < 0) worst = ZIPLM_ERR_DEVICE;
+            worst = worse(worst, status_to_return_code(status));
         }
         return worst;
     }

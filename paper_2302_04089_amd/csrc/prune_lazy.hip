@@ -40,12 +40,8 @@
 // whose column tile has not been reached yet gets the previous block's downdates applied on the fly,
 // exactly like the pending ones of the current block.  All waits are bounded: on a time-out the waiter raises status = -1 and
 // leaves; the others then time out or see the flag, and the grid drains.
-#include <stdio.h>
-#include <stdlib.h>
-
-#include <mutex>
-
 #include "common.h"
+#include "lazy_timing.h"
 
 namespace ziplm {
 
@@ -93,9 +89,8 @@ struct State {
     int cpb;                      // columns per workgroup
     int cp;                       // cpb rounded up to a multiple of RG
     int pay_words;                // m + 4*BMAX + 2
-#ifdef ZIPLM_LAZY_TIMING
-    unsigned long long *timing;   // [8] accumulated 100 MHz ticks per phase (workgroup 0), then [nb] local ticks
-#endif
+    int stall_wg;                 // -1; the self-test of the bounded waits names a workgroup that never takes part
+    ZIPLM_LAZY_TIMING_FIELD
 };
 
 // One launch runs the loops of up to MAX_PACK layers of one shape side by side, each on its own nb workgroups
@@ -370,27 +365,24 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
     }
 }
 
-#ifdef ZIPLM_LAZY_TIMING
-#define TICK(slot) do { if (b == 0 && tid == 0) { const unsigned long long now_ = wall_clock64(); tacc[slot] += now_ - tlast; tlast = now_; } } while (0)
-#else
-#define TICK(slot) do { } while (0)
-#endif
-
 // PACKED: several layers share the launch.  The single-layer instantiations address the one State through
 // constant offsets of the kernel argument; with the layer chosen at run time the compiler re-reads fields
 // inside the loop, which costs the single-layer loop 2.5%.
 template <bool W_IN_LDS, bool PACKED>
 __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-#ifdef ZIPLM_LAZY_TIMING
-    unsigned long long tacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    unsigned long long tlast = wall_clock64();
-    unsigned long long tlocal = 0, texch = wall_clock64();
-#endif
+    ZIPLM_LAZY_TIMING_LOCALS
     const int nb = PACKED ? pack.nb : (int)gridDim.x;
     const int layer = PACKED ? blockIdx.x / nb : 0, b = blockIdx.x - layer * nb;
     const State &S = pack.s[layer];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (!PACKED && S.stall_wg == b) {
+        // Self-test of the bounded waits (single-layer launches only): this workgroup withholds its candidates, the
+        // others wait for them, give up at the limit and raise the status word, which this workgroup polls (bounded
+        // as well) before it leaves.
+        if (tid == 0) { Waiter w; while (w.again(S.status)) {} }
+        return;
+    }
     const int m = S.m, d = S.d, cpb = S.cpb, cp = S.cp;
     const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb);
     double *uloc = reinterpret_cast<double *>(smem + L.uloc);
@@ -564,9 +556,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
         if (tid == 0) {
             if (!slot_early)
                 __hip_atomic_store(S.slots + (size_t)par * nb + b, key | tag4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#ifdef ZIPLM_LAZY_TIMING
-            tlocal += wall_clock64() - texch;
-#endif
+            ZIPLM_LAZY_TIMING_LOCAL_DONE;
         }
         // The payload travels ahead of the exchange only from workgroups that are likely to win (score
         // within the range of the previous step's leaders); any other winner publishes after the
@@ -606,9 +596,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             for (int sb = tid; sb < nb; sb += LT) {
                 unsigned long long kv;
                 if (!slot_wait(S.slots + (size_t)par * nb + sb, tag4, sb, cpb, kv, err, S.status)) { fail = true; break; }
-#ifdef ZIPLM_LAZY_TIMING
-                if (b == 0 && tid == 0) tacc[7] += wall_clock64() - tlast;     // own slot seen again: store -> load round trip
-#endif
+                ZIPLM_LAZY_TIMING_OWN_SLOT;
                 mykey = umin64(mykey, kv);
             }
             if (bg_active && wave >= NPOLL) {
@@ -640,12 +628,13 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             tau = (nwaves_used >= 2) ? __longlong_as_double((long long)(kmax | 0xffffull)) : 1.0e300;
         }
         TICK(2);
-#ifdef ZIPLM_LAZY_TIMING
-        if (tid == 0) texch = wall_clock64();
-#endif
+        ZIPLM_LAZY_TIMING_EXCHANGE_DONE;
         // A dependent LDS read costs a fifth of a microsecond on this path: the time-out and error flags of the
         // exchange are looked at after step 3 (p is a valid column or "none" whatever they say).
-        if (p < 0) { error_step = 1 + t; break; }              // same inputs in every workgroup: uniform
+        // same inputs in every workgroup: uniform.  No candidate at all: nothing is left alive (the caller asked for
+        // more removals than live columns), unless a workgroup reported a non-positive diagonal entry -- told apart
+        // after the loop
+        if (p < 0) { error_step = -(2 + t); break; }
         const int owner = (int)(((unsigned long long)(unsigned)p * cpb_magic) >> 32);      // p / cpb
         // The thread index is made opaque for this stretch: predicates on it are then recomputed (one compare) where
         // they are used instead of being kept across the whole step loop in scalar register pairs, of which the
@@ -693,12 +682,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                     const int ct = p >> 4;
                     misc[4] = (bg_active && (ct / NBG) >= seq_done[NPOLL + ct % NBG]) ? 1 : 0;
                 }
-#ifdef ZIPLM_LAZY_TIMING
-                if (b == 1 && tid3 == 64 && owner != b) {      // was the payload there at the first look?
-                    S.timing[8 + 1024] += 1;
-                    S.timing[8 + 1025] += ((unsigned)(w0[0] & 0xffffffffu) == tag) ? 1 : 0;
-                }
-#endif
+                ZIPLM_LAZY_TIMING_PAYLOAD_SEEN(w0[0]);
                 if (tid3 < cp) hstale[tid3] = hv;
                 if (pa) {
                     unsigned hi = (unsigned)(a0 >> 32), lo = (unsigned)(a1 >> 32);
@@ -908,10 +892,9 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
 
     // ------------------------------------------------------------------ final masking + write-back
     __syncthreads();
-#ifdef ZIPLM_LAZY_TIMING
-    if (b == 0 && tid == 0) for (int q = 0; q < 8; ++q) S.timing[q] = tacc[q];
-    if (tid == 0) S.timing[8 + b] = tlocal;
-#endif
+    ZIPLM_LAZY_TIMING_WRITE_BACK;
+    // status: 1 + step for a non-positive diagonal entry, -(2 + step) when nothing was left to remove
+    if (error_step < -1 && misc[2]) error_step = -error_step - 1;
     if (b == 0 && tid == 0 && error_step != 0) atomicCAS(S.status, 0, error_step);
     if (ok && error_step == 0) {
         for (int c = tid; c < d; c += LT) {
@@ -967,59 +950,18 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     s.bar = c.take<unsigned long long>((size_t)p.nb);
     s.status = c.take<int>(1);
     l.snap_steps = c.take<int>((size_t)(n_snap > 0 ? n_snap : 1));
-#ifdef ZIPLM_LAZY_TIMING
-    s.timing = c.take<unsigned long long>(8 + 1024 + 8);
-#endif
+    ZIPLM_LAZY_TIMING_TAKE(s, c);
     l.bytes = c.off;
     return l;
 }
 
 // ------------------------------------------------------------------------------------------------
-// Exchange area: the candidate slots and the winner's payload, the two things other workgroups wait for.
-// In uncached device memory a store becomes visible to the other XCDs' loads sooner than through the write
-// path of the L2 (3% of the whole loop).  Such memory cannot be returned while the process lives (buffers
-// allocated after it was freed have been seen holding wrong values), so there is one area per device,
-// allocated on first use and kept; a layer whose payload does not fit, a failed allocation, or
-// ZIPLM_EXCHANGE_IN_WORKSPACE=1 fall back to the caller's workspace, which always has room for it.
-// Launches on different streams share the area: each waits for the previous one's event before it clears it.
+// Exchange area: the candidate slots and the winner's payload, the two things other workgroups wait for, of one
+// layer.  They live in the caller's workspace unless the caller passes a separate area (uncached device memory
+// makes a store visible to the other XCDs' loads sooner than the write path of the L2: 3% of the loop).
 // ------------------------------------------------------------------------------------------------
-struct ExchangeArea {
-    void *ptr = nullptr;
-    bool tried = false, used = false;
-    hipEvent_t last = nullptr;
-};
-constexpr size_t EXCHANGE_BYTES = (size_t)32 << 20;
-constexpr int EXCHANGE_MAX_DEVICES = 64;
-static ExchangeArea g_exchange[EXCHANGE_MAX_DEVICES];
-static std::mutex g_exchange_mutex;
-
-// per layer
 static size_t exchange_bytes_needed(const Plan &p) {
     return align_up(sizeof(unsigned long long) * (size_t)2 * p.nb) + align_up(sizeof(unsigned long long) * (size_t)2 * p.nb * p.pay_words);
-}
-
-// Caller holds g_exchange_mutex.  nullptr: use the workspace.
-static ExchangeArea *exchange_area_for(const Plan &p, int pack) {
-    const char *e = getenv("ZIPLM_EXCHANGE_IN_WORKSPACE");
-    if (e && e[0] == '1') return nullptr;
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= EXCHANGE_MAX_DEVICES) return nullptr;
-    if ((size_t)pack * exchange_bytes_needed(p) > EXCHANGE_BYTES) return nullptr;
-    ExchangeArea &a = g_exchange[dev];
-    if (!a.tried) {
-        a.tried = true;
-        void *q = nullptr;
-        if (hipExtMallocWithFlags(&q, EXCHANGE_BYTES, hipDeviceMallocUncached) != hipSuccess) {
-            (void)hipGetLastError();
-            return nullptr;
-        }
-        if (hipEventCreateWithFlags(&a.last, hipEventDisableTiming) != hipSuccess) {
-            (void)hipGetLastError();
-            return nullptr;             // the memory stays allocated: it must not be freed
-        }
-        a.ptr = q;
-    }
-    return a.ptr ? &a : nullptr;
 }
 
 }  // namespace lazy
@@ -1046,13 +988,21 @@ size_t lazy_columns_pack_workspace_bytes(int pack, int d_row, int d_col, int n_s
     return (size_t)pack * lazy::make_layout(d_row, d_col, n_snap, p, nullptr).bytes;
 }
 
+// bytes of a separate exchange area for one launch of `pack` layers
+size_t lazy_columns_pack_exchange_bytes(int pack, int d_row, int d_col) {
+    const lazy::Plan p = lazy::make_plan(d_row, d_col, pack);
+    return p.feasible ? (size_t)pack * lazy::exchange_bytes_needed(p) : 0;
+}
+
 // Enqueues the whole loop of `pack` layers (layer l: W + l * stride_w, Hinv + l * stride_hinv, order_out and
 // err_out + l * n_remove, W_snap + l * n_snap * d_row * d_col).  status_dev_out[l] receives the device address
-// of layer l's status word.  alive_in applies to a single layer only.
+// of layer l's status word.  alive_in applies to a single layer only.  exchange: nullptr (the slots and payloads
+// then live in the workspace) or an area of at least lazy_columns_pack_exchange_bytes bytes.  stall_wg: -1, or the
+// workgroup (of layer 0) that the self-test of the bounded waits keeps out of the loop.
 int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64_t stride_hinv, int d_row, int d_col,
                         int n_remove, int32_t *order_out, double *err_out, const uint8_t *alive_in, int n_snap,
-                        const int32_t *snap_steps_host, float *W_snap, void *workspace, hipStream_t st,
-                        int **status_dev_out) {
+                        const int32_t *snap_steps_host, float *W_snap, void *workspace, void *exchange,
+                        hipStream_t st, int **status_dev_out, int stall_wg) {
     using namespace lazy;
     if (pack < 1 || pack > MAX_PACK || (pack > 1 && alive_in)) return ZIPLM_ERR_INVALID_ARG;
     const Plan p = make_plan(d_row, d_col, pack);
@@ -1072,28 +1022,27 @@ int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64
         S.n_snap = n_snap; S.snap_steps = lay[0].snap_steps;
         S.W_snap = W_snap ? W_snap + (size_t)q * n_snap * d_row * d_col : nullptr;
         S.cpb = p.cpb; S.cp = p.cp; S.pay_words = p.pay_words;
+        S.stall_wg = (q == 0) ? stall_wg : -1;
     }
     if (n_snap > 0) {
         // pageable source: staged before the call returns
         ZIPLM_HIP_TRY(hipMemcpyAsync(lay[0].snap_steps, snap_steps_host, sizeof(int) * (size_t)n_snap, hipMemcpyHostToDevice, st));
         ZIPLM_HIP_TRY(hipStreamSynchronize(st));
     }
-    std::lock_guard<std::mutex> guard(g_exchange_mutex);       // held until the launch and its event are enqueued
-    ExchangeArea *xa = exchange_area_for(p, pack);
+    const bool xa = exchange != nullptr;
     if (xa) {
-        if (xa->used) ZIPLM_HIP_TRY(hipStreamWaitEvent(st, xa->last, 0));
-        Carver cx(xa->ptr);
+        Carver cx(exchange);
         for (int q = 0; q < pack; ++q) {
             lay[q].st.slots = cx.take<unsigned long long>((size_t)2 * p.nb);
             lay[q].st.pay = cx.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
         }
-        ZIPLM_HIP_TRY(hipMemsetAsync(xa->ptr, 0, cx.off, st));
+        if (zero_fill(exchange, cx.off, st) != ZIPLM_OK) return ZIPLM_ERR_DEVICE;
     }
     for (int q = 0; q < pack; ++q) {
         // zero-initialised: slots, payload, barrier epochs, status (contiguous in the workspace, in this order)
         Layout ws_lay = make_layout(d_row, d_col, n_snap, p, static_cast<char *>(workspace) + (size_t)q * layer_bytes);
         char *zero_from = reinterpret_cast<char *>(xa ? (void *)ws_lay.st.bar : (void *)ws_lay.st.slots);
-        ZIPLM_HIP_TRY(hipMemsetAsync(zero_from, 0, reinterpret_cast<char *>(ws_lay.snap_steps) - zero_from, st));
+        if (zero_fill(zero_from, reinterpret_cast<char *>(ws_lay.snap_steps) - zero_from, st) != ZIPLM_OK) return ZIPLM_ERR_DEVICE;
         pk.s[q] = lay[q].st;
         status_dev_out[q] = lay[q].st.status;
     }
@@ -1108,32 +1057,7 @@ int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64
     if (per_cu < 1 || pack * p.nb > per_cu * device_cu_count()) return ZIPLM_ERR_DEVICE;
     void *args[] = {&pk};
     ZIPLM_HIP_TRY(hipLaunchCooperativeKernel(const_cast<void *>(fn), dim3(pack * p.nb), dim3(LT), args, (unsigned)p.lds_bytes, st));
-    if (xa) {
-        ZIPLM_HIP_TRY(hipEventRecord(xa->last, st));
-        xa->used = true;
-    }
-#ifdef ZIPLM_LAZY_TIMING
-    {
-        unsigned long long tm[8];
-        hipStreamSynchronize(st);
-        hipMemcpy(tm, lay[0].st.timing, sizeof(tm), hipMemcpyDeviceToHost);
-        const char *names[8] = {"snapshot+loop top", "candidate+publish", "exchange+argmin", "payload+gather", "row slice + Eq.3",
-                                "flush barrier", "flush update", "(own slot round trip)"};
-        for (int q = 0; q < 8; ++q)
-            fprintf(stderr, "[lazy timing] %-20s %9.3f ms total  %7.3f us/step\n", names[q], tm[q] * 1e-5,
-                    tm[q] * 1e-2 / (n_remove > 0 ? n_remove : 1));
-        unsigned long long loc[1024];
-        hipMemcpy(loc, lay[0].st.timing + 8, sizeof(unsigned long long) * p.nb, hipMemcpyDeviceToHost);
-        double mn = 1e30, mx = 0, sum = 0; int imx = 0;
-        for (int q = 0; q < p.nb; ++q) { double v = loc[q] * 1e-2 / (n_remove > 0 ? n_remove : 1); sum += v; if (v < mn) mn = v; if (v > mx) { mx = v; imx = q; } }
-        fprintf(stderr, "[lazy timing] local us/step (exchange done -> slot published): min %.3f avg %.3f max %.3f (block %d)\n", mn, sum / p.nb, mx, imx);
-        { unsigned long long pr[2]; hipMemcpy(pr, lay[0].st.timing + 8 + 1024, sizeof(pr), hipMemcpyDeviceToHost);
-          if (pr[0]) fprintf(stderr, "[lazy timing] winner's payload already visible at the first read of step 3: %.1f%% of %llu steps (workgroup 1)\n", 100.0 * pr[1] / pr[0], pr[0]); }
-        { double x[8] = {0}; int c[8] = {0}; for (int q = 0; q < p.nb; ++q) { x[q & 7] += loc[q] * 1e-2 / n_remove; c[q & 7]++; }
-          fprintf(stderr, "[lazy timing] local us/step by workgroup index mod 8:"); for (int q = 0; q < 8; ++q) fprintf(stderr, " %.3f", x[q] / (c[q] ? c[q] : 1)); fprintf(stderr, "\n");
-          fprintf(stderr, "[lazy timing] local us/step by workgroup index / 32:"); for (int g = 0; g < 8; ++g) { double a = 0; int n = 0; for (int q = 32 * g; q < 32 * g + 32 && q < p.nb; ++q) { a += loc[q] * 1e-2 / n_remove; ++n; } fprintf(stderr, " %.3f", n ? a / n : 0.0); } fprintf(stderr, "\n"); }
-    }
-#endif
+    ZIPLM_LAZY_TIMING_REPORT(lay[0].st, p.nb, n_remove, st);
     return ZIPLM_OK;
 }
 

@@ -29,6 +29,9 @@ EXPORTS = (
     "ziplm_structured_obs_prune", "ziplm_prune_workspace_bytes",
     "ziplm_module_error", "ziplm_module_error_workspace_bytes", "ziplm_prior",
     "ziplm_structured_obs_prune_batch", "ziplm_prune_batch_workspace_bytes",
+    "ziplm_prune_exchange_bytes", "ziplm_exchange_alloc",
+    "ziplm_structured_obs_prune_eager", "ziplm_prune_eager_workspace_bytes",
+    "ziplm_selftest_bounded_wait",
 )
 
 _lib = None
@@ -66,12 +69,25 @@ def lib():
     L.ziplm_structured_obs_prune.restype = i32
     L.ziplm_structured_obs_prune.argtypes = [vp, vp, i32, i32, i32, i32, vp, vp, vp, i32,
                                              ctypes.POINTER(ctypes.c_int32), vp, ctypes.POINTER(i32),
-                                             vp, sz, vp]
+                                             vp, sz, vp, sz, vp]
+    L.ziplm_prune_exchange_bytes.restype = sz
+    L.ziplm_prune_exchange_bytes.argtypes = [i32, i32, i32, i32]
+    L.ziplm_exchange_alloc.restype = i32
+    L.ziplm_exchange_alloc.argtypes = [sz, ctypes.POINTER(vp)]
+    L.ziplm_structured_obs_prune_eager.restype = i32
+    L.ziplm_structured_obs_prune_eager.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp, i32,
+                                                   ctypes.POINTER(ctypes.c_int32), vp, ctypes.POINTER(i32),
+                                                   vp, sz, vp]
+    L.ziplm_prune_eager_workspace_bytes.restype = sz
+    L.ziplm_prune_eager_workspace_bytes.argtypes = [i32, i32, i32]
+    L.ziplm_selftest_bounded_wait.restype = i32
+    L.ziplm_selftest_bounded_wait.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
     L.ziplm_prune_workspace_bytes.restype = sz
     L.ziplm_prune_workspace_bytes.argtypes = [i32, i32, i32, i32]
     L.ziplm_structured_obs_prune_batch.restype = i32
     L.ziplm_structured_obs_prune_batch.argtypes = [vp, vp, i32, i64, i64, i32, i32, i32, i32, vp, vp, i32,
-                                                   ctypes.POINTER(ctypes.c_int32), vp, ctypes.POINTER(i32), vp, sz, vp]
+                                                   ctypes.POINTER(ctypes.c_int32), vp, ctypes.POINTER(i32),
+                                                   vp, sz, vp, sz, vp]
     L.ziplm_prune_batch_workspace_bytes.restype = sz
     L.ziplm_prune_batch_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
     L.ziplm_module_error.restype = i32
@@ -149,10 +165,37 @@ def ziplm_hinv(H, damp_rel=0.01, out=None, workspace=None, stream=None, check=Tr
     return out, (lam.value if check else None)
 
 
+class ExchangeArea:
+    """An exchange area from ziplm_exchange_alloc: uncached device memory the caller keeps for the life of the
+    process (the library has no call that frees it) and passes to the single-column loops."""
+
+    def __init__(self, ptr, nbytes):
+        self.ptr = int(ptr)
+        self.nbytes = int(nbytes)
+
+
+def ziplm_prune_exchange_bytes(n_layers, d_row, d_col, group_size=1):
+    return int(lib().ziplm_prune_exchange_bytes(int(n_layers), int(d_row), int(d_col), int(group_size)))
+
+
+def ziplm_exchange_alloc(nbytes):
+    out = ctypes.c_void_p()
+    rc = lib().ziplm_exchange_alloc(int(nbytes), ctypes.byref(out))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return ExchangeArea(out.value, nbytes)
+
+
+def _exchange_args(exchange):
+    if exchange is None:
+        return None, 0
+    return ctypes.c_void_p(exchange.ptr), exchange.nbytes
+
+
 def ziplm_structured_obs_prune(W, Hinv, group_size, n_remove, alive=None, snapshot_steps=None,
-                               workspace=None, stream=None, check=True):
+                               workspace=None, stream=None, check=True, exchange=None):
     """Algorithm 1 in place on W and Hinv.  Returns (order int32[n_remove], err float64[n_remove],
-    W_snap or None), all on the device."""
+    W_snap or None), all on the device.  exchange: an ExchangeArea or None."""
     _check(W, torch.float32, "W")
     _check(Hinv, torch.float32, "Hinv")
     m, d = W.shape
@@ -172,10 +215,56 @@ def ziplm_structured_obs_prune(W, Hinv, group_size, n_remove, alive=None, snapsh
         W.data_ptr(), Hinv.data_ptr(), m, d, int(group_size), int(n_remove), order.data_ptr(), err.data_ptr(),
         alive.data_ptr() if alive is not None else None, n_snap, steps_c,
         W_snap.data_ptr() if n_snap else None, ctypes.byref(info) if check else None,
+        *_exchange_args(exchange), ws.data_ptr(), ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc, info.value)
+    return order[:n_remove], err[:n_remove], W_snap
+
+
+def ziplm_prune_eager_workspace_bytes(d_row, d_col, n_snap=0):
+    return int(lib().ziplm_prune_eager_workspace_bytes(int(d_row), int(d_col), int(n_snap)))
+
+
+def ziplm_structured_obs_prune_eager(W, Hinv, n_remove, alive=None, snapshot_steps=None, workspace=None,
+                                     stream=None, check=True):
+    """Algorithm 1 over single columns on the eager kernel (whole state read and written every step)."""
+    _check(W, torch.float32, "W")
+    _check(Hinv, torch.float32, "Hinv")
+    m, d = W.shape
+    dev = W.device
+    order = torch.empty(max(n_remove, 1), dtype=torch.int32, device=dev)
+    err = torch.empty(max(n_remove, 1), dtype=torch.float64, device=dev)
+    steps = [] if snapshot_steps is None else [int(s) for s in snapshot_steps]
+    n_snap = len(steps)
+    W_snap = torch.empty((n_snap, m, d), dtype=torch.float32, device=dev) if n_snap else None
+    steps_c = (ctypes.c_int32 * n_snap)(*steps) if n_snap else None
+    if alive is not None:
+        _check(alive, torch.uint8, "alive")
+    ws = workspace if workspace is not None else _workspace(ziplm_prune_eager_workspace_bytes(m, d, n_snap), dev)
+    info = ctypes.c_int(0)
+    rc = lib().ziplm_structured_obs_prune_eager(
+        W.data_ptr(), Hinv.data_ptr(), m, d, int(n_remove), order.data_ptr(), err.data_ptr(),
+        alive.data_ptr() if alive is not None else None, n_snap, steps_c,
+        W_snap.data_ptr() if n_snap else None, ctypes.byref(info) if check else None,
         ws.data_ptr(), ws.numel(), _stream(stream))
     if rc != OK:
         raise ZiplmError(rc, info.value)
     return order[:n_remove], err[:n_remove], W_snap
+
+
+def ziplm_selftest_bounded_wait(W, Hinv, workspace=None, stream=None):
+    """Runs the single-column loop with one workgroup held back; returns (status, info): expected
+    (ERR_DEVICE, -1) after a little over 4 s, with W and Hinv unchanged."""
+    _check(W, torch.float32, "W")
+    _check(Hinv, torch.float32, "Hinv")
+    m, d = W.shape
+    order = torch.empty(d, dtype=torch.int32, device=W.device)
+    err = torch.empty(d, dtype=torch.float64, device=W.device)
+    ws = workspace if workspace is not None else _workspace(ziplm_prune_workspace_bytes(m, d, 1, 0), W.device)
+    info = ctypes.c_int(0)
+    rc = lib().ziplm_selftest_bounded_wait(W.data_ptr(), Hinv.data_ptr(), m, d, order.data_ptr(), err.data_ptr(),
+                                           ctypes.byref(info), ws.data_ptr(), ws.numel(), _stream(stream))
+    return rc, info.value
 
 
 def ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap=0):
@@ -183,7 +272,7 @@ def ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap
 
 
 def ziplm_structured_obs_prune_batch(W, Hinv, group_size, n_remove, snapshot_steps=None, workspace=None,
-                                     stream=None, check=True):
+                                     stream=None, check=True, exchange=None):
     """Algorithm 1 for a stack of layers of one shape: W (n_layers, d_row, d_col), Hinv (n_layers, d_col,
     d_col), both in place.  Returns (order int32[n_layers, n_remove], err float64[n_layers, n_remove],
     W_snap (n_layers, n_snap, d_row, d_col) or None), all on the device."""
@@ -204,7 +293,7 @@ def ziplm_structured_obs_prune_batch(W, Hinv, group_size, n_remove, snapshot_ste
     rc = lib().ziplm_structured_obs_prune_batch(
         W.data_ptr(), Hinv.data_ptr(), n_layers, m * d, d * d, m, d, int(group_size), int(n_remove),
         order.data_ptr(), err.data_ptr(), n_snap, steps_c, W_snap.data_ptr() if n_snap else None,
-        info if check else None, ws.data_ptr(), ws.numel(), _stream(stream))
+        info if check else None, *_exchange_args(exchange), ws.data_ptr(), ws.numel(), _stream(stream))
     if rc != OK:
         raise ZiplmError(rc, list(info))
     if n_remove == 0:

@@ -347,36 +347,84 @@ def test_prune_more_than_sixteen_columns_per_workgroup(z, oracle, m):
     assert_columns_close(Hd.cpu().numpy(), ref["Hinv"], "Hd")
 
 
-def test_prune_eager_fallback_kernel(z, oracle, monkeypatch):
-    """The eager single-column kernel (used when the deferred-update kernel's state does not fit) is
-    selected with ZIPLM_PRUNE_EAGER=1 and must meet the same bar."""
-    monkeypatch.setenv("ZIPLM_PRUNE_EAGER", "1")
+def _run_eager_case(z, oracle, spec, n_remove, snaps):
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    Wd, Hd = dev(W32), dev(Hi32)
+    order, err, W_snap = z.ziplm_structured_obs_prune_eager(Wd, Hd, n_remove, snapshot_steps=snaps)
+    torch.cuda.synchronize()
+    ref = compare_run(oracle, W32, Hi32, 1, n_remove, order.cpu().numpy(), err.cpu().numpy(), snap_steps=snaps)
+    assert_columns_close(Wd.cpu().numpy(), ref["W"], "W after the call")
+    assert_columns_close(Hd.cpu().numpy(), ref["Hinv"], "surviving Hinv")
+    for q, k in enumerate(snaps or []):
+        assert_columns_close(W_snap[q].cpu().numpy(), ref["W_snap"][q], "snapshot after %d removals" % k)
+    return order, err
+
+
+def test_prune_eager_kernel_entry_point(z, oracle):
+    """The eager single-column kernel (Algorithm 1 as printed: the whole state read and written every step) through
+    its own entry point, at the same bar; a partial removal leaves the oracle's surviving inverse."""
     spec = workloads.small(40, 300, 1, 1200, x_kind="gelu", seed=31)
-    _run_prune_case(z, oracle, spec, 300, [0, 150, 300])
+    _run_eager_case(z, oracle, spec, 300, [0, 150, 300])
+    _run_eager_case(z, oracle, spec, 120, [60])
 
 
-def test_exchange_area_in_workspace_gives_identical_results(z, oracle, monkeypatch):
-    """The candidate slots and the winners' payloads live in a per-device uncached area by default and in the
-    caller's workspace with ZIPLM_EXCHANGE_IN_WORKSPACE=1: same arithmetic, bit-identical results."""
+def test_prune_falls_back_to_the_eager_kernel_for_a_very_tall_layer(z, oracle):
+    """A column of 40000 rows does not fit a workgroup's LDS, so ziplm_structured_obs_prune runs such a layer on
+    the eager kernel by itself (no exchange area: the query says 0), single call and batch alike."""
+    m, d, n = 40000, 24, 96
+    assert z.ziplm_prune_exchange_bytes(1, m, d) == 0 and z.ziplm_prune_exchange_bytes(1, 64, d) > 0
+    assert z.ziplm_prune_workspace_bytes(m, d, 1) == z.ziplm_prune_eager_workspace_bytes(m, d)
+    spec = workloads.small(m, d, 1, n, x_kind="gelu", seed=33)
+    _run_prune_case(z, oracle, spec, d, [0, d // 2, d])
+    specs = [workloads.small(m, d, 1, n, x_kind="normal", seed=34 + l) for l in range(2)]
+    ins = [_oracle_inputs(oracle, sp) for sp in specs]
+    Wb, Hb = dev(np.stack([i[1] for i in ins])), dev(np.stack([i[3] for i in ins]))
+    order_b, err_b, _ = z.ziplm_structured_obs_prune_batch(Wb, Hb, 1, d)
+    torch.cuda.synchronize()
+    for l in range(2):
+        compare_run(oracle, ins[l][1], ins[l][3], 1, d, order_b[l].cpu().numpy(), err_b[l].cpu().numpy())
+    assert float(Wb.abs().max()) == 0.0
+
+
+@pytest.fixture(scope="module")
+def exchange_area(z):
+    """One uncached exchange area for the whole module (such memory is never freed)."""
+    return z.ziplm_exchange_alloc(8 << 20)
+
+
+def test_separate_exchange_area_gives_identical_results(z, oracle, exchange_area):
+    """The candidate slots and the winners' payloads live in the caller's workspace, or in a separate area the
+    caller passes (uncached device memory from ziplm_exchange_alloc): same arithmetic, bit-identical results.
+    An area that is too small or misaligned is refused before anything runs."""
     spec = workloads.small(48, 320, 1, 1300, x_kind="gelu", seed=41)
     X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    need = z.ziplm_prune_exchange_bytes(1, 48, 320)
+    assert 0 < need <= exchange_area.nbytes and need % 256 == 0
     outs = []
-    for flag in ("0", "1"):
-        monkeypatch.setenv("ZIPLM_EXCHANGE_IN_WORKSPACE", flag)
+    for xa in (None, exchange_area):
         Wd, Hd = dev(W32), dev(Hi32)
-        o, e, sn = z.ziplm_structured_obs_prune(Wd, Hd, 1, 320, snapshot_steps=[160])
+        o, e, sn = z.ziplm_structured_obs_prune(Wd, Hd, 1, 320, snapshot_steps=[160], exchange=xa)
         outs.append((o.cpu(), e.cpu(), Wd.cpu(), Hd.cpu(), sn.cpu()))
     for a, b in zip(*outs):
         assert torch.equal(a, b)
     compare_run(oracle, W32, Hi32, 1, 320, outs[0][0].numpy(), outs[0][1].numpy(), snap_steps=[160])
+    Wd, Hd = dev(W32), dev(Hi32)
+    for bad in (z.ExchangeArea(exchange_area.ptr, need - 256), z.ExchangeArea(exchange_area.ptr + 8, exchange_area.nbytes - 8)):
+        with pytest.raises(z.ZiplmError) as ei:
+            z.ziplm_structured_obs_prune(Wd, Hd, 1, 320, exchange=bad)
+        assert ei.value.status == z.ERR_WORKSPACE
+    assert torch.equal(Wd.cpu(), torch.from_numpy(W32))
 
 
-def test_prune_calls_on_two_streams_share_the_exchange_area(z, oracle):
-    """Asynchronous calls on two streams use the same per-device exchange area one after the other: every
-    result equals that of the same call made alone."""
+@pytest.mark.parametrize("where", ["workspace", "separate"])
+def test_prune_calls_on_two_streams_ordered_by_events(z, oracle, exchange_area, where):
+    """One rule per device: two single-column loops are never in flight together.  Asynchronous calls on two
+    streams, each ordered behind the previous one with an event (and, in the second variant, all sharing one
+    separate exchange area), give the results of the same calls made alone."""
     specs = [workloads.small(40, 288, 1, 1200, x_kind="gelu", seed=51),
              workloads.small(24, 416, 1, 1700, x_kind="normal", seed=52)]
     inputs = [_oracle_inputs(oracle, sp) for sp in specs]
+    xa = exchange_area if where == "separate" else None
     alone = []
     for sp, (X, W32, H, Hi32) in zip(specs, inputs):
         Wd, Hd = dev(W32), dev(Hi32)
@@ -384,18 +432,80 @@ def test_prune_calls_on_two_streams_share_the_exchange_area(z, oracle):
         alone.append((o.cpu(), e.cpu()))
     torch.cuda.synchronize()
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
-    results = []
+    results, last = [], None
     for rep in range(3):
         for k in (0, 1):
             X, W32, H, Hi32 = inputs[k]
             with torch.cuda.stream(streams[k]):
                 Wd, Hd = dev(W32), dev(Hi32)
-                o, e, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, specs[k].d_col, stream=streams[k], check=False)
+                if last is not None:
+                    streams[k].wait_event(last)
+                o, e, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, specs[k].d_col, stream=streams[k], check=False, exchange=xa)
+                last = torch.cuda.Event()
+                last.record(streams[k])
                 results.append((k, o, e, Wd, Hd))
     torch.cuda.synchronize()
     for k, o, e, Wd, Hd in results:
         assert torch.equal(o.cpu(), alone[k][0]) and torch.equal(e.cpu(), alone[k][1])
         assert float(Wd.abs().max()) == 0.0
+
+
+def test_bounded_wait_self_test_gives_up_and_leaves_the_layer_alone(z, oracle):
+    """Host-forced give-up: one workgroup is held back, the others wait for its candidate, reach the 4 s limit, raise
+    the status word, and every workgroup leaves.  The call reports a device error and W, Hinv are untouched; the
+    same buffers then go through a regular call."""
+    spec = workloads.small(32, 512, 1, 2000, x_kind="gelu", seed=61)
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    Wd, Hd = dev(W32), dev(Hi32)
+    rc, info = z.ziplm_selftest_bounded_wait(Wd, Hd)
+    assert (rc, info) == (z.ERR_DEVICE, -1)
+    assert torch.equal(Wd.cpu(), torch.from_numpy(W32)) and torch.equal(Hd.cpu(), torch.from_numpy(Hi32))
+    order, err, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, 512)
+    compare_run(oracle, W32, Hi32, 1, 512, order.cpu().numpy(), err.cpu().numpy())
+
+
+@pytest.mark.parametrize("g,path", [(1, "lazy"), (1, "eager"), (4, "groups")])
+def test_more_removals_than_live_structures_is_an_argument_error(z, oracle, g, path):
+    """n_remove may not exceed the structures alive under alive_in; only the device sees the mask, so the request
+    runs until nothing is left and comes back as ZIPLM_ERR_INVALID_ARG with info = -(2 + steps done), not as a
+    positive-definiteness failure."""
+    spec = workloads.small(16, 64, g, 400, x_kind="gelu", seed=71)
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    G = 64 // g
+    alive = np.ones(G, np.uint8)
+    alive[::2] = 0                                        # half of the structures came in removed
+    Wd, Hd = dev(W32), dev(Hi32)
+    call = z.ziplm_structured_obs_prune_eager if path == "eager" else z.ziplm_structured_obs_prune
+    args = (Wd, Hd, G // 2 + 3) if path == "eager" else (Wd, Hd, g, G // 2 + 3)
+    with pytest.raises(z.ZiplmError) as ei:
+        call(*args, alive=torch.from_numpy(alive).cuda())
+    assert ei.value.status == z.ERR_INVALID_ARG and ei.value.info == -(2 + G // 2)
+
+
+def test_failed_factorisation_is_marked_on_the_device(z):
+    """Without info_host nobody waits for the factorisation's verdict: an indefinite H then leaves NaN on the diagonal
+    of Hinv, and the greedy loop refuses it at its first step instead of pruning with garbage."""
+    d = 96
+    rng = np.random.default_rng(5)
+    A = rng.standard_normal((d, d)).astype(np.float32)
+    H = (A + A.T)                                         # indefinite
+    Hd = dev(H)
+    out, lam = z.ziplm_hinv(Hd, 0.01, check=False)
+    torch.cuda.synchronize()
+    assert lam is None and bool(torch.isnan(torch.diagonal(out)).all())
+    W = dev(rng.standard_normal((8, d)).astype(np.float32))
+    with pytest.raises(z.ZiplmError) as ei:
+        z.ziplm_structured_obs_prune(W, out, 1, d)
+    assert ei.value.status == z.ERR_NOT_PD and ei.value.info == 1
+
+
+def test_prior_with_an_unusable_total_is_nan(z):
+    err = torch.tensor([1.0, 2.0, 3.0], dtype=torch.float64, device="cuda")
+    for total in (0.0, -1.0, float("inf"), float("nan")):
+        p = z.ziplm_prior(err, torch.tensor([total], dtype=torch.float64, device="cuda"))
+        assert bool(torch.isnan(p).all())
+    p = z.ziplm_prior(err, torch.tensor([6.0], dtype=torch.float64, device="cuda"))
+    assert torch.allclose(p.cpu(), torch.tensor([1 / 6, 3 / 6, 1.0], dtype=torch.float64).sqrt())
 
 
 def test_hessian_and_inverse_on_several_streams_equal_the_sequential_results(z):
@@ -580,26 +690,3 @@ def test_prune_batch_single_columns_matches_oracle(z, oracle, m, d, n, layers, s
     for l in range(layers):
         if l != bad:
             assert torch.equal(W2[l], Wb[l]) and torch.equal(H2[l], Hb[l])      # the good layers are complete
-
-
-def test_prune_batch_single_columns_on_the_eager_fallback(z, oracle, monkeypatch):
-    """With the eager single-column kernel forced (ZIPLM_PRUNE_EAGER=1) the batched call runs the layers one
-    after the other through that kernel: bit-identical to single-layer calls, and against the oracle."""
-    monkeypatch.setenv("ZIPLM_PRUNE_EAGER", "1")
-    m, d, n, layers = 24, 160, 700, 3
-    Ws, His = [], []
-    for l in range(layers):
-        X, W32, H, Hi32 = _oracle_inputs(oracle, workloads.small(m, d, 1, n, x_kind="gelu", seed=81 + l))
-        Ws.append(W32)
-        His.append(Hi32)
-    Wb, Hb = dev(np.stack(Ws)), dev(np.stack(His))
-    snaps = [0, d // 2, d]
-    order_b, err_b, snap_b = z.ziplm_structured_obs_prune_batch(Wb, Hb, 1, d, snapshot_steps=snaps)
-    torch.cuda.synchronize()
-    for l in range(layers):
-        Wl, Hl = dev(Ws[l]), dev(His[l])
-        o, e, sn = z.ziplm_structured_obs_prune(Wl, Hl, 1, d, snapshot_steps=snaps)
-        torch.cuda.synchronize()
-        assert torch.equal(o, order_b[l]) and torch.equal(e, err_b[l]) and torch.equal(sn, snap_b[l])
-        ref = compare_run(oracle, Ws[l], His[l], 1, d, order_b[l].cpu().numpy(), err_b[l].cpu().numpy(), snap_steps=snaps)
-        assert_columns_close(snap_b[l, 1].cpu().numpy(), ref["W_snap"][1], "snap_b")
