@@ -247,6 +247,21 @@ int ziplm_module_error(const float *W, const float *H, int d_row, int d_col, flo
 size_t ziplm_module_error_workspace_bytes(int d_row, int d_col);
 
 /*
+ * ziplm_module_error for callers that cannot allocate or carry a workspace: code running under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same result bit for bit;
+ * the per-tile partial sums go to a scratch array built into the library's device image (32 KiB, one copy
+ * on every GPU the library runs on, held until the process ends) instead of a workspace.  The call
+ * allocates and frees nothing.
+ * Limit: ceil(d_row / 128) * ceil(d_col / 128) <= ziplm_module_error_static_max_tiles() (4096); larger
+ * layers get ZIPLM_ERR_UNSUPPORTED and must use ziplm_module_error.
+ * All calls on one GPU share that array: calls whose work may overlap in time (different streams without
+ * an ordering between them) race on it and must be ordered by the caller.
+ */
+int ziplm_module_error_static(const float *W, const float *H, int d_row, int d_col, float lambda,
+                              double *err_out, void *stream);
+int ziplm_module_error_static_max_tiles(void);
+
+/*
  * Prior of the sparsity search (Section 3.2, "Structured SPDY search"):
  * p_s = ||W_s X - W X|| / ||W X|| for the layer after each removal of a greedy run,
  *

@@ -32,6 +32,7 @@ EXPORTS = (
     "ziplm_prune_exchange_bytes", "ziplm_exchange_alloc",
     "ziplm_structured_obs_prune_eager", "ziplm_prune_eager_workspace_bytes",
     "ziplm_selftest_bounded_wait",
+    "ziplm_module_error_static", "ziplm_module_error_static_max_tiles",
 )
 
 _lib = None
@@ -94,6 +95,10 @@ def lib():
     L.ziplm_module_error.argtypes = [vp, vp, i32, i32, f32, vp, vp, sz, vp]
     L.ziplm_module_error_workspace_bytes.restype = sz
     L.ziplm_module_error_workspace_bytes.argtypes = [i32, i32]
+    L.ziplm_module_error_static.restype = i32
+    L.ziplm_module_error_static.argtypes = [vp, vp, i32, i32, f32, vp, vp]
+    L.ziplm_module_error_static_max_tiles.restype = i32
+    L.ziplm_module_error_static_max_tiles.argtypes = []
     L.ziplm_prior.restype = i32
     L.ziplm_prior.argtypes = [vp, i32, vp, vp, vp]
     _lib = L
@@ -332,6 +337,20 @@ def ziplm_module_error(W, H, lam=0.0, out=None, workspace=None, stream=None):
     ws = workspace if workspace is not None else _workspace(need, W.device)
     rc = lib().ziplm_module_error(W.data_ptr(), H.data_ptr(), m, d, float(lam), out.data_ptr(), ws.data_ptr(),
                                   ws.numel(), _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return out
+
+
+def ziplm_module_error_static(W, H, lam=0.0, out=None, stream=None):
+    """ziplm_module_error without a workspace: the partial sums go to the library's built-in scratch array."""
+    _check(W, torch.float32, "W")
+    _check(H, torch.float32, "H")
+    m, d = W.shape
+    assert H.shape == (d, d)
+    out = torch.empty(1, dtype=torch.float64, device=W.device) if out is None else out
+    _check(out, torch.float64, "out")
+    rc = lib().ziplm_module_error_static(W.data_ptr(), H.data_ptr(), m, d, float(lam), out.data_ptr(), _stream(stream))
     if rc != OK:
         raise ZiplmError(rc)
     return out
