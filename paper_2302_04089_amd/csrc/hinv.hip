@@ -22,6 +22,8 @@
 
 namespace ziplm {
 
+int device_cu_count();
+
 constexpr int NB = 64;  // Cholesky panel width
 
 // lambda = damp_rel * mean(diag H), accumulated in fp64 by one workgroup.
@@ -392,6 +394,9 @@ struct HinvLayout {
     float *A, *T, *S, *dinv, *ldiag, *loff, *partial;
     double *lambda;
     int *info;
+    // Newton step: partial sums of the tiles two workgroups share
+    int resid_workgroups;
+    double *resid_scratch;
     size_t bytes;
 };
 
@@ -410,6 +415,9 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.loff = c.take<float>((size_t)(l.dp / PW) * NB * NB);    // the block below the first one in every 128 x 128
     l.lambda = c.take<double>(1);
     l.info = c.take<int>(1);
+    l.resid_workgroups = dgemm::residual_workgroups(l.dp, 2 * device_cu_count());     // two workgroups fit a compute unit
+    if (l.resid_workgroups > dgemm::RESIDUAL_MAX_WORKGROUPS) l.resid_workgroups = dgemm::RESIDUAL_MAX_WORKGROUPS;
+    l.resid_scratch = c.take<double>(dgemm::residual_scratch_doubles(l.resid_workgroups));
     l.bytes = c.off;
     return l;
 }
@@ -529,7 +537,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         r.R = l.T; r.ldr = dp;
         r.lambda = l.lambda;
         r.n = dp;
-        ZIPLM_HIP_TRY(dgemm::launch_residual(r, st));
+        r.scratch = l.resid_scratch;
+        ZIPLM_HIP_TRY(dgemm::launch_residual(r, l.resid_workgroups, st));
     }
     {
         Args c = {};
@@ -540,7 +549,15 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         c.M = d_col; c.N = d_col; c.K = dp;
         c.alpha = 1.f; c.beta = 0.f;
         c.flags = F_TRI_GRID | F_MIRROR;
-        ZIPLM_HIP_TRY((launch<K_CONTIG, R_CONTIG, true, false>(c, 1, st)));
+        // 300 tiles on 512 slots at 3072 columns: the k range of every tile is shared so that the slots fill up
+        // (accumulators in S and the merges' buffer behind it, both free again)
+        const int tm = (d_col + BM - 1) / BM, tiles = tm * (tm + 1) / 2;
+        const size_t sets = ((char *)l.partial - (char *)l.S) / (sizeof(float) * 64 * THREADS) + MERGE_PARTIAL_SETS;
+        int nsplit = (int)(sets / (size_t)tiles);
+        if (nsplit > 3) nsplit = 3;
+        if (dp < 1024 || tiles >= 2 * 2 * device_cu_count()) nsplit = 1;
+        c.partial = l.S;
+        ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(c, 1, nsplit < 1 ? 1 : nsplit, st)));
     }
     hipLaunchKernelGGL(poison_on_failure_kernel, dim3((d_col + 255) / 256 < 64 ? (d_col + 255) / 256 : 64), dim3(256), 0, st, Hinv, d_col, l.info);
     ZIPLM_HIP_TRY(hipGetLastError());

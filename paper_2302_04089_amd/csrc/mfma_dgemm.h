@@ -31,7 +31,18 @@ struct ResidualArgs {
     const double *lambda;  // device scalar
     int n;
     int64_t lda, ldx, ldr;
+    // Work sharing.  The (tile, k slice) pairs are numbered tile by tile and dealt out in equal contiguous
+    // ranges to the workgroups of the launch, as many workgroups as the device runs at once, so that nobody
+    // waits for a second round of tiles (576 tiles on 512 slots would take two rounds for 1.125 rounds of work).
+    // A range that starts or ends inside a tile leaves its part of that tile as partial sums in `scratch` (two sets
+    // of accumulators per workgroup: [2 w] for the tail of the tile its range starts in, [2 w + 1] for the head of
+    // the tile it ends in).  The launch uses at most one workgroup per tile, so a tile is shared by two workgroups
+    // at most: a second launch adds head and tail, always in that order, and writes those tiles.
+    double *scratch;       // [2 * workgroups][64 accumulators][256 threads]
 };
+
+// The range of units of workgroup w out of G.
+__device__ __forceinline__ long long residual_range_begin(long long total, int w, int G) { return total * w / G; }
 
 __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs g) {
     using gemm::floatx4;
@@ -40,85 +51,164 @@ __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs
     const int wm = wave >> 1, wn = wave & 1;
     const int cl16 = lane & 15, q4 = lane >> 4;
     const int tiles_n = g.n / gemm::BN;
-    // workgroups go to the eight XCDs round-robin; each XCD takes a contiguous eighth of the row-major tile list,
-    // so the tiles in flight on one L2 share their row slabs of A
-    const int nt = gridDim.x, x = blockIdx.x % 8;
-    const int tile = x * (nt / 8) + min(x, nt % 8) + blockIdx.x / 8;
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
-
-    doublex4 acc[4][4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = doublex4{0.0, 0.0, 0.0, 0.0};
-
-    gemm::Slab<gemm::K_CONTIG, true, false> ra, rb;
     const int nslices = g.n / gemm::BK;
-    ra.load_inside(g.A, g.lda, tm * gemm::BM, 0, tid);
-    rb.load_inside(g.X, g.ldx, tn * gemm::BN, 0, tid);
-    ra.store(lds[0][0], tid);
-    rb.store(lds[0][1], tid);
-    __syncthreads();
-    int cur = 0;
-    for (int s = 0; s < nslices; ++s) {
-        const bool more = s + 1 < nslices;
-        if (more) {
-            ra.load_inside(g.A, g.lda, tm * gemm::BM, (int64_t)(s + 1) * gemm::BK, tid);
-            rb.load_inside(g.X, g.ldx, tn * gemm::BN, (int64_t)(s + 1) * gemm::BK, tid);
-        }
-        const float *sA = lds[cur][0] + (wm * 64 + cl16) * gemm::PITCH_K + 4 * q4;
-        const float *sB = lds[cur][1] + (wn * 64 + cl16) * gemm::PITCH_K + 4 * q4;
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            floatx4 a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const floatx4 *>(sA + i * 16 * gemm::PITCH_K + 16 * h);
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const floatx4 *>(sB + j * 16 * gemm::PITCH_K + 16 * h);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                double ad[4], bd[4];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { ad[i] = (double)a[i][e]; bd[i] = (double)b[i][e]; }
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(ad[i], bd[j], acc[i][j], 0, 0, 0);
-            }
-        }
-        if (more) {
-            ra.store(lds[cur ^ 1][0], tid);
-            rb.store(lds[cur ^ 1][1], tid);
-        }
-        __syncthreads();
-        cur ^= 1;
-    }
-
+    // workgroups go to the eight XCDs round-robin; each XCD takes a contiguous eighth of the ranges, so the tiles in
+    // flight on one L2 share their row slabs of A
+    const int G = gridDim.x, x = blockIdx.x % 8;
+    const int w = x * (G / 8) + min(x, G % 8) + blockIdx.x / 8;
+    const long long total = (long long)tiles_n * tiles_n * nslices;
+    const long long u0 = residual_range_begin(total, w, G), u1 = residual_range_begin(total, w + 1, G);
     const double lam = *g.lambda;
+
+    for (long long u = u0; u < u1;) {
+        const int tile = (int)(u / nslices), k0 = (int)(u % nslices);
+        const int k1 = (int)min((long long)nslices, k0 + (u1 - u));
+        const int tm = tile / tiles_n, tn = tile % tiles_n;
+        u += k1 - k0;
+
+        doublex4 acc[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = doublex4{0.0, 0.0, 0.0, 0.0};
+
+        gemm::Slab<gemm::K_CONTIG, true, false> ra, rb;
+        __syncthreads();                 // the previous segment's last slice has been read by every wavefront
+        ra.load_inside(g.A, g.lda, tm * gemm::BM, (int64_t)k0 * gemm::BK, tid);
+        rb.load_inside(g.X, g.ldx, tn * gemm::BN, (int64_t)k0 * gemm::BK, tid);
+        ra.store(lds[0][0], tid);
+        rb.store(lds[0][1], tid);
+        __syncthreads();
+        int cur = 0;
+        for (int s = k0; s < k1; ++s) {
+            const bool more = s + 1 < k1;
+            if (more) {
+                ra.load_inside(g.A, g.lda, tm * gemm::BM, (int64_t)(s + 1) * gemm::BK, tid);
+                rb.load_inside(g.X, g.ldx, tn * gemm::BN, (int64_t)(s + 1) * gemm::BK, tid);
+            }
+            const float *sA = lds[cur][0] + (wm * 64 + cl16) * gemm::PITCH_K + 4 * q4;
+            const float *sB = lds[cur][1] + (wn * 64 + cl16) * gemm::PITCH_K + 4 * q4;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                floatx4 a[4], b[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) a[i] = *reinterpret_cast<const floatx4 *>(sA + i * 16 * gemm::PITCH_K + 16 * h);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) b[j] = *reinterpret_cast<const floatx4 *>(sB + j * 16 * gemm::PITCH_K + 16 * h);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    double ad[4], bd[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) { ad[i] = (double)a[i][e]; bd[i] = (double)b[i][e]; }
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(ad[i], bd[j], acc[i][j], 0, 0, 0);
+                }
+            }
+            if (more) {
+                ra.store(lds[cur ^ 1][0], tid);
+                rb.store(lds[cur ^ 1][1], tid);
+            }
+            __syncthreads();
+            cur ^= 1;
+        }
+
+        if (k0 > 0 || k1 < nslices) {
+            // part of a tile: leave the partial sums for the second launch.  One running pointer, advanced behind an
+            // opaque step: sixty-four addresses computed ahead of the stores (their offsets exceed what an instruction
+            // can encode) would need more registers than are left.
+            double *dst = g.scratch + ((size_t)2 * w + (k0 > 0 ? 0 : 1)) * (64 * gemm::THREADS) + tid;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        *dst = acc[i][j][v];
+                        dst += gemm::THREADS;
+                        asm volatile("" : "+v"(dst));
+                    }
+            continue;
+        }
+
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int col = tn * gemm::BN + wn * 64 + j * 16 + cl16;
+                float xv[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
+                    xv[v] = g.X[(int64_t)row * g.ldx + col];
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
+                    const double r = ((row == col) ? 1.0 : 0.0) - acc[i][j][v] - lam * (double)xv[v];
+                    g.R[(int64_t)row * g.ldr + col] = (float)r;
+                }
+            }
+    }
+}
+
+// Second launch: workgroup w < G - 1 looks at the boundary between ranges w and w + 1; if it falls inside a tile, the
+// tile is the sum of the head left by w and the tail left by w + 1.  Same thread <-> element mapping as above.
+__global__ __launch_bounds__(gemm::THREADS) void residual_fixup_kernel(ResidualArgs g, int G) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int cl16 = lane & 15, q4 = lane >> 4;
+    const int tiles_n = g.n / gemm::BN;
+    const int nslices = g.n / gemm::BK;
+    const int w = blockIdx.x;
+    const long long total = (long long)tiles_n * tiles_n * nslices;
+    const long long u1 = residual_range_begin(total, w + 1, G);
+    if (u1 % nslices == 0) return;
+    const int tile = (int)(u1 / nslices);
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const double lam = *g.lambda;
+    const double *head = g.scratch + ((size_t)2 * w + 1) * (64 * gemm::THREADS) + tid;
+    const double *tail = g.scratch + ((size_t)2 * (w + 1)) * (64 * gemm::THREADS) + tid;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int col = tn * gemm::BN + wn * 64 + j * 16 + cl16;
+            double sum[4];
             float xv[4];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
+                const size_t e = (size_t)((i * 4 + j) * 4 + v) * gemm::THREADS;
+                sum[v] = head[e] + tail[e];
                 xv[v] = g.X[(int64_t)row * g.ldx + col];
             }
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
-                const double r = ((row == col) ? 1.0 : 0.0) - acc[i][j][v] - lam * (double)xv[v];
+                const double r = ((row == col) ? 1.0 : 0.0) - sum[v] - lam * (double)xv[v];
                 g.R[(int64_t)row * g.ldr + col] = (float)r;
             }
         }
 }
 
-inline hipError_t launch_residual(const ResidualArgs &g, hipStream_t stream) {
+// Workgroups of the first launch: at most one per tile (a tile is then shared by two workgroups at most), at most
+// `slots` (what the device runs at once).
+inline int residual_workgroups(int n, int slots) {
+    const int tiles = (n / gemm::BM) * (n / gemm::BN);
+    return tiles < slots ? tiles : slots;
+}
+constexpr int RESIDUAL_MAX_WORKGROUPS = 1024;
+inline size_t residual_scratch_doubles(int workgroups) { return (size_t)2 * workgroups * 64 * gemm::THREADS; }
+
+inline hipError_t launch_residual(const ResidualArgs &g, int workgroups, hipStream_t stream) {
+    hipLaunchKernelGGL(residual_kernel, dim3(workgroups), dim3(gemm::THREADS), 0, stream, g);
+    // whole tiles per workgroup: every range ends on a tile boundary and nothing is left to add
     const int tiles = (g.n / gemm::BM) * (g.n / gemm::BN);
-    hipLaunchKernelGGL(residual_kernel, dim3(tiles), dim3(gemm::THREADS), 0, stream, g);
+    if (tiles % workgroups != 0)
+        hipLaunchKernelGGL(residual_fixup_kernel, dim3(workgroups - 1), dim3(gemm::THREADS), 0, stream, g, workgroups);
     return hipGetLastError();
 }
 

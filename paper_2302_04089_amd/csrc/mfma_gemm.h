@@ -75,7 +75,7 @@ struct Args {
     float dot_lambda;
     // optional addend: with D set the result is alpha * acc + D (beta and the old C are ignored); with F_MIRROR the
     // transposed element receives the same value (tiles on the diagonal mirror their lower half), so C is exactly
-    // symmetric.  Not combined with split-K.
+    // symmetric.  Not batched.
     const float *D;
     int64_t ldd;
 };
@@ -456,7 +456,8 @@ __device__ __forceinline__ void reduce_epilogue(const float (&sum)[16], const Ar
     floatx16 acc[2][2];
 #pragma unroll
     for (int e = 0; e < 16; ++e) acc[e >> 3][(e >> 2) & 1][4 * Q + (e & 3)] = sum[e];
-    epilogue<4 * Q, 4 * Q + 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane, g.D, g.ldd);
+    epilogue<4 * Q, 4 * Q + 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane, g.D, g.ldd,
+                               (g.flags & F_MIRROR) && tm == tn);
 }
 
 // Second pass of a split-K product: sums the raw accumulators of all splits in split order and

@@ -65,6 +65,13 @@ constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
 constexpr int MAX_CPB = 250;             // the local column index travels in 8 bits
 constexpr int MAX_D = 65535;             // the global column index travels in 16 bits of the comparison key
+// 64-bit words between the candidate slots of two workgroups: every slot has a 128-byte line of its own.  Packed
+// eight to a line, the sixteen writers of a line and the 256 x 8 readers polling it delay one another (an
+// all-to-all exchange of 256 workgroups: 2.5 us per round packed, 2.1 us with a line per slot).
+#ifndef ZIPLM_SLOT_STRIDE
+#define ZIPLM_SLOT_STRIDE 16
+#endif
+constexpr int SLOT_STRIDE = ZIPLM_SLOT_STRIDE;
 
 struct State {
     // caller's buffers
@@ -82,7 +89,7 @@ struct State {
     double *P;                    // [nb][d][cp]  panels of the stored (stale between flushes) inverse Hessian
     float *Wt;                    // [d][m]       transposed W when it does not fit LDS, else unused
     double *U;                    // [2][BMAX][d] pending pivot rows of the current / previous block of steps
-    unsigned long long *slots;    // [2][nb]
+    unsigned long long *slots;    // [2][nb][SLOT_STRIDE], word 0 of each
     unsigned long long *pay;      // [2][nb][pay_words]
     unsigned long long *bar;      // [nb] flush-barrier epochs
     int *status;
@@ -483,7 +490,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     int error_step = 0;
     unsigned tag4 = 0;
     // background flush of the previous block of pending rows
-    const bool bg_enabled = (cp == RG) && (nb <= 64 * NPOLL);
+    const bool bg_enabled = ZIPLM_LAZY_BACKGROUND_FLUSH && (cp == RG) && (nb <= 64 * NPOLL);
     const int ntiles = (d + 15) / 16;
     const int q4 = lane >> 4, cl16 = lane & 15;
     bool bg_active = false;
@@ -555,7 +562,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
         const double cand_score_trunc = __longlong_as_double((long long)(key & ~0xfffull));
         if (tid == 0) {
             if (!slot_early)
-                __hip_atomic_store(S.slots + (size_t)par * nb + b, key | tag4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(S.slots + ((size_t)par * nb + b) * SLOT_STRIDE, key | tag4, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             ZIPLM_LAZY_TIMING_LOCAL_DONE;
         }
         // The payload travels ahead of the exchange only from workgroups that are likely to win (score
@@ -595,7 +602,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             bool fail = false, err = false;
             for (int sb = tid; sb < nb; sb += LT) {
                 unsigned long long kv;
-                if (!slot_wait(S.slots + (size_t)par * nb + sb, tag4, sb, cpb, kv, err, S.status)) { fail = true; break; }
+                if (!slot_wait(S.slots + ((size_t)par * nb + sb) * SLOT_STRIDE, tag4, sb, cpb, kv, err, S.status)) { fail = true; break; }
                 ZIPLM_LAZY_TIMING_OWN_SLOT;
                 mykey = umin64(mykey, kv);
             }
@@ -817,7 +824,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 score[jl] = sc;
                 if (reported == participants - 1 && more_steps) {
                     const unsigned tag4_next = (tag4 == 15u) ? 1u : tag4 + 1u;
-                    __hip_atomic_store(S.slots + (size_t)((t + 1) & 1) * nb + b, knext | tag4_next, __ATOMIC_RELAXED,
+                    __hip_atomic_store(S.slots + ((size_t)((t + 1) & 1) * nb + b) * SLOT_STRIDE, knext | tag4_next, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 }
                 __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -945,7 +952,7 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     s.Wt = c.take<float>(p.w_in_lds ? 1 : (size_t)d_col * padded_rows(d_row));
     s.U = c.take<double>((size_t)2 * BMAX * d_col);
     // zero-initialised region: slots, payload, barrier epochs, status
-    s.slots = c.take<unsigned long long>((size_t)2 * p.nb);
+    s.slots = c.take<unsigned long long>((size_t)2 * p.nb * SLOT_STRIDE);
     s.pay = c.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
     s.bar = c.take<unsigned long long>((size_t)p.nb);
     s.status = c.take<int>(1);
@@ -961,7 +968,7 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
 // makes a store visible to the other XCDs' loads sooner than the write path of the L2: 3% of the loop).
 // ------------------------------------------------------------------------------------------------
 static size_t exchange_bytes_needed(const Plan &p) {
-    return align_up(sizeof(unsigned long long) * (size_t)2 * p.nb) + align_up(sizeof(unsigned long long) * (size_t)2 * p.nb * p.pay_words);
+    return align_up(sizeof(unsigned long long) * (size_t)2 * p.nb * SLOT_STRIDE) + align_up(sizeof(unsigned long long) * (size_t)2 * p.nb * p.pay_words);
 }
 
 }  // namespace lazy
@@ -1033,7 +1040,7 @@ int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64
     if (xa) {
         Carver cx(exchange);
         for (int q = 0; q < pack; ++q) {
-            lay[q].st.slots = cx.take<unsigned long long>((size_t)2 * p.nb);
+            lay[q].st.slots = cx.take<unsigned long long>((size_t)2 * p.nb * SLOT_STRIDE);
             lay[q].st.pay = cx.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
         }
         if (zero_fill(exchange, cx.off, st) != ZIPLM_OK) return ZIPLM_ERR_DEVICE;
