@@ -9,11 +9,17 @@ Prints ONE JSON line.  `value` is seconds per layer for the whole path (lower is
 --config 5 it is seconds for the 24 problems of the 12-layer sweep (Hessians and inverses of
 the layers on a few streams, then the loops of each kind in one batched call).
 `roofline` describes the greedy-loop kernel against HBM bandwidth with the algorithmic byte
-count  sum over steps of (8 r^2 + 8 d_row r + 4 r), r = live columns;  `roofline_hessian` the
-Hessian kernel against the fp32 matrix-core peak with d (d + 1) n_tok useful flops.
-`hbm_triad_gbs` is what a plain triad over 1 GiB arrays reaches on the same device (the achievable
-HBM rate; `frac_of_triad` prices the loop against it).  `cpu_baseline` is the fp64 CPU oracle timed
-on this host on the same layer.
+count  sum over steps of (8 r^2 + 8 d_row r + 4 r), r = live columns (`achieved`, `frac`: the
+model rate the target is stated in).  The kernel defers the eliminations and does not move those
+bytes, so the same object also carries what bounds it in fact: `traffic` (HBM bytes per launch from
+the rocprofv3 counter runs recorded under profiles/), `physical_gbs` / `physical_frac` (those bytes
+over the measured time: the rate at the memory pins) and `handoff_us` / `latency_floor_frac`
+(the one-way hand-off time between two workgroups measured on this device just before the timed
+steps, times the number of removals, over the loop time: the serial chain of Algorithm 1 cannot run
+faster than one hand-off per removal).  `roofline_hessian` prices the Hessian kernel against the
+fp32 matrix-core peak with d (d + 1) n_tok useful flops.  `hbm_triad_gbs` is what a plain triad over
+1 GiB arrays reaches on the same device (the achievable HBM rate; `frac_of_triad` prices the loop
+against it).  `cpu_baseline` is the fp64 CPU oracle timed on this host on the same layer.
 """
 import argparse
 import json
@@ -25,12 +31,21 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the greedy-loop kernel from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised
-# in profiles/greedy_loop_and_hessian_config3_hbm_counters.md (KiB, already scaled by the copy-kernel factors);
-# --traffic-kib overrides them after a new counter run.
-MEASURED_TRAFFIC_KIB = {3: (3158435.0, 3120838.0)}
 HBM_PEAK_GBS = 8000.0
 MFMA_F32_PEAK_TFLOPS = 157.3
+
+
+def recorded_traffic_bytes(config):
+    """HBM bytes per launch of the greedy-loop kernel as the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs measured
+    them (scaled by the same counters' reading for a kernel of known traffic): the line
+    `traffic_bytes_per_launch: N` of profiles/greedy_loop_config<N>_hbm_counters.md, or None without that record."""
+    import re
+    path = os.path.join(ROOT, "profiles", "greedy_loop_config%d_hbm_counters.md" % config)
+    try:
+        m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+    except OSError:
+        return None
+    return float(m.group(1)) if m else None
 
 
 def loop_algorithmic_bytes(d_row, d_col, group_size, n_remove):
@@ -54,11 +69,12 @@ def main():
                     help="configuration 5 only: streams the Hessians and inverses of the layers are spread over")
     ap.add_argument("--config", type=int, default=3, help="workload configuration 1..5 (5: the 24-problem sweep)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--calibration-copy-mib", type=int, default=0,
-                    help="also run one plain device-to-device copy of this many MiB before the timed steps, so a "
-                         "rocprofv3 --pmc run of this command holds a kernel of known HBM traffic to scale counters by")
-    ap.add_argument("--traffic-kib", type=float, nargs=2, default=None, metavar=("FETCH", "WRITE"),
-                    help="per-launch HBM KiB of the loop kernel from rocprofv3 --pmc runs (for the record)")
+    ap.add_argument("--x-layout", choices=("feature", "token"), default="feature",
+                    help="layout of the calibration inputs handed to the Hessian call: feature-major X[d_col][n_tok] "
+                         "(the configurations' layout) or token-major X[n_tok][d_col] (how activations are captured)")
+    ap.add_argument("--loop-kernel", choices=("deferred", "eager"), default="deferred",
+                    help="single-column loops through ziplm_structured_obs_prune (deferred eliminations) or through "
+                         "ziplm_structured_obs_prune_eager (the whole state read and written every step)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (layers are independent and would be sharded one "
@@ -87,6 +103,8 @@ def main():
         q = Problem()
         q.spec = spec
         q.X = torch.from_numpy(workloads.make_X(spec)).cuda()
+        if args.x_layout == "token":
+            q.X = q.X.t().contiguous()
         q.W0 = torch.from_numpy(workloads.make_W(spec)).cuda()
         d, m, g = spec.d_col, spec.d_row, spec.group_size
         q.W = torch.empty_like(q.W0)
@@ -94,13 +112,19 @@ def main():
         q.Hi = torch.empty_like(q.H)
         q.ws_h = torch.empty(max(ziplm.ziplm_hessian_workspace_bytes(d, spec.n_tok), 256), dtype=torch.uint8, device="cuda")
         q.ws_i = torch.empty(ziplm.ziplm_hinv_workspace_bytes(d), dtype=torch.uint8, device="cuda")
-        q.ws_p = torch.empty(ziplm.ziplm_prune_workspace_bytes(m, d, g, 0), dtype=torch.uint8, device="cuda")
+        eager = args.loop_kernel == "eager" and g == 1
+        q.ws_p = torch.empty(ziplm.ziplm_prune_eager_workspace_bytes(m, d, 0) if eager else
+                             ziplm.ziplm_prune_workspace_bytes(m, d, g, 0), dtype=torch.uint8, device="cuda")
         problems.append(q)
     gen_s = time.time() - t0
     # one exchange area (uncached device memory, kept for the life of the process) for every single-column loop
     xbytes = max([ziplm.ziplm_prune_exchange_bytes(12 if args.config == 5 else 1, q.spec.d_row, q.spec.d_col, q.spec.group_size)
                   for q in problems])
     exchange = ziplm.ziplm_exchange_alloc(xbytes) if xbytes > 0 else None
+    x_layout = ziplm.X_TOKEN_MAJOR if args.x_layout == "token" else ziplm.X_FEATURE_MAJOR
+    if args.loop_kernel == "eager" and args.config == 5:
+        print("bench.py: --loop-kernel eager times one layer; use it with --config 1, 3 or 4", file=sys.stderr)
+        sys.exit(2)
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
@@ -149,12 +173,16 @@ def main():
                 q.W.copy_(q.W0)
                 q.H.zero_()
                 e[0].record()
-                ziplm.ziplm_hessian_accumulate(q.H, q.X, 2.0, workspace=q.ws_h)
+                ziplm.ziplm_hessian_accumulate(q.H, q.X, 2.0, layout=x_layout, workspace=q.ws_h)
                 e[1].record()
                 ziplm.ziplm_hinv(q.H, spec.damp_rel, out=q.Hi, workspace=q.ws_i, check=False)
                 e[2].record()
             if id(q) in stacked:
                 e[3] = e[2]                      # pruned below, all problems of one shape together
+            elif args.loop_kernel == "eager" and spec.group_size == 1:
+                q.order, q.err, _ = ziplm.ziplm_structured_obs_prune_eager(q.W, q.Hi, spec.n_groups, workspace=q.ws_p,
+                                                                           check=False)
+                e[3].record()
             else:
                 q.order, q.err, _ = ziplm.ziplm_structured_obs_prune(q.W, q.Hi, spec.group_size, spec.n_groups,
                                                                      workspace=q.ws_p, check=False,
@@ -176,14 +204,11 @@ def main():
         if record:
             result["events"].append(marks)
 
-    if args.calibration_copy_mib > 0:
-        n = args.calibration_copy_mib * (1 << 20) // 4
-        src = torch.ones(n, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)          # reads n*4 bytes, writes n*4 bytes
-        torch.cuda.synchronize()
-        del src, dst
+    # one-way hand-off between two workgroups on different XCDs through the memory the loop exchanges its
+    # candidates in, measured on this device before anything else is running
+    handoff_us = None
+    if exchange is not None:
+        handoff_us = min(ziplm.ziplm_selftest_handoff_latency(2000, 1, exchange=exchange) for _ in range(3))
     for _ in range(args.warmup):
         one_step(False)
     torch.cuda.synchronize()
@@ -242,10 +267,8 @@ def main():
     syrk_flops = sum(float(q.spec.d_col) * (q.spec.d_col + 1) * q.spec.n_tok for q in problems)
     hess_tflops = syrk_flops / (mean["hessian"] * 1e-3) / 1e12
 
-    traffic = None
-    kib = args.traffic_kib if args.traffic_kib is not None else MEASURED_TRAFFIC_KIB.get(args.config)
-    if kib is not None:
-        traffic = (kib[0] + kib[1]) * 1024.0
+    traffic = recorded_traffic_bytes(args.config) if (column_specs and args.loop_kernel == "deferred") else None
+    physical_gbs = traffic / (loop_ms * 1e-3) / 1e9 if (traffic and column_specs) else None
 
     if args.config == 5:
         workload = ("config 5: GPT-2-small-shaped sweep, 12 layers x (attention out-proj W 768x768 in 12 heads of 64 "
@@ -254,12 +277,17 @@ def main():
                     "Hessians and inverses of the layers on %d streams in turn (their stage times and the Hessian "
                     "rate are then measured under overlap; --sweep-streams 1 gives them undisturbed)" % max(1, len(side)))
         n_steps_loop = sum(sp.n_groups for sp in column_specs)      # the 12 x 3072 single-column removals
+        chain_steps = (len(column_specs) + 3) // 4 * column_specs[0].n_groups     # four loops side by side per launch
     else:
         spec = specs[0]
         workload = ("config %d: %s, W %dx%d, group %d, %d tokens %s, damp %.2g, remove all %d"
                     % (args.config, spec.name, spec.d_row, spec.d_col, spec.group_size, spec.n_tok, spec.x_kind,
                        spec.damp_rel, spec.n_groups))
-        n_steps_loop = spec.n_groups
+        if args.x_layout == "token":
+            workload += "; X token-major"
+        if args.loop_kernel == "eager":
+            workload += "; loop on the eager kernel"
+        n_steps_loop = chain_steps = spec.n_groups
     out = {
         "metric": "structured-OBS prune time per layer (Hessian + inverse + greedy loop)",
         "value": ms_per_step / 1e3,
@@ -284,7 +312,11 @@ def main():
         "roofline": {"kernel": "greedy loop", "bound": "hbm", "achieved": loop_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": loop_gbs / HBM_PEAK_GBS if column_specs else None,
                      "frac_of_triad": loop_gbs / triad_gbs if column_specs else None,
-                     "traffic": traffic, "algorithmic_bytes": loop_bytes},
+                     "traffic": traffic, "algorithmic_bytes": loop_bytes,
+                     "physical_gbs": physical_gbs,
+                     "physical_frac": physical_gbs / HBM_PEAK_GBS if physical_gbs else None,
+                     "handoff_us": handoff_us,
+                     "latency_floor_frac": (chain_steps * handoff_us * 1e-3 / loop_ms) if (handoff_us and column_specs) else None},
         "roofline_hessian": {"kernel": "hessian syrk", "bound": "mfma", "achieved": hess_tflops,
                              "peak": MFMA_F32_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": hess_tflops / MFMA_F32_PEAK_TFLOPS, "useful_flops": syrk_flops},
@@ -315,7 +347,14 @@ def main():
                        "the whole layer of the same workload, once")
                       + " (Hessian %.2f s, inverse %.2f s, loop %.2f s)" % tuple(mult * x for x in parts)}
     out["input_generation_s"] = gen_s
-    print(json.dumps(out))
+    print(json.dumps(out), flush=True)
+    # Device memory, streams and events are released here, while everything that watches the HIP runtime (a profiler's
+    # interposed library, for one) is still alive: left to interpreter shutdown they were destroyed after such a
+    # tool's own teardown, and the process then ended in a segmentation fault after its output had been written.
+    result.clear()
+    del problems, stacks, side
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
 
 
 if __name__ == "__main__":

@@ -227,6 +227,18 @@ int ziplm_selftest_bounded_wait(float *W, float *Hinv, int d_row, int d_col, int
                                 size_t workspace_bytes, void *stream);
 
 /*
+ * Hand-off latency between two workgroups on this device: what the serial chain of Algorithm 1 costs
+ * at the very least per removal when the columns are spread over the whole chip (the argmin of a step
+ * needs a value from every workgroup).  Workgroup 0 and workgroup `partner` (1..15; workgroup i of the
+ * launch runs on XCD i % 8, so 1 is another XCD and 8 the same one) pass a word back and forth
+ * `rounds` times with the device-scope store and polling load the loop uses; *us_out_host (host
+ * pointer) receives the mean one-way time in microseconds.  Waits for the stream.  workspace: 1 KiB,
+ * 256-byte aligned, ordinary or uncached device memory -- the time depends on which.
+ */
+int ziplm_selftest_handoff_latency(int rounds, int partner, double *us_out_host, void *workspace,
+                                   size_t workspace_bytes, void *stream);
+
+/*
  * Error of dropping a whole module ("Pruned structures", Section 3.1: besides heads and
  * feed-forward columns, an entire attention or feed-forward module may be removed).  With every
  * column pruned nothing is left to compensate, so the layer-wise error in the quadratic form of

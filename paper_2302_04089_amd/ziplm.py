@@ -31,7 +31,7 @@ EXPORTS = (
     "ziplm_structured_obs_prune_batch", "ziplm_prune_batch_workspace_bytes",
     "ziplm_prune_exchange_bytes", "ziplm_exchange_alloc",
     "ziplm_structured_obs_prune_eager", "ziplm_prune_eager_workspace_bytes",
-    "ziplm_selftest_bounded_wait",
+    "ziplm_selftest_bounded_wait", "ziplm_selftest_handoff_latency",
     "ziplm_module_error_static", "ziplm_module_error_static_max_tiles",
 )
 
@@ -83,6 +83,8 @@ def lib():
     L.ziplm_prune_eager_workspace_bytes.argtypes = [i32, i32, i32]
     L.ziplm_selftest_bounded_wait.restype = i32
     L.ziplm_selftest_bounded_wait.argtypes = [vp, vp, i32, i32, vp, vp, ctypes.POINTER(i32), vp, sz, vp]
+    L.ziplm_selftest_handoff_latency.restype = i32
+    L.ziplm_selftest_handoff_latency.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double), vp, sz, vp]
     L.ziplm_prune_workspace_bytes.restype = sz
     L.ziplm_prune_workspace_bytes.argtypes = [i32, i32, i32, i32]
     L.ziplm_structured_obs_prune_batch.restype = i32
@@ -270,6 +272,21 @@ def ziplm_selftest_bounded_wait(W, Hinv, workspace=None, stream=None):
     rc = lib().ziplm_selftest_bounded_wait(W.data_ptr(), Hinv.data_ptr(), m, d, order.data_ptr(), err.data_ptr(),
                                            ctypes.byref(info), ws.data_ptr(), ws.numel(), _stream(stream))
     return rc, info.value
+
+
+def ziplm_selftest_handoff_latency(rounds=2000, partner=1, exchange=None, stream=None):
+    """Mean one-way hand-off time (us) between workgroup 0 and workgroup `partner`; the words live in `exchange`
+    (an ExchangeArea) or in ordinary device memory."""
+    us = ctypes.c_double(0.0)
+    if exchange is None:
+        ws = _workspace(1024, torch.device("cuda", torch.cuda.current_device()))
+        ptr, nbytes = ws.data_ptr(), ws.numel()
+    else:
+        ptr, nbytes = ctypes.c_void_p(exchange.ptr), exchange.nbytes
+    rc = lib().ziplm_selftest_handoff_latency(int(rounds), int(partner), ctypes.byref(us), ptr, nbytes, _stream(stream))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return us.value
 
 
 def ziplm_prune_batch_workspace_bytes(n_layers, d_row, d_col, group_size, n_snap=0):
