@@ -809,9 +809,16 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 rd = __builtin_fma(__builtin_fma(-dj, rd, 1.0), rd, rd);
                 double sc = s * rd;
                 sc = __builtin_fma(__builtin_fma(-dj, sc, s), rd, sc);
-                // LDS serves one wavefront's operations in order, so the three below go out back to back and cost one
-                // round trip: the read returns the workgroup's minimum if this report turns out to be the last one
-                // (every other column's minimum was issued ahead of its count)
+                // INVARIANT (the only place where the kernel relies on the order in which one wavefront's LDS operations
+                // are issued): merge the key, count, read the minimum back -- in this order, back to back, one round
+                // trip.  LDS executes a wavefront's operations in issue order, and the atomics of different wavefronts
+                // one at a time; so the wavefront whose count comes out last reads a minimum that holds every other
+                // column's key, each of which was issued ahead of its own count.  The three are relaxed atomics on two
+                // addresses: nothing in the language stops a compiler from swapping the merge and the count, which
+                // would let the last counter publish a minimum that misses a key.  This compiler keeps atomics in
+                // program order, and tests/test_kernel_resources.py checks the generated code for exactly this
+                // sequence.  (A fence between them would make the order a language-level fact at the price of a second
+                // LDS round trip on the chain that decides when the next slot goes out.)
                 atomicMin(cand_key, (dj > 0.0) ? cand_key_of(sc, (unsigned)jl) : cand_key_of(0.0, ENC_ERROR));
                 const int reported = atomicAdd(&misc[6], 1);
                 // (an atomic load, not a volatile one: the latter is compiled to a flat load with system scope, which
