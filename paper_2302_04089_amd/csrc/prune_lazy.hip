@@ -332,6 +332,16 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
             coefa[e] = (rgc < nrgc && kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
         }
         __syncthreads();
+        // bit x: one of this lane's four rows in row group x of the pass is alive (the three-row-group form, which the
+        // launches of several layers use, has no register left for the test and keeps touching every row)
+        unsigned rows_live = FLUSH_RGC < 3 ? 0u : ~0u;
+#pragma unroll
+        for (int x = 0; x < FLUSH_RGC; ++x) {
+            if (FLUSH_RGC < 3 && x < nrgc) {
+                const int r0 = g0 + x * RG + 4 * q4;
+                if (alive_own[r0] | alive_own[r0 + 1] | alive_own[r0 + 2] | alive_own[r0 + 3]) rows_live |= 1u << x;
+            }
+        }
         for (int ct = wave; ct < ntiles; ct += NW) {
             const int c = ct * 16 + cl16;
             const bool col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
@@ -359,7 +369,9 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
             if (col_ok) {
 #pragma unroll
                 for (int x = 0; x < FLUSH_RGC; ++x) {
-                    if (x < nrgc) {
+                    // a lane's four rows: nothing to read or write when none of them is alive (the padding rows of the
+                    // panel never are, and owned columns die as the run goes on): the flush is bound by this traffic
+                    if (x < nrgc && ((rows_live >> x) & 1u)) {
                         doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c * cp + g0 + x * RG + 4 * q4);
                         doublex4 cur = *dst;
                         cur -= acc[x];
