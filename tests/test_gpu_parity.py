@@ -690,3 +690,49 @@ def test_prune_batch_single_columns_matches_oracle(z, oracle, m, d, n, layers, s
     for l in range(layers):
         if l != bad:
             assert torch.equal(W2[l], Wb[l]) and torch.equal(H2[l], Hb[l])      # the good layers are complete
+
+
+def test_hessian_inverse_and_module_error_replay_from_a_hip_graph(z, oracle):
+    """The calls that enqueue plain launches only (no cooperative launch, no host wait, no memset node) can be
+    captured into a HIP graph: Hessian, inverse and the whole-module error in its workspace-free form are captured
+    once and replayed three times, with eager work and synchronisations between the replays; every replay must
+    equal the eager result bit for bit."""
+    spec = workloads.small(48, 200, 1, 1000, x_kind="gelu", seed=71)
+    X = dev(workloads.make_X(spec))
+    W = dev(workloads.make_W(spec))
+    d = spec.d_col
+    H_e = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    z.ziplm_hessian_accumulate(H_e, X, 2.0)
+    Hi_e, lam = z.ziplm_hinv(H_e, spec.damp_rel)
+    tot_e = z.ziplm_module_error_static(W, H_e, 0.25)
+    torch.cuda.synchronize()
+
+    H = torch.zeros((d, d), dtype=torch.float32, device="cuda")
+    Hi = torch.empty_like(H)
+    tot = torch.zeros(1, dtype=torch.float64, device="cuda")
+    ws_h = torch.empty(max(z.ziplm_hessian_workspace_bytes(d, spec.n_tok), 256), dtype=torch.uint8, device="cuda")
+    ws_i = torch.empty(z.ziplm_hinv_workspace_bytes(d), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        # warm-up outside the capture (first-use set-up of the library happens here, not under capture)
+        z.ziplm_hessian_accumulate(H, X, 2.0, workspace=ws_h, stream=side)
+        z.ziplm_hinv(H, spec.damp_rel, out=Hi, workspace=ws_i, stream=side, check=False)
+        z.ziplm_module_error_static(W, H, 0.25, out=tot, stream=side)
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            H.zero_()                        # torch's fill kernel
+            z.ziplm_hessian_accumulate(H, X, 2.0, workspace=ws_h, stream=side)
+            z.ziplm_hinv(H, spec.damp_rel, out=Hi, workspace=ws_i, stream=side, check=False)
+            z.ziplm_module_error_static(W, H, 0.25, out=tot, stream=side)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        H.fill_(float(rep + 1)); Hi.zero_(); tot.zero_()        # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(H, H_e), "replay %d: Hessian" % rep
+        assert torch.equal(Hi, Hi_e), "replay %d: inverse" % rep
+        assert torch.equal(tot, tot_e), "replay %d: whole-module error" % rep
+    assert abs(float(tot[0]) - oracle.module_error(W.cpu().numpy(), H_e.cpu().numpy(), 0.25)) <= 1e-5 * float(tot[0])
