@@ -11,6 +11,7 @@
  *   and, for the sparsity search that consumes the pruned layers (Section 3.2):
  *      ziplm_module_error         error of dropping the whole module, tr(W (H + lambda I) W^T)
  *      ziplm_prior                p_s after every removal of a run
+ *      ziplm_search_select/mutate the search itself, on the host
  *
  * Conventions
  *   - Every matrix is row-major.  W is d_row x d_col; a structure is a set of COLUMNS of W
@@ -287,6 +288,39 @@ int ziplm_module_error_static_max_tiles(void);
  * is on the device, so a violation cannot be returned as a status: every prior_out[t] is then NaN.
  */
 int ziplm_prior(const double *err, int n, const double *total, double *prior_out, void *stream);
+
+/*
+ * Host-side search for a per-layer sparsity configuration under a runtime budget (Section 3.2, "Runtime
+ * awareness", "Finding the optimal sparsity configuration", "Structured SPDY search").  No device work: every
+ * pointer is a HOST pointer.  A configuration picks one level (a pruned version from the per-layer database of
+ * a greedy run) per layer; the flat arrays list the levels of layer 0, then of layer 1, ...: n_levels_host[l]
+ * entries each, ordered by increasing sparsity.
+ *
+ * ziplm_search_select: the configuration of least  sum_l cost[l][s_l]  with  sum_l time[l][s_l] <= budget, by
+ * dynamic programming on a time axis of `buckets` equal steps (1 .. 2^24).  Times are rounded up to whole steps,
+ * so the result always meets the budget in the unrounded times (at the price of leaving up to n_layers steps of
+ * it unused).  Equal costs go to the lower level.  choice_out_host[n_layers]; cost_out_host / time_out_host
+ * (optional): the sum of the chosen costs / unrounded times.  ZIPLM_ERR_UNSUPPORTED if no configuration fits.
+ *
+ * ziplm_search_mutate: the outer loop of the structured SPDY search.  cost[l][s] = c_l * prior[l][s] (prior: the
+ * p_s of ziplm_prior at the level's number of removals; 0 for the dense level, 1 for a dropped module) with one
+ * sensitivity coefficient c_l per layer, all 1 at the start.  n_steps times (the paper: 1000): every coefficient is
+ * redrawn with probability mutate_prob (the paper: 0.1) as a uniform number in (0, 1], ziplm_search_select picks the
+ * configuration, score(choice, user) rates it (lower is better: the caller evaluates the stitched model), and the
+ * trial replaces the incumbent if its score is not worse.  uniform_host[n_steps][n_layers][2]: the caller's
+ * uniform numbers in [0, 1) (decision, value), so a run can be reproduced.  Outputs: the best configuration, its
+ * coefficients and score (the last two optional).  What the paper leaves to the SPDY method it adapts -- the
+ * starting coefficients, the distribution of a redrawn one, the acceptance of equal scores -- is this library's
+ * reading.
+ */
+typedef double (*ziplm_score_fn)(const int32_t *choice, void *user);
+int ziplm_search_select(int n_layers, const int32_t *n_levels_host, const double *time_host,
+                        const double *cost_host, double budget, int buckets, int32_t *choice_out_host,
+                        double *cost_out_host, double *time_out_host);
+int ziplm_search_mutate(int n_layers, const int32_t *n_levels_host, const double *time_host,
+                        const double *prior_host, double budget, int buckets, int n_steps,
+                        double mutate_prob, const double *uniform_host, ziplm_score_fn score, void *user,
+                        int32_t *choice_out_host, double *coef_out_host, double *score_out_host);
 
 #ifdef __cplusplus
 }

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libziplm.so")
-SOURCES = ["api.hip", "hessian.hip", "hinv.hip", "prune.hip", "prune_lazy.hip", "prior.hip"]
+SOURCES = ["api.hip", "hessian.hip", "hinv.hip", "prune.hip", "prune_lazy.hip", "prior.hip", "search.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I" + INCLUDE, "-I" + CSRC,
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -34,7 +34,7 @@ def build(verbose=False):
     objs = []
     procs = []
     for s in SOURCES:
-        obj = os.path.join(objdir, s.replace(".hip", ".o"))
+        obj = os.path.join(objdir, os.path.splitext(s)[0] + ".o")
         cmd = [hipcc] + FLAGS + FILE_FLAGS.get(s, []) + extra + ["-c", os.path.join(CSRC, s), "-o", obj]
         if verbose:
             print(" ".join(cmd))

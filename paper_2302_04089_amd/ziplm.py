@@ -33,9 +33,11 @@ EXPORTS = (
     "ziplm_structured_obs_prune_eager", "ziplm_prune_eager_workspace_bytes",
     "ziplm_selftest_bounded_wait", "ziplm_selftest_handoff_latency",
     "ziplm_module_error_static", "ziplm_module_error_static_max_tiles",
+    "ziplm_search_select", "ziplm_search_mutate",
 )
 
 _lib = None
+SCORE_CALLBACK = ctypes.CFUNCTYPE(ctypes.c_double, ctypes.POINTER(ctypes.c_int32), ctypes.c_void_p)
 
 
 class ZiplmError(RuntimeError):
@@ -103,6 +105,12 @@ def lib():
     L.ziplm_module_error_static_max_tiles.argtypes = []
     L.ziplm_prior.restype = i32
     L.ziplm_prior.argtypes = [vp, i32, vp, vp, vp]
+    dp_, ip_ = ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int32)
+    L.ziplm_search_select.restype = i32
+    L.ziplm_search_select.argtypes = [i32, ip_, dp_, dp_, ctypes.c_double, i32, ip_, dp_, dp_]
+    L.ziplm_search_mutate.restype = i32
+    L.ziplm_search_mutate.argtypes = [i32, ip_, dp_, dp_, ctypes.c_double, i32, i32, ctypes.c_double, dp_,
+                                      SCORE_CALLBACK, vp, ip_, dp_, dp_]
     _lib = L
     return L
 
@@ -384,3 +392,43 @@ def ziplm_prior(err, total, out=None, stream=None):
     if rc != OK:
         raise ZiplmError(rc)
     return out
+
+
+def _flat_levels(per_layer):
+    n_levels = (ctypes.c_int32 * len(per_layer))(*[len(v) for v in per_layer])
+    flat = [float(x) for v in per_layer for x in v]
+    return n_levels, (ctypes.c_double * len(flat))(*flat)
+
+
+def ziplm_search_select(levels_time, levels_cost, budget, buckets=10000):
+    """Host-side: one level per layer of least total cost within the time budget.  levels_time / levels_cost: a list
+    per layer.  Returns (choice list, total cost, total time)."""
+    n = len(levels_time)
+    n_levels, t = _flat_levels(levels_time)
+    _, c = _flat_levels(levels_cost)
+    choice = (ctypes.c_int32 * n)()
+    cost, time_ = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = lib().ziplm_search_select(n, n_levels, t, c, float(budget), int(buckets), choice, ctypes.byref(cost), ctypes.byref(time_))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return list(choice), cost.value, time_.value
+
+
+def ziplm_search_mutate(levels_time, levels_prior, budget, score, uniforms, buckets=10000, mutate_prob=0.1):
+    """Host-side: the outer loop of the structured SPDY search.  score(choice list) -> float, lower is better;
+    uniforms: array-like [n_steps][n_layers][2] of numbers in [0, 1).  Returns (choice, coefficients, best score)."""
+    n = len(levels_time)
+    n_levels, t = _flat_levels(levels_time)
+    _, p = _flat_levels(levels_prior)
+    flat_u = [float(x) for step in uniforms for pair in step for x in pair]
+    n_steps = len(uniforms)
+    u = (ctypes.c_double * max(len(flat_u), 1))(*flat_u)
+    cb = SCORE_CALLBACK(lambda ch, _user: float(score([ch[i] for i in range(n)])))
+    choice = (ctypes.c_int32 * n)()
+    coef = (ctypes.c_double * n)()
+    best = ctypes.c_double(0.0)
+    rc = lib().ziplm_search_mutate(n, n_levels, t, p, float(budget), int(buckets), n_steps, float(mutate_prob), u, cb, None,
+                                   choice, coef, ctypes.byref(best))
+    if rc != OK:
+        raise ZiplmError(rc)
+    return list(choice), list(coef), best.value
