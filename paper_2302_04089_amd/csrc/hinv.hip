@@ -16,6 +16,8 @@
 //                  fp32 operands, fp64 sums), the correction X0 R on the fp32 ones (R is small, so its rounding is
 //                  second order).  The step squares the error of X0, which leaves the rounding of the fp32
 //                  result: the greedy loop's removal order and late-step errors then follow an fp64 inverse.
+//                  Up to two more steps follow when the residual says that one was not enough; past what they can
+//                  repair the result is refused (poison_on_failure_kernel).
 #include "common.h"
 #include "mfma_gemm.h"
 #include "mfma_dgemm.h"
@@ -25,6 +27,9 @@ namespace ziplm {
 int device_cu_count();
 
 constexpr int NB = 64;  // Cholesky panel width
+
+// Newton steps enqueued per call (all but the first gated on the device, see poison_on_failure_kernel)
+constexpr int kNewtonSteps = 3;
 
 // lambda = damp_rel * mean(diag H), accumulated in fp64 by one workgroup.
 __global__ __launch_bounds__(256) void damp_lambda_kernel(const float *__restrict__ H, int d, float damp_rel,
@@ -40,13 +45,17 @@ __global__ __launch_bounds__(256) void damp_lambda_kernel(const float *__restric
     }
     if (threadIdx.x == 0) {
         *lambda_out = (double)damp_rel * (part[0] / (double)d);
-        *info = 0;
+        info[0] = 0;        // 1 + column of the first non-positive pivot, or -1: refinement refused
+        info[1] = 0;        // departure counter of the last kernel
+        for (int s = 0; s < kNewtonSteps; ++s) info[2 + s] = 0;     // largest |R_ij| of each Newton step's residual, float bits
     }
 }
 
-// A (dp x dp) = [H + lambda I, 0; 0, I]; lambda == nullptr: [H, 0; 0, I]
+// A (dp x dp) = [H + lambda I, 0; 0, I]; lambda == nullptr: [H, 0; 0, I].  With a gate: only if *gate > gate_above.
 __global__ __launch_bounds__(256) void embed_kernel(const float *__restrict__ H, int d, float *__restrict__ A,
-                                                    int dp, const double *__restrict__ lambda) {
+                                                    int dp, const double *__restrict__ lambda,
+                                                    const unsigned *__restrict__ gate, unsigned gate_above) {
+    if (gemm::gate_closed(gate, gate_above)) return;
     const float lam = lambda ? (float)(*lambda) : 0.f;
     const int64_t total = (int64_t)dp * dp;
     for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
@@ -370,11 +379,32 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
     }
 }
 
-// A failed factorisation (info != 0) must not pass for an inverse with callers that never look at info: the
-// diagonal of Hinv becomes NaN, which the greedy loop reports as a non-positive pivot at its first step.
-__global__ __launch_bounds__(256) void poison_on_failure_kernel(float *__restrict__ Hinv, int d, const int *__restrict__ info) {
-    if (*info == 0) return;
+// A Newton step X <- X + X (I - A X) squares the error of X only while the residual R = I - A X is small, and its own
+// fp32 product leaves about 1e-7.  Measured on rank-deficient Hessians (relative error of the result against the fp64
+// inverse, by the largest entry of the residual the step started from): 4.6e-5 -> 6e-8, 4.5e-4 -> 1.4e-6,
+// 1.2e-3 -> 6e-6, 8e-3 -> 1.3e-4.  So:
+//   * a step whose residual stays below kRepeatAbove is the last one (error below 5e-7; conditioning up to about 1e5
+//     gets there with the first step);
+//   * above it another step follows, up to kNewtonSteps in all, each enqueued by the host and gated on the device by
+//     the residual of the one before (a closed gate costs a few empty launches);
+//   * the result is refused when the residual the LAST executed step started from is above kResidualLimit (error up
+//     to about 1e-5), NaN included: the matrix is too ill conditioned for the fp32 factorisation to be refined.
+constexpr float kRepeatAbove = 2.5e-4f;
+constexpr float kResidualLimit = 1.5e-3f;
+constexpr int kInfoWords = 2 + kNewtonSteps;      // status, departure counter, one residual maximum per step
+
+// A failed factorisation (info != 0) or a refused refinement must not pass for an inverse with callers that never look
+// at info: the diagonal of Hinv becomes NaN, which the greedy loop reports as a non-positive pivot at its first step.
+__global__ __launch_bounds__(256) void poison_on_failure_kernel(float *__restrict__ Hinv, int d, int *__restrict__ info) {
+    // the residual of the last step that ran: step s + 1 ran iff step s left more than kRepeatAbove
+    float last = __uint_as_float((unsigned)info[2]);
+    for (int s = 1; s < kNewtonSteps && !(last <= kRepeatAbove); ++s) last = __uint_as_float((unsigned)info[2 + s]);
+    const bool refused = !(last <= kResidualLimit);
+    if (info[0] == 0 && !refused) return;
     for (int i = blockIdx.x * 256 + threadIdx.x; i < d; i += gridDim.x * 256) Hinv[(int64_t)i * d + i] = __builtin_nanf("");
+    // every workgroup reads info[0] before any of them may change it: the flag is raised by the last one to leave
+    __syncthreads();
+    if (threadIdx.x == 0 && info[0] == 0 && atomicAdd(&info[1], 1) == (int)gridDim.x - 1) info[0] = -1;
 }
 
 // The large merges of the triangular inverse have 48 to 256 output tiles for 256 compute units (two workgroups fit on each): their k range
@@ -414,7 +444,7 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored 64 x 64 diagonal blocks
     l.loff = c.take<float>((size_t)(l.dp / PW) * NB * NB);    // the block below the first one in every 128 x 128
     l.lambda = c.take<double>(1);
-    l.info = c.take<int>(1);
+    l.info = c.take<int>(kInfoWords);
     l.resid_workgroups = dgemm::residual_workgroups(l.dp, 2 * device_cu_count());     // two workgroups fit a compute unit
     if (l.resid_workgroups > dgemm::RESIDUAL_MAX_WORKGROUPS) l.resid_workgroups = dgemm::RESIDUAL_MAX_WORKGROUPS;
     l.resid_scratch = c.take<double>(dgemm::residual_scratch_doubles(l.resid_workgroups));
@@ -442,7 +472,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     const int fill_blocks = 1024;
 
     hipLaunchKernelGGL(damp_lambda_kernel, dim3(1), dim3(256), 0, st, H, d_col, damp_rel, l.lambda, l.info);
-    hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.A, dp, l.lambda);
+    hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.A, dp, l.lambda,
+                       static_cast<const unsigned *>(nullptr), 0u);
     ZIPLM_HIP_TRY(hipGetLastError());
 
     // ---- A = L L^T, right-looking over 128-column panels: one panel launch, one trailing update ----
@@ -525,30 +556,42 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         ZIPLM_HIP_TRY((launch_splitk<R_CONTIG, R_CONTIG, true, false>(f, 1, nsplit < 1 ? 1 : nsplit, st)));
     }
 
-    // ---- one Newton step: R = I - (H + lambda I) X0 in fp64 (into T), Hinv = X0 + X0 R (lower tiles + mirror) ----
+    // ---- Newton steps: R = I - (H + lambda I) X in fp64 (into T), Hinv = X + X R (lower tiles + mirror) ----
     // H is copied into a padded matrix (S, free again) so that the residual runs on whole tiles; the padding of H and
-    // of X0 is the identity, so the padded block of R stays apart from the d_col x d_col one.
-    hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp, static_cast<const double *>(nullptr));
-    ZIPLM_HIP_TRY(hipGetLastError());
-    {
-        dgemm::ResidualArgs r = {};
-        r.A = l.S; r.lda = dp;
-        r.X = l.A; r.ldx = dp;
-        r.R = l.T; r.ldr = dp;
-        r.lambda = l.lambda;
-        r.n = dp;
-        r.scratch = l.resid_scratch;
-        ZIPLM_HIP_TRY(dgemm::launch_residual(r, l.resid_workgroups, st));
-    }
-    {
+    // of X is the identity, so the padded block of R stays apart from the d_col x d_col one.  The first step starts
+    // from X0 in A; a later one (gated: it runs only if the step before left a residual above kRepeatAbove) copies
+    // Hinv back into A first.
+    for (int step = 0; step < kNewtonSteps; ++step) {
+        const unsigned *gate = step ? reinterpret_cast<const unsigned *>(l.info + 2 + step - 1) : nullptr;
+        const unsigned above = __builtin_bit_cast(unsigned, kRepeatAbove);
+        if (step)
+            hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, Hinv, d_col, l.A, dp,
+                               static_cast<const double *>(nullptr), gate, above);
+        hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp,
+                           static_cast<const double *>(nullptr), gate, above);
+        ZIPLM_HIP_TRY(hipGetLastError());
+        {
+            dgemm::ResidualArgs r = {};
+            r.A = l.S; r.lda = dp;
+            r.X = l.A; r.ldx = dp;
+            r.R = l.T; r.ldr = dp;
+            r.lambda = l.lambda;
+            r.n = dp;
+            r.scratch = l.resid_scratch;
+            r.rmax_bits = reinterpret_cast<unsigned *>(l.info + 2 + step);
+            r.n_valid = d_col;
+            r.gate = gate; r.gate_above = above;
+            ZIPLM_HIP_TRY(dgemm::launch_residual(r, l.resid_workgroups, st));
+        }
         Args c = {};
-        c.A = l.A; c.lda = dp;          // X0, rows along k
+        c.A = l.A; c.lda = dp;          // X, rows along k
         c.B = l.T; c.ldb = dp;          // R[k][n]
         c.C = Hinv; c.ldc = d_col;
         c.D = l.A; c.ldd = dp;
         c.M = d_col; c.N = d_col; c.K = dp;
         c.alpha = 1.f; c.beta = 0.f;
         c.flags = F_TRI_GRID | F_MIRROR;
+        c.gate = gate; c.gate_above = above;
         // 300 tiles on 512 slots at 3072 columns: the k range of every tile is shared so that the slots fill up
         // (accumulators in S and the merges' buffer behind it, both free again)
         const int tm = (d_col + BM - 1) / BM, tiles = tm * (tm + 1) / 2;
@@ -571,7 +614,8 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         if (lambda_out_host) *lambda_out_host = (float)lam;
         if (info_host) {
             *info_host = info;
-            if (info != 0) return ZIPLM_ERR_NOT_PD;
+            if (info > 0) return ZIPLM_ERR_NOT_PD;
+            if (info < 0) return ZIPLM_ERR_UNSUPPORTED;       // too ill conditioned for the fp32 factorisation to be refined
         }
     }
     return ZIPLM_OK;

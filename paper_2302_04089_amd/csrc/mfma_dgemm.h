@@ -39,7 +39,26 @@ struct ResidualArgs {
     // the tile it ends in).  The launch uses at most one workgroup per tile, so a tile is shared by two workgroups
     // at most: a second launch adds head and tail, always in that order, and writes those tiles.
     double *scratch;       // [2 * workgroups][64 accumulators][256 threads]
+    // Largest |R_ij| over the n_valid x n_valid block that holds the caller's matrix (the rest is padding), as the
+    // bit pattern of a non-negative float, raised with an unsigned atomic maximum; NaN counts as infinity.  One
+    // Newton step squares the error only while R is small: the caller refuses the result beyond a limit.
+    unsigned *rmax_bits;
+    int n_valid;
+    // optional gate, as in gemm::Args: nothing happens unless *gate > gate_above
+    const unsigned *gate;
+    unsigned gate_above;
 };
+
+__device__ __forceinline__ void residual_note_max(float local, unsigned *rmax_bits) {
+    // maximum over the wavefront, then one atomic per wavefront
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) local = fmaxf(local, __shfl_xor(local, o));
+    if ((threadIdx.x & 63) == 0) atomicMax(rmax_bits, __float_as_uint(local));
+}
+__device__ __forceinline__ float residual_magnitude(double r) {
+    const float a = fabsf((float)r);
+    return (a == a) ? a : __builtin_inff();
+}
 
 // The range of units of workgroup w out of G.
 __device__ __forceinline__ long long residual_range_begin(long long total, int w, int G) { return total * w / G; }
@@ -47,6 +66,7 @@ __device__ __forceinline__ long long residual_range_begin(long long total, int w
 __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs g) {
     using gemm::floatx4;
     __shared__ __attribute__((aligned(16))) float lds[2][2][gemm::SLAB];
+    if (gemm::gate_closed(g.gate, g.gate_above)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int cl16 = lane & 15, q4 = lane >> 4;
@@ -133,6 +153,7 @@ __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs
             continue;
         }
 
+        float rmax = 0.f;
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -149,14 +170,17 @@ __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs
                     const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
                     const double r = ((row == col) ? 1.0 : 0.0) - acc[i][j][v] - lam * (double)xv[v];
                     g.R[(int64_t)row * g.ldr + col] = (float)r;
+                    if (row < g.n_valid && col < g.n_valid) rmax = fmaxf(rmax, residual_magnitude(r));
                 }
             }
+        residual_note_max(rmax, g.rmax_bits);
     }
 }
 
 // Second launch: workgroup w < G - 1 looks at the boundary between ranges w and w + 1; if it falls inside a tile, the
 // tile is the sum of the head left by w and the tail left by w + 1.  Same thread <-> element mapping as above.
 __global__ __launch_bounds__(gemm::THREADS) void residual_fixup_kernel(ResidualArgs g, int G) {
+    if (gemm::gate_closed(g.gate, g.gate_above)) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int cl16 = lane & 15, q4 = lane >> 4;
@@ -171,6 +195,7 @@ __global__ __launch_bounds__(gemm::THREADS) void residual_fixup_kernel(ResidualA
     const double lam = *g.lambda;
     const double *head = g.scratch + ((size_t)2 * w + 1) * (64 * gemm::THREADS) + tid;
     const double *tail = g.scratch + ((size_t)2 * (w + 1)) * (64 * gemm::THREADS) + tid;
+    float rmax = 0.f;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -190,8 +215,10 @@ __global__ __launch_bounds__(gemm::THREADS) void residual_fixup_kernel(ResidualA
                 const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
                 const double r = ((row == col) ? 1.0 : 0.0) - sum[v] - lam * (double)xv[v];
                 g.R[(int64_t)row * g.ldr + col] = (float)r;
+                if (row < g.n_valid && col < g.n_valid) rmax = fmaxf(rmax, residual_magnitude(r));
             }
         }
+    residual_note_max(rmax, g.rmax_bits);
 }
 
 // Workgroups of the first launch: at most one per tile (a tile is then shared by two workgroups at most), at most

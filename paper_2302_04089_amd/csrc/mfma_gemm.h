@@ -78,7 +78,15 @@ struct Args {
     // symmetric.  Not batched.
     const float *D;
     int64_t ldd;
+    // optional gate: with gate set, the launch does nothing unless *gate > gate_above (a word written by an earlier
+    // kernel on the stream), so that the host can enqueue work whose need only the device knows
+    const unsigned *gate;
+    unsigned gate_above;
 };
+
+__device__ __forceinline__ bool gate_closed(const unsigned *gate, unsigned above) {
+    return gate && __builtin_nontemporal_load(gate) <= above;
+}
 
 // ---------------------------------------------------------------------------------------------
 // Global -> register -> LDS staging of one 128 x 32 slab.
@@ -294,6 +302,7 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
 template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false, int CHUNK = 0>
 __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     __shared__ __attribute__((aligned(16))) float lds[2][2][SLAB];
+    if (gate_closed(g.gate, g.gate_above)) return;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
@@ -465,6 +474,7 @@ __device__ __forceinline__ void reduce_epilogue(const float (&sum)[16], const Ar
 // four groups of four accumulator registers (rows 8q..8q+7 of each 32-row block), so that a tile's
 // reduction is spread over four workgroups.
 static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, int nsplit, int ntiles) {
+    if (gate_closed(g.gate, g.gate_above)) return;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;

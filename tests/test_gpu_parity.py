@@ -499,6 +499,37 @@ def test_failed_factorisation_is_marked_on_the_device(z):
     assert ei.value.status == z.ERR_NOT_PD and ei.value.info == 1
 
 
+@pytest.mark.parametrize("d,n_tok", [(320, 160), (1100, 400)])
+def test_ill_conditioned_inverse_is_either_accurate_or_refused(z, d, n_tok):
+    """A rank-deficient Hessian with ever less dampening (condition number about 1 / damp_rel): the fp32 factorisation
+    gets worse, the refinement takes more Newton steps, and past what it can repair the call must say so.  Whatever
+    the call returns without an error is the fp64 inverse to 2e-5 of its largest entry; an error comes with a NaN
+    diagonal; and the well-conditioned end of the sweep is not refused."""
+    rng = np.random.default_rng(d)
+    X = rng.standard_normal((d, n_tok)).astype(np.float32)
+    H = (2.0 * X.astype(np.float64) @ X.T.astype(np.float64)).astype(np.float32)
+    Hd = dev(H)
+    verdicts = []
+    for damp in (1e-2, 1e-3, 1e-4, 1e-5, 1e-6, 1e-7):
+        lam = damp * float(np.mean(np.diag(H).astype(np.float64)))
+        exact = np.linalg.inv(H.astype(np.float64) + lam * np.eye(d))
+        try:
+            out, _ = z.ziplm_hinv(Hd, damp)
+        except z.ZiplmError as e:
+            assert e.status in (z.ERR_UNSUPPORTED, z.ERR_NOT_PD)
+            assert (e.info == -1) if e.status == z.ERR_UNSUPPORTED else (e.info >= 1)
+            out2, _ = z.ziplm_hinv(Hd, damp, check=False)
+            torch.cuda.synchronize()
+            assert bool(torch.isnan(torch.diagonal(out2)).all())
+            verdicts.append("refused")
+            continue
+        err = np.abs(out.cpu().numpy().astype(np.float64) - exact).max() / np.abs(exact).max()
+        assert err <= 2e-5, "damp %.0e: accepted with relative error %.2e" % (damp, err)
+        verdicts.append("ok")
+    assert verdicts[:3] == ["ok"] * 3, verdicts              # conditioning up to 1e4 ... 1e6 is repaired
+    assert verdicts[-1] == "refused", verdicts               # 1e9 is beyond fp32
+
+
 def test_prior_with_an_unusable_total_is_nan(z):
     err = torch.tensor([1.0, 2.0, 3.0], dtype=torch.float64, device="cuda")
     for total in (0.0, -1.0, float("inf"), float("nan")):
