@@ -557,18 +557,18 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     }
 
     // ---- Newton steps: R = I - (H + lambda I) X in fp64 (into T), Hinv = X + X R (lower tiles + mirror) ----
-    // H is copied into a padded matrix (S, free again) so that the residual runs on whole tiles; the padding of H and
-    // of X is the identity, so the padded block of R stays apart from the d_col x d_col one.  The first step starts
-    // from X0 in A; a later one (gated: it runs only if the step before left a residual above kRepeatAbove) copies
-    // Hinv back into A first.
+    // H is copied once into a padded matrix (S, free again) so that the residual runs on whole tiles; the padding of H
+    // and of X is the identity, so the padded block of R stays apart from the d_col x d_col one.  From here on the
+    // caller's H is not read again (Hinv may be the same memory).  The first step starts from X0 in A; a later one
+    // (gated: it runs only if the step before left a residual above kRepeatAbove) copies Hinv back into A first.
+    hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp,
+                       static_cast<const double *>(nullptr), static_cast<const unsigned *>(nullptr), 0u);
     for (int step = 0; step < kNewtonSteps; ++step) {
         const unsigned *gate = step ? reinterpret_cast<const unsigned *>(l.info + 2 + step - 1) : nullptr;
         const unsigned above = __builtin_bit_cast(unsigned, kRepeatAbove);
         if (step)
             hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, Hinv, d_col, l.A, dp,
                                static_cast<const double *>(nullptr), gate, above);
-        hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp,
-                           static_cast<const double *>(nullptr), gate, above);
         ZIPLM_HIP_TRY(hipGetLastError());
         {
             dgemm::ResidualArgs r = {};
@@ -592,14 +592,14 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         c.alpha = 1.f; c.beta = 0.f;
         c.flags = F_TRI_GRID | F_MIRROR;
         c.gate = gate; c.gate_above = above;
-        // 300 tiles on 512 slots at 3072 columns: the k range of every tile is shared so that the slots fill up
-        // (accumulators in S and the merges' buffer behind it, both free again)
+        // 300 tiles on 512 slots at 3072 columns: the k range of every tile is shared so that the slots fill up.  The
+        // accumulators go where the residual kept its partial tiles (done with them); S keeps H for the next step.
         const int tm = (d_col + BM - 1) / BM, tiles = tm * (tm + 1) / 2;
-        const size_t sets = ((char *)l.partial - (char *)l.S) / (sizeof(float) * 64 * THREADS) + MERGE_PARTIAL_SETS;
+        const size_t sets = dgemm::residual_scratch_doubles(l.resid_workgroups) * sizeof(double) / (sizeof(float) * 64 * THREADS);
         int nsplit = (int)(sets / (size_t)tiles);
         if (nsplit > 3) nsplit = 3;
         if (dp < 1024 || tiles >= 2 * 2 * device_cu_count()) nsplit = 1;
-        c.partial = l.S;
+        c.partial = reinterpret_cast<float *>(l.resid_scratch);
         ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(c, 1, nsplit < 1 ? 1 : nsplit, st)));
     }
     hipLaunchKernelGGL(poison_on_failure_kernel, dim3((d_col + 255) / 256 < 64 ? (d_col + 255) / 256 : 64), dim3(256), 0, st, Hinv, d_col, l.info);

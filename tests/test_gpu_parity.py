@@ -525,6 +525,10 @@ def test_ill_conditioned_inverse_is_either_accurate_or_refused(z, d, n_tok):
             continue
         err = np.abs(out.cpu().numpy().astype(np.float64) - exact).max() / np.abs(exact).max()
         assert err <= 2e-5, "damp %.0e: accepted with relative error %.2e" % (damp, err)
+        # the later steps no longer read the caller's H: in place gives the same bits
+        Hc = Hd.clone()
+        z.ziplm_hinv(Hc, damp, out=Hc)
+        assert torch.equal(Hc, out)
         verdicts.append("ok")
     assert verdicts[:3] == ["ok"] * 3, verdicts              # conditioning up to 1e4 ... 1e6 is repaired
     assert verdicts[-1] == "refused", verdicts               # 1e9 is beyond fp32
