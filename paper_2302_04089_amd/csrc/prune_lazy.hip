@@ -59,7 +59,10 @@ constexpr int RG = 16;                   // owned rows per matrix-core pass (pan
 constexpr int AFRAG = (BMAX / 4) * 64;  // entries of one set of matrix-core A fragments: [k-group][lane]
 constexpr int NPOLL = 4;                // wavefronts that poll the candidate slots (up to 256 workgroups)
 constexpr int NBG = NW - NPOLL;         // wavefronts that apply the previous block's downdates meanwhile
-constexpr int BG_KS = 4;                // k-groups (of 4 pending rows) a background unit covers: a quarter tile
+#ifndef ZIPLM_BG_KS
+#define ZIPLM_BG_KS 8
+#endif
+constexpr int BG_KS = ZIPLM_BG_KS;      // k-groups (of 4 pending rows) a background unit covers: half a tile
 constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
@@ -261,7 +264,7 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, rpivs, rpivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, misc, wt, total;
+    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, rpivs, rpivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, live_list, live_pos, word_prefix, misc, wt, total;
 };
 __host__ __device__ inline int padded_rows(int m) { return (m + 255) / 256 * 256; }   // Eq. 3 runs unguarded
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
@@ -290,6 +293,14 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.alive_own = take(sizeof(int) * cp);
     l.alive_bits = take(sizeof(unsigned) * ((d + 31) / 32));
     l.snap_bits = take(sizeof(unsigned) * ((d + 32) / 32 + 1));
+    // Columns alive at the end of the last block of steps, in ascending order, and each such column's place in that
+    // list: the deferred eliminations run over the list, not over all columns (panels of one row group only: at most
+    // 4096 columns, 16 KB for the pair; not in the instantiations that keep W in the workspace, which have no
+    // register to spare for it)
+    const bool listed = w_in_lds && cp == RG;
+    l.live_list = take(listed ? sizeof(unsigned short) * d : 0);
+    l.live_pos = take(listed ? sizeof(unsigned short) * d : 0);
+    l.word_prefix = take(listed ? sizeof(int) * ((d + 31) / 32 + 1) : 0);
     l.misc = take(96);
     l.wt = take(w_in_lds ? sizeof(float) * (size_t)cpb * mp : 0);
     l.total = o;
@@ -313,6 +324,7 @@ template <int FLUSH_RGC>
 __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double *__restrict__ Ub,
                                                       const double *uloc, const double *pivs, double *coefa,
                                                       const int *alive_own, const unsigned *alive_bits,
+                                                      const unsigned short *live_list, int nlist,
                                                       int k, int d, int cp) {
     // This runs once per 64 steps at most.  The thread index is made opaque here so that the address arithmetic
     // below is redone on entry instead of being hoisted out of the step loop, where it would hold vector
@@ -322,7 +334,9 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
     const int lane = tid & 63, wave = tid >> 6;
     const int q4 = lane >> 4, cl16 = lane & 15;
     const int nks = (k + 3) / 4;
-    const int ntiles = (d + 15) / 16;
+    // with a list of the live columns a tile is sixteen consecutive entries of the list (a column's rows of the panel
+    // are one 128-byte line wherever the column lies), otherwise sixteen consecutive columns
+    const int ntiles = ((live_list ? nlist : d) + 15) / 16;
     for (int g0 = 0; g0 < cp; g0 += RG * FLUSH_RGC) {
         const int nrgc = min(FLUSH_RGC, (cp - g0) / RG);
         // A fragment entry: row group e / AFRAG, k-group (e / 64) % 16, lane e % 64; zeros for row groups past the panel
@@ -343,8 +357,14 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
             }
         }
         for (int ct = wave; ct < ntiles; ct += NW) {
-            const int c = ct * 16 + cl16;
-            const bool col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
+            int c = ct * 16 + cl16;
+            bool col_ok;
+            if (live_list) {
+                col_ok = c < nlist;
+                c = col_ok ? (int)live_list[c] : 0;
+            } else {
+                col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
+            }
             if (!__any(col_ok)) continue;
             doublex4 acc[FLUSH_RGC];
 #pragma unroll
@@ -425,7 +445,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     int *alive_own = reinterpret_cast<int *>(smem + L.alive_own);
     unsigned *alive_bits = reinterpret_cast<unsigned *>(smem + L.alive_bits);
     unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
-    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet
+    unsigned short *live_list = reinterpret_cast<unsigned short *>(smem + L.live_list);
+    unsigned short *live_pos = reinterpret_cast<unsigned short *>(smem + L.live_pos);
+    int *word_prefix = reinterpret_cast<int *>(smem + L.word_prefix);
+    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet, [7] length of live_list
     unsigned long long *cand_key = reinterpret_cast<unsigned long long *>(smem + L.misc + 64);   // best owned column
     unsigned long long *gkey_min = reinterpret_cast<unsigned long long *>(smem + L.misc + 80);   // arg-min of the exchange; the pair
     unsigned long long *gkey_max = reinterpret_cast<unsigned long long *>(smem + L.misc + 88);   // is 16-byte aligned: one read
@@ -512,9 +535,17 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     // lives in LDS (seq_done, bgpart), like the partial accumulators.
     auto bg_unit = [&](int &seq, int &part) {
         const int ct = (wave - NPOLL) + NBG * seq;
-        if (ct >= ntiles) return false;
-        const int c = ct * 16 + cl16;
-        const bool col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
+        int c = ct * 16 + cl16;
+        bool col_ok;
+        if (W_IN_LDS) {         // tiles of the list of live columns
+            const int nlist = misc[7];
+            if (ct * 16 >= nlist) return false;
+            col_ok = c < nlist;
+            c = col_ok ? (int)live_list[c] : 0;
+        } else {
+            if (ct >= ntiles) return false;
+            col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
+        }
         const double *ub = Uprev + (size_t)q4 * d + c;
         double *accp = bgacc + (size_t)(wave - NPOLL) * 256 + lane;
         // the accumulator starts as the panel tile and the A fragments are negated, so the last unit of a
@@ -698,7 +729,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 if (r_hist) rp = rpivs[kk_hist];
                 if (r_prev) rp = rpivprev[kk_prev];
                 if (tid3 == 0) {
-                    const int ct = p >> 4;
+                    // the pivot was alive when the block in the background was handed over: it is on the list
+                    const int ct = !W_IN_LDS ? p >> 4 : bg_active ? (int)live_pos[p] >> 4 : 0;
                     misc[4] = (bg_active && (ct / NBG) >= seq_done[NPOLL + ct % NBG]) ? 1 : 0;
                 }
                 ZIPLM_LAZY_TIMING_PAYLOAD_SEEN(w0[0]);
@@ -894,6 +926,39 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             TICK(5);
             if (misc[0]) { ok = false; break; }
 
+            // The columns alive now, listed: what the flush of this block has to touch.  (The background flush of the
+            // block before, which ran over the old list, was finished above.)
+            const bool listed = W_IN_LDS && cp == RG;
+            if (listed) {
+                const int nwords = (d + 31) / 32;
+                if (wave == 0) {
+                    int carry = 0;
+                    for (int w0 = 0; w0 < nwords; w0 += 64) {
+                        const int w = w0 + lane;
+                        const int cnt = (w < nwords) ? __popc(alive_bits[w]) : 0;
+                        int incl = cnt;
+#pragma unroll
+                        for (int o = 1; o < 64; o <<= 1) {
+                            const int v = __shfl_up(incl, o);
+                            if (lane >= o) incl += v;
+                        }
+                        if (w < nwords) word_prefix[w] = carry + incl - cnt;
+                        carry += __shfl(incl, 63);
+                    }
+                    if (lane == 0) misc[7] = carry;
+                }
+                __syncthreads();
+                for (int c = tid; c < d; c += LT) {
+                    const unsigned bits = alive_bits[c >> 5];
+                    if ((bits >> (c & 31)) & 1u) {
+                        const int at = word_prefix[c >> 5] + __popc(bits & ((1u << (c & 31)) - 1u));
+                        live_list[at] = (unsigned short)c;
+                        live_pos[c] = (unsigned short)at;
+                    }
+                }
+                __syncthreads();
+            }
+
             if (bg_enabled && k == BMAX && t + 1 < S.n_remove) {
                 // hand this block to the background: keep its owned slices, pivots and A fragments
                 for (int e = tid; e < BMAX * cp; e += LT) uprev[e] = uloc[e];
@@ -908,7 +973,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 bg_active = true;
                 __syncthreads();
             } else {
-                flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2)>(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits, k, d, cp);
+                flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2)>(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits,
+                                                             listed ? live_list : nullptr, misc[7], k, d, cp);
             }
             k = 0;
             ublk ^= 1;
