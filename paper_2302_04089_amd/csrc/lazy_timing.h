@@ -3,15 +3,6 @@
 // (which then waits for the stream); the regular build compiles every macro below to nothing.
 #pragma once
 
-// -DZIPLM_LAZY_NO_BACKGROUND_FLUSH: every block of 64 deferred eliminations is applied synchronously, also where the
-// regular build applies it in the background during the following steps' exchanges.  Same results; with the phase
-// timing it shows what the exchange costs by itself.
-#ifdef ZIPLM_LAZY_NO_BACKGROUND_FLUSH
-#define ZIPLM_LAZY_BACKGROUND_FLUSH false
-#else
-#define ZIPLM_LAZY_BACKGROUND_FLUSH true
-#endif
-
 #ifndef ZIPLM_LAZY_TIMING
 
 #define ZIPLM_LAZY_TIMING_FIELD

@@ -57,12 +57,7 @@ constexpr int NW = LT / 64;
 constexpr int BMAX = 64;                 // pending pivot rows between flushes (one lane per row)
 constexpr int RG = 16;                   // owned rows per matrix-core pass (panel rows are padded to this)
 constexpr int AFRAG = (BMAX / 4) * 64;  // entries of one set of matrix-core A fragments: [k-group][lane]
-constexpr int NPOLL = 4;                // wavefronts that poll the candidate slots (up to 256 workgroups)
-constexpr int NBG = NW - NPOLL;         // wavefronts that apply the previous block's downdates meanwhile
-#ifndef ZIPLM_BG_KS
-#define ZIPLM_BG_KS 8
-#endif
-constexpr int BG_KS = ZIPLM_BG_KS;      // k-groups (of 4 pending rows) a background unit covers: half a tile
+constexpr int LIST_MAX_D = 4096;         // layers up to this many columns keep a list of their live columns in LDS
 constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
@@ -264,7 +259,7 @@ __device__ __forceinline__ unsigned long long wave_min_u64(unsigned long long v)
 // LDS carve-up (byte offsets), identical on host and device
 // ------------------------------------------------------------------------------------------------
 struct Lds {
-    size_t uloc, uprev, coefa, coefbg, bgacc, bgpart, cvec, cprev, pivs, pivprev, rpivs, rpivprev, seq_done, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, live_list, live_pos, word_prefix, misc, wt, total;
+    size_t uloc, coefa, cvec, pivs, rpivs, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, live_list, word_prefix, misc, wt, total;
 };
 __host__ __device__ inline int padded_rows(int m) { return (m + 255) / 256 * 256; }   // Eq. 3 runs unguarded
 __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
@@ -273,17 +268,10 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 15) / 16 * 16; return r; };
     l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [row][k]
-    l.uprev = take(sizeof(double) * BMAX * cp);          // the same for the previous block (background flush)
-    l.coefa = take(sizeof(double) * AFRAG);               // matrix-core A fragments of a synchronous flush
-    l.coefbg = take(sizeof(double) * AFRAG);              // matrix-core A fragments of the background flush
-    l.bgacc = take(sizeof(double) * 4 * 64 * NBG);       // its accumulators between steps: [wavefront][4][lane]
-    l.bgpart = take(sizeof(int) * NW);                   // k-group quarter each background wavefront is at
+    // matrix-core A fragments of the flush: one set per row group of a pass (up to three, see flush_panel)
+    l.coefa = take(sizeof(double) * AFRAG * (cp > RG ? 3 : 1));
     l.cvec = take(sizeof(double) * BMAX);                // u_k[p] / piv_k for the current pivot
-    l.cprev = take(sizeof(double) * BMAX);               // the same over the previous block's rows
-    l.pivprev = take(sizeof(double) * BMAX);
     l.rpivs = take(sizeof(double) * BMAX);               // reciprocals of the pivots of the pending rows
-    l.rpivprev = take(sizeof(double) * BMAX);
-    l.seq_done = take(sizeof(int) * NW);                 // column tiles each background wavefront has finished
     l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
     l.wcol = take(mp * sizeof(float));                   // column p of W, zero beyond row m
     l.norm = take(sizeof(double) * cp);
@@ -293,13 +281,10 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
     l.alive_own = take(sizeof(int) * cp);
     l.alive_bits = take(sizeof(unsigned) * ((d + 31) / 32));
     l.snap_bits = take(sizeof(unsigned) * ((d + 32) / 32 + 1));
-    // Columns alive at the end of the last block of steps, in ascending order, and each such column's place in that
-    // list: the deferred eliminations run over the list, not over all columns (panels of one row group only: at most
-    // 4096 columns, 16 KB for the pair; not in the instantiations that keep W in the workspace, which have no
-    // register to spare for it)
-    const bool listed = w_in_lds && cp == RG;
+    // Columns alive at the end of the last block of steps, in ascending order: the deferred eliminations run over the
+    // list, not over all columns (up to LIST_MAX_D columns: 8 KB; wider layers need the space for their pending rows)
+    const bool listed = d <= LIST_MAX_D;
     l.live_list = take(listed ? sizeof(unsigned short) * d : 0);
-    l.live_pos = take(listed ? sizeof(unsigned short) * d : 0);
     l.word_prefix = take(listed ? sizeof(int) * ((d + 31) / 32 + 1) : 0);
     l.misc = take(96);
     l.wt = take(w_in_lds ? sizeof(float) * (size_t)cpb * mp : 0);
@@ -314,12 +299,11 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
 // D[row 4v + l/16][col l%16].  Matrix row i = 4v + q is mapped to owned row g0 + 4q + v, so a lane ends
 // up with four consecutive rows of one column: 32 contiguous bytes of the panel.
 // A panel wider than one row group (several layers share the launch, or d_col above 4096) is taken
-// FLUSH_RGC row groups at a time, so that a tile of pending rows is fetched once for all of them; their A
-// fragments then extend from coefa into the background flush's buffers, which such a panel leaves unused
-// (lds_layout keeps coefa, coefbg and bgacc adjacent: 5 sets of fragments).  Two is what the register budget
-// allows; the instantiation that the single-layer loop of a 768 x 3072 or 1024 x 4096 layer runs (W in LDS,
-// one row group) keeps one, so that its register allocation stays as it was tuned.
-constexpr int FLUSH_KB = 4;              // k-groups whose pending-row entries are requested together
+// FLUSH_RGC row groups at a time, so that a tile of pending rows is fetched once for all of them (coefa holds one set
+// of A fragments per row group of the pass).  Two or three is what the register budget of those instantiations
+// allows; the one that the single-layer loop of a 768 x 3072 or 1024 x 4096 layer runs (W in LDS, one row group)
+// keeps one.
+constexpr int FLUSH_KB = 8;              // k-groups whose pending-row entries are requested together
 template <int FLUSH_RGC>
 __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double *__restrict__ Ub,
                                                       const double *uloc, const double *pivs, double *coefa,
@@ -343,7 +327,7 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
         for (int e = tid; e < (cp > RG ? FLUSH_RGC : 1) * AFRAG; e += LT) {
             const int rgc = e / AFRAG, l = e & 63, kk = 4 * ((e >> 6) & (BMAX / 4 - 1)) + (l >> 4);
             const int arow = g0 + rgc * RG + 4 * (l & 3) + ((l & 15) >> 2);
-            coefa[e] = (rgc < nrgc && kk < k && alive_own[arow]) ? uloc[arow * BMAX + kk] / pivs[kk] : 0.0;
+            coefa[e] = (rgc < nrgc && kk < k && alive_own[arow]) ? -(uloc[arow * BMAX + kk] / pivs[kk]) : 0.0;
         }
         __syncthreads();
         // bit x: one of this lane's four rows in row group x of the pass is alive (the three-row-group form, which the
@@ -366,16 +350,26 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
                 col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
             }
             if (!__any(col_ok)) continue;
+            // The accumulators start as the panel's entries and the A fragments are negated: the tile's entries are
+            // asked for together with the first pending rows and leave with a plain store, instead of a dependent
+            // read-modify-write behind the products.  A lane's four rows: nothing to read or write when none of them is
+            // alive (the padding rows of the panel never are, and owned columns die as the run goes on).
             doublex4 acc[FLUSH_RGC];
 #pragma unroll
-            for (int x = 0; x < FLUSH_RGC; ++x) acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
-            const double *ub = Ub + (size_t)q4 * d + c;
+            for (int x = 0; x < FLUSH_RGC; ++x) {
+                acc[x] = doublex4{0.0, 0.0, 0.0, 0.0};
+                if (col_ok && x < nrgc && ((rows_live >> x) & 1u))
+                    acc[x] = *reinterpret_cast<const doublex4 *>(P + (size_t)c * cp + g0 + x * RG + 4 * q4);
+            }
+            // a uniform base per k-group plus one 32-bit lane offset: one address register for all the requests
+            const unsigned voff = ((unsigned)q4 * (unsigned)d + (unsigned)c) * (unsigned)sizeof(double);
             for (int h = 0; h < nks; h += FLUSH_KB) {
                 double bv[FLUSH_KB];
 #pragma unroll
                 for (int e = 0; e < FLUSH_KB; ++e) {
                     const int kk = 4 * (h + e) + q4;
-                    bv[e] = (kk < k && col_ok) ? __hip_atomic_load(ub + (size_t)(h + e) * 4 * d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
+                    const char *base = reinterpret_cast<const char *>(Ub + (size_t)(h + e) * 4 * d);
+                    bv[e] = (kk < k && col_ok) ? __hip_atomic_load(reinterpret_cast<const double *>(base + voff), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
                 }
 #pragma unroll
                 for (int e = 0; e < FLUSH_KB; ++e) {
@@ -388,16 +382,9 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
             }
             if (col_ok) {
 #pragma unroll
-                for (int x = 0; x < FLUSH_RGC; ++x) {
-                    // a lane's four rows: nothing to read or write when none of them is alive (the padding rows of the
-                    // panel never are, and owned columns die as the run goes on): the flush is bound by this traffic
-                    if (x < nrgc && ((rows_live >> x) & 1u)) {
-                        doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c * cp + g0 + x * RG + 4 * q4);
-                        doublex4 cur = *dst;
-                        cur -= acc[x];
-                        *dst = cur;
-                    }
-                }
+                for (int x = 0; x < FLUSH_RGC; ++x)
+                    if (x < nrgc && ((rows_live >> x) & 1u))
+                        *reinterpret_cast<doublex4 *>(P + (size_t)c * cp + g0 + x * RG + 4 * q4) = acc[x];
             }
         }
         __syncthreads();
@@ -425,16 +412,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     const int m = S.m, d = S.d, cpb = S.cpb, cp = S.cp;
     const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb);
     double *uloc = reinterpret_cast<double *>(smem + L.uloc);
-    double *uprev = reinterpret_cast<double *>(smem + L.uprev);
-    double *coefbg = reinterpret_cast<double *>(smem + L.coefbg);
-    double *bgacc = reinterpret_cast<double *>(smem + L.bgacc);
-    int *bgpart = reinterpret_cast<int *>(smem + L.bgpart);
     double *cvec = reinterpret_cast<double *>(smem + L.cvec);
-    double *cprev = reinterpret_cast<double *>(smem + L.cprev);
-    double *pivprev = reinterpret_cast<double *>(smem + L.pivprev);
     double *rpivs = reinterpret_cast<double *>(smem + L.rpivs);
-    double *rpivprev = reinterpret_cast<double *>(smem + L.rpivprev);
-    int *seq_done = reinterpret_cast<int *>(smem + L.seq_done);
     double *pivs = reinterpret_cast<double *>(smem + L.pivs);
     float *wcol = reinterpret_cast<float *>(smem + L.wcol);
     double *coefa = reinterpret_cast<double *>(smem + L.coefa);
@@ -446,9 +425,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     unsigned *alive_bits = reinterpret_cast<unsigned *>(smem + L.alive_bits);
     unsigned *snap_bits = reinterpret_cast<unsigned *>(smem + L.snap_bits);
     unsigned short *live_list = reinterpret_cast<unsigned short *>(smem + L.live_list);
-    unsigned short *live_pos = reinterpret_cast<unsigned short *>(smem + L.live_pos);
     int *word_prefix = reinterpret_cast<int *>(smem + L.word_prefix);
-    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [4] pivot's tile not flushed yet, [7] length of live_list
+    int *misc = reinterpret_cast<int *>(smem + L.misc);   // [0] fail flag, [2] error seen, [7] length of live_list
     unsigned long long *cand_key = reinterpret_cast<unsigned long long *>(smem + L.misc + 64);   // best owned column
     unsigned long long *gkey_min = reinterpret_cast<unsigned long long *>(smem + L.misc + 80);   // arg-min of the exchange; the pair
     unsigned long long *gkey_max = reinterpret_cast<unsigned long long *>(smem + L.misc + 88);   // is 16-byte aligned: one read
@@ -524,59 +502,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     bool ok = true;
     int error_step = 0;
     unsigned tag4 = 0;
-    // background flush of the previous block of pending rows
-    const bool bg_enabled = ZIPLM_LAZY_BACKGROUND_FLUSH && (cp == RG) && (nb <= 64 * NPOLL);
-    const int ntiles = (d + 15) / 16;
-    const int q4 = lane >> 4, cl16 = lane & 15;
-    bool bg_active = false;
-    const double *Uprev = S.U;
-    // one unit: BG_KS k-groups of one 16-column tile; tiles of wavefront w: (w - NPOLL) + NBG * seq.
-    // Progress (seq, part) is passed in and out by the caller, identically in every lane; between steps it
-    // lives in LDS (seq_done, bgpart), like the partial accumulators.
-    auto bg_unit = [&](int &seq, int &part) {
-        const int ct = (wave - NPOLL) + NBG * seq;
-        int c = ct * 16 + cl16;
-        bool col_ok;
-        if (W_IN_LDS) {         // tiles of the list of live columns
-            const int nlist = misc[7];
-            if (ct * 16 >= nlist) return false;
-            col_ok = c < nlist;
-            c = col_ok ? (int)live_list[c] : 0;
-        } else {
-            if (ct >= ntiles) return false;
-            col_ok = (c < d) && ((alive_bits[c >> 5] >> (c & 31)) & 1u);
-        }
-        const double *ub = Uprev + (size_t)q4 * d + c;
-        double *accp = bgacc + (size_t)(wave - NPOLL) * 256 + lane;
-        // the accumulator starts as the panel tile and the A fragments are negated, so the last unit of a
-        // tile ends with a plain store instead of a dependent read-modify-write
-        doublex4 *dst = reinterpret_cast<doublex4 *>(P + (size_t)c * cp + 4 * q4);
-        doublex4 acc = {0.0, 0.0, 0.0, 0.0};
-        if (part > 0) {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) acc[v] = accp[64 * v];
-        } else if (col_ok) {
-            acc = *dst;
-        }
-        double bv[BG_KS];
-#pragma unroll
-        for (int e = 0; e < BG_KS; ++e)
-            bv[e] = col_ok ? __hip_atomic_load(ub + (size_t)(part * BG_KS + e) * 4 * d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0;
-#pragma unroll
-        for (int e = 0; e < BG_KS; ++e)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(coefbg[(part * BG_KS + e) * 64 + lane], bv[e], acc, 0, 0, 0);
-        if (part == BMAX / 4 / BG_KS - 1) {
-            if (col_ok) *dst = acc;
-            ++seq;
-            part = 0;
-        } else {
-#pragma unroll
-            for (int v = 0; v < 4; ++v) accp[64 * v] = acc[v];
-            ++part;
-        }
-        return true;
-    };
-
     double tau = 1.0e300;   // publish the payload ahead of the exchange only if my best score is <= tau
     const unsigned long long cpb_magic = (0x100000000ull + (unsigned)cpb - 1) / (unsigned)cpb;
 
@@ -628,12 +553,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 ll_store(pw + m + 2 * BMAX, dhi(dv), tag);
                 ll_store(pw + m + 2 * BMAX + 1, dlo(dv), tag);
             }
-            if (bg_active && tid >= LT - 3 * BMAX && tid < LT - 2 * BMAX) {   // entries of the previous block's rows
-                const int kk = tid - (LT - 3 * BMAX);
-                const double u = uprev[cl * BMAX + kk];
-                ll_store(pw + m + 2 * BMAX + 2 + 2 * kk, dhi(u), tag);
-                ll_store(pw + m + 2 * BMAX + 2 + 2 * kk + 1, dlo(u), tag);
-            }
         };
         if (published) publish_payload(cand);
         TICK(1);
@@ -648,14 +567,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 if (!slot_wait(S.slots + ((size_t)par * nb + sb) * SLOT_STRIDE, tag4, sb, cpb, kv, err, S.status)) { fail = true; break; }
                 ZIPLM_LAZY_TIMING_OWN_SLOT;
                 mykey = umin64(mykey, kv);
-            }
-            if (bg_active && wave >= NPOLL) {
-                int seq = seq_done[wave], part = bgpart[wave];     // written before the previous barrier
-                // ahead of the polling wavefronts in the instruction arbiter: their loop only burns issue slots
-                __builtin_amdgcn_s_setprio(3);
-                bg_unit(seq, part);
-                if (lane == 0) { seq_done[wave] = seq; bgpart[wave] = part; }
-                __builtin_amdgcn_s_setprio(0);
             }
             const int nwaves_used = min(NW, (nb + 63) / 64);
             if (wave < nwaves_used) {
@@ -705,13 +616,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             // diagonal, its entry of the stale column) before it waits for any of it.
             constexpr int N3 = 6, T3 = 64 * N3, WQ = 3;
             if (tid3 < T3) {
-                const int kk_hist = tid3 - BMAX, kk_prev = tid3 - 2 * BMAX;
+                const int kk_hist = tid3 - BMAX;
                 const bool r_hist = kk_hist >= 0 && kk_hist < k;
-                const bool r_prev = bg_active && kk_prev >= 0 && kk_prev < BMAX;
-                const bool r_diag = tid3 == 3 * BMAX;
-                const unsigned long long *pa = r_hist ? pw + m + 2 * kk_hist
-                                             : r_prev ? pw + m + 2 * BMAX + 2 + 2 * kk_prev
-                                             : r_diag ? pw + m + 2 * BMAX : nullptr;
+                const bool r_diag = tid3 == 2 * BMAX;
+                const unsigned long long *pa = r_hist ? pw + m + 2 * kk_hist : r_diag ? pw + m + 2 * BMAX : nullptr;
                 double hv = 0.0;
                 // column p of the stored matrix restricted to my rows (= my slice of row p, by symmetry)
                 if (tid3 < cp) hv = P[(size_t)p * cp + tid3];
@@ -727,12 +635,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 }
                 double rp = 0.0;                  // reciprocal pivot of my pending row: asked for ahead of the waits
                 if (r_hist) rp = rpivs[kk_hist];
-                if (r_prev) rp = rpivprev[kk_prev];
-                if (tid3 == 0) {
-                    // the pivot was alive when the block in the background was handed over: it is on the list
-                    const int ct = !W_IN_LDS ? p >> 4 : bg_active ? (int)live_pos[p] >> 4 : 0;
-                    misc[4] = (bg_active && (ct / NBG) >= seq_done[NPOLL + ct % NBG]) ? 1 : 0;
-                }
                 ZIPLM_LAZY_TIMING_PAYLOAD_SEEN(w0[0]);
                 if (tid3 < cp) hstale[tid3] = hv;
                 if (pa) {
@@ -741,7 +643,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                     if (!there && !ll_wait2(pa, tag, hi, lo, S.status)) fail = true;
                     const double val = dmake(hi, lo);
                     if (r_hist) cvec[kk_hist] = val * rp;
-                    else if (r_prev) cprev[kk_prev] = val * rp;
                     else {
                         // reciprocal by two Newton steps from the hardware estimate: short enough not to hold up the barrier
                         double r = __builtin_amdgcn_rcp(val);
@@ -770,11 +671,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             __syncthreads();
         }
         TICK(3);
-        // One LDS round trip for all five; the two failure flags are acted on after step 4 (a branch here would
+        // One LDS round trip for all four; the two failure flags are acted on after step 4 (a branch here would
         // keep the column wavefronts from issuing their loads; nothing of a failed run is written back).
-        const int flag_fail = misc[0], flag_err = misc[2], flag_unflushed = misc[4];
+        const int flag_fail = misc[0], flag_err = misc[2];
         const double piv = misc_d[1], rpiv = misc_d[2];
-        const bool unflushed = flag_unflushed != 0;
         // columns that will report a new score in step 4; the last one to do so publishes the workgroup's
         // slot of the next step at once, without waiting for the barrier and the loop head
         const int participants = nlive - (owner == b ? 1 : 0);
@@ -804,7 +704,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             }
             const double diag_old = diag[jl];        // asked for here, needed after the column's pass
             double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
-            if (unflushed) term += cprev[lane] * uprev[jl * BMAX + lane];
             const double u = hstale[jl] - wave_sum(term);
             const double f = u * rpiv;
             const float nf = -(float)f;
@@ -894,16 +793,6 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
 
         // ---------------------------------------------------------- 5. flush the pending downdates
         if (k == BMAX || t + 1 == S.n_remove) {
-            // whatever is left of the previous block's background flush is finished first
-            if (bg_active) {
-                if (wave >= NPOLL) {
-                    int seq = seq_done[wave], part = bgpart[wave];
-                    // at most (BMAX / 4 / BG_KS) units per tile remain: the bound only guards against a stuck loop
-                    for (int guard = 0; guard < (BMAX / 4 / BG_KS) * (ntiles / NBG + 1) && bg_unit(seq, part); ++guard) {}
-                }
-                __syncthreads();
-                bg_active = false;
-            }
             // all slices of the pending rows must be in memory before anyone reads them
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
@@ -926,9 +815,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             TICK(5);
             if (misc[0]) { ok = false; break; }
 
-            // The columns alive now, listed: what the flush of this block has to touch.  (The background flush of the
-            // block before, which ran over the old list, was finished above.)
-            const bool listed = W_IN_LDS && cp == RG;
+            // The columns alive now, listed: what the flush of this block has to touch.
+            const bool listed = d <= LIST_MAX_D;
             if (listed) {
                 const int nwords = (d + 31) / 32;
                 if (wave == 0) {
@@ -953,29 +841,13 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                     if ((bits >> (c & 31)) & 1u) {
                         const int at = word_prefix[c >> 5] + __popc(bits & ((1u << (c & 31)) - 1u));
                         live_list[at] = (unsigned short)c;
-                        live_pos[c] = (unsigned short)at;
                     }
                 }
                 __syncthreads();
             }
 
-            if (bg_enabled && k == BMAX && t + 1 < S.n_remove) {
-                // hand this block to the background: keep its owned slices, pivots and A fragments
-                for (int e = tid; e < BMAX * cp; e += LT) uprev[e] = uloc[e];
-                if (tid < BMAX) { pivprev[tid] = pivs[tid]; rpivprev[tid] = rpivs[tid]; }
-                for (int e = tid; e < AFRAG; e += LT) {
-                    const int l = e & 63, kk = 4 * (e >> 6) + (l >> 4);
-                    const int arow = 4 * (l & 3) + ((l & 15) >> 2);
-                    coefbg[e] = alive_own[arow] ? -(uloc[arow * BMAX + kk] / pivs[kk]) : 0.0;
-                }
-                if (tid < NW) { seq_done[tid] = 0; bgpart[tid] = 0; }
-                Uprev = S.U + (size_t)ublk * BMAX * d;
-                bg_active = true;
-                __syncthreads();
-            } else {
-                flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2)>(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits,
-                                                             listed ? live_list : nullptr, misc[7], k, d, cp);
-            }
+            flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2)>(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits,
+                                                         listed ? live_list : nullptr, misc[7], k, d, cp);
             k = 0;
             ublk ^= 1;
             TICK(6);
@@ -1015,7 +887,7 @@ static Plan make_plan(int d_row, int d_col, int pack = 1) {
     p.cpb = (d_col + cus - 1) / cus;
     p.cp = (p.cpb + RG - 1) / RG * RG;
     p.nb = (d_col + p.cpb - 1) / p.cpb;
-    p.pay_words = d_row + 4 * BMAX + 2;
+    p.pay_words = d_row + 2 * BMAX + 2;
     const size_t lds_cap = 158 * 1024;
     p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb).total <= lds_cap ? 1 : 0;
     p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb).total;
