@@ -34,12 +34,11 @@
 //      until then would reach the other workgroups most of a microsecond later.
 //
 // One exchange per step is the only device-wide synchronisation; every 64 steps one barrier makes the
-// finished block of pending rows visible.  When a workgroup owns at most 16 columns the flush of that
-// block is then not done at once but in the background: while four wavefronts wait for the next steps'
-// candidates, the other twelve each apply half a column tile of the previous block per step.  A pivot
-// whose column tile has not been reached yet gets the previous block's downdates applied on the fly,
-// exactly like the pending ones of the current block.  All waits are bounded: on a time-out the waiter raises status = -1 and
-// leaves; the others then time out or see the flag, and the grid drains.
+// finished block of pending rows visible, and every workgroup applies the block to its panel at once, over
+// the list of columns that are still alive (a removed column is never read again).  Spreading that work
+// over the following steps' waits, an earlier form, lost to the plain one once the flush followed the
+// live columns.  All waits are bounded: on a time-out the waiter raises status = -1 and leaves; the others
+// then time out or see the flag, and the grid drains.
 #include "common.h"
 #include "lazy_timing.h"
 
