@@ -251,6 +251,29 @@ def test_prune_resume_with_alive_mask(z, oracle):
     assert_columns_close(Wd.cpu().numpy(), ref["W"], "Wd")
 
 
+def test_prune_resume_ragged_width_over_several_blocks(z, oracle):
+    """1000 columns (the last word of the alive bits is partly filled), resumed with 130 columns already gone and
+    taken 300 removals further: the deferred eliminations of the second call run over a list of live columns with gaps
+    from its first block on, four full blocks of 64 and a partial one; the surviving inverse Hessian is compared too."""
+    spec = workloads.small(40, 1000, 1, 3500, x_kind="gelu", seed=23)
+    X, W32, H, Hi32 = _oracle_inputs(oracle, spec)
+    Wd, Hd = dev(W32), dev(Hi32)
+    o1, e1, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, 130)
+    alive = torch.ones(1000, dtype=torch.uint8, device="cuda")
+    alive[o1.long()] = 0
+    o2, e2, _ = z.ziplm_structured_obs_prune(Wd, Hd, 1, 300, alive=alive)
+    torch.cuda.synchronize()
+    order = torch.cat([o1, o2]).cpu().numpy()
+    err = torch.cat([e1, e2]).cpu().numpy()
+    ref = compare_run(oracle, W32, Hi32, 1, 430, order, err)
+    Wg, Hg = Wd.cpu().numpy(), Hd.cpu().numpy()
+    gone = np.zeros(1000, bool)
+    gone[ref["order"]] = True
+    assert np.all(Wg[:, gone] == 0.0) and np.all(Hg[gone, :] == 0.0) and np.all(Hg[:, gone] == 0.0)
+    assert_columns_close(Wg, ref["W"], "W after both calls")
+    assert_columns_close(Hg, ref["Hinv"], "surviving Hinv after both calls")
+
+
 def test_prune_zero_removals_is_identity(z):
     W = torch.randn(8, 32, device="cuda")
     Hi = torch.eye(32, device="cuda")
