@@ -8,10 +8,10 @@
 //   * Eq. 4 is a rank-1 downdate  Hinv -= u u^T / u[p]  with u = the current row p.  The next step
 //     only needs (a) the current diagonal, which each owner keeps up to date from u alone, and (b) the
 //     current row of the next pivot, which is  stale_row - sum_k u_k[p'] u_k / piv_k  over the
-//     downdates not yet applied.  So the downdates of up to 64 consecutive steps are kept as a list
+//     downdates not yet applied.  So the downdates of a block of consecutive steps (64, or 256 for wide layers) are kept as a list
 //     of pivot rows and applied to the stored matrix in one pass ("flush"), a 16 x 64 x d
 //     contraction per workgroup on the fp64 matrix cores.  The stored fp64 matrix is then read and
-//     written once per 64 steps instead of once per step.
+//     written once per block instead of once per step.
 //   * W is compensated at every step (Eq. 3 needs no deferral: the scores need the current W).
 //
 // Work is divided by columns: workgroup b owns `cpb` consecutive columns j, i.e. column j of W (kept
@@ -33,7 +33,7 @@
 //      ends the step also waits for the step's global stores to be acknowledged, and a candidate held back
 //      until then would reach the other workgroups most of a microsecond later.
 //
-// One exchange per step is the only device-wide synchronisation; every 64 steps one barrier makes the
+// One exchange per step is the only device-wide synchronisation; at the end of a block one barrier makes the
 // finished block of pending rows visible, and every workgroup applies the block to its panel at once, over
 // the list of columns that are still alive (a removed column is never read again).  Spreading that work
 // over the following steps' waits, an earlier form, lost to the plain one once the flush followed the
@@ -53,9 +53,14 @@ constexpr unsigned long long KEY_EMPTY_ = ~0ull;
 
 constexpr int LT = 1024;                 // threads per workgroup (16 wavefronts)
 constexpr int NW = LT / 64;
-constexpr int BMAX = 64;                 // pending pivot rows between flushes (one lane per row)
+// Pending pivot rows between two flushes.  Every flush reads and writes the whole panel, so a longer block means a
+// smaller share of that per step (0.52 -> 0.35 us at 3072 columns for 64 -> 256 rows) and a longer history that every
+// step's payload carries and every pivot-row slice is corrected with (+0.3 us per step for the same change: slower at
+// 3072 columns, 2.3% faster at 4096, where the panel is 1.8 times the size).  Wide layers whose workgroups own a single
+// row group (they have the LDS for it) take the long block.
+constexpr int BMAX_WIDE = 256, BMAX_NARROW = 64, WIDE_FROM_D = 4096;
+static_assert(BMAX_WIDE % 64 == 0 && BMAX_WIDE >= 64 && BMAX_WIDE <= 256, "one to four pending rows per lane");
 constexpr int RG = 16;                   // owned rows per matrix-core pass (panel rows are padded to this)
-constexpr int AFRAG = (BMAX / 4) * 64;  // entries of one set of matrix-core A fragments: [k-group][lane]
 constexpr int LIST_MAX_D = 4096;         // layers up to this many columns keep a list of their live columns in LDS
 constexpr unsigned long long kTimeoutTicks = 400000000ull;   // 4 s of the 100 MHz wall clock
 constexpr int IDX_NONE = -1;             // workgroup has no live column
@@ -85,14 +90,14 @@ struct State {
     // workspace
     double *P;                    // [nb][d][cp]  panels of the stored (stale between flushes) inverse Hessian
     float *Wt;                    // [d][m]       transposed W when it does not fit LDS, else unused
-    double *U;                    // [2][BMAX][d] pending pivot rows of the current / previous block of steps
+    double *U;                    // [2][block_rows][d] pending pivot rows of the current / previous block of steps
     unsigned long long *slots;    // [2][nb][SLOT_STRIDE], word 0 of each
     unsigned long long *pay;      // [2][nb][pay_words]
     unsigned long long *bar;      // [nb] flush-barrier epochs
     int *status;
     int cpb;                      // columns per workgroup
     int cp;                       // cpb rounded up to a multiple of RG
-    int pay_words;                // m + 4*BMAX + 2
+    int pay_words;                // m + 2 * block_rows + 2
     int stall_wg;                 // -1; the self-test of the bounded waits names a workgroup that never takes part
     ZIPLM_LAZY_TIMING_FIELD
 };
@@ -261,17 +266,22 @@ struct Lds {
     size_t uloc, coefa, cvec, pivs, rpivs, wcol, norm, diag, score, hstale, alive_own, alive_bits, snap_bits, live_list, word_prefix, misc, wt, total;
 };
 __host__ __device__ inline int padded_rows(int m) { return (m + 255) / 256 * 256; }   // Eq. 3 runs unguarded
-__host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb) {
+// block length of a layer: the long one only where W stays in LDS and the launch holds one layer (one more kernel
+// instantiation, the block length being a compile-time constant of each)
+inline int block_rows(int cp, int d, bool w_in_lds, int pack) {
+    return (cp == RG && d >= WIDE_FROM_D && w_in_lds && pack == 1) ? BMAX_WIDE : BMAX_NARROW;
+}
+__host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, int cpb, int bmax) {
     Lds l;
     const int mp = padded_rows(m);
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 15) / 16 * 16; return r; };
-    l.uloc = take(sizeof(double) * BMAX * cp);           // pending pivot rows, owned slice: [row][k]
+    l.uloc = take(sizeof(double) * bmax * cp);           // pending pivot rows, owned slice: [row][k]
     // matrix-core A fragments of the flush: one set per row group of a pass (up to three, see flush_panel)
-    l.coefa = take(sizeof(double) * AFRAG * (cp > RG ? 3 : 1));
-    l.cvec = take(sizeof(double) * BMAX);                // u_k[p] / piv_k for the current pivot
-    l.rpivs = take(sizeof(double) * BMAX);               // reciprocals of the pivots of the pending rows
-    l.pivs = take(sizeof(double) * BMAX);                // pivots of the pending rows
+    l.coefa = take(sizeof(double) * (bmax / 4 * 64) * (cp > RG ? 3 : 1));     // [row group][k-group][lane]
+    l.cvec = take(sizeof(double) * bmax);                // u_k[p] / piv_k for the current pivot
+    l.rpivs = take(sizeof(double) * bmax);               // reciprocals of the pivots of the pending rows
+    l.pivs = take(sizeof(double) * bmax);                // pivots of the pending rows
     l.wcol = take(mp * sizeof(float));                   // column p of W, zero beyond row m
     l.norm = take(sizeof(double) * cp);
     l.diag = take(sizeof(double) * cp);
@@ -303,13 +313,13 @@ __host__ __device__ inline Lds lds_layout(int m, int d, int cp, bool w_in_lds, i
 // allows; the one that the single-layer loop of a 768 x 3072 or 1024 x 4096 layer runs (W in LDS, one row group)
 // keeps one.
 constexpr int FLUSH_KB = 8;              // k-groups whose pending-row entries are requested together
-template <int FLUSH_RGC>
+template <int FLUSH_RGC, int BROWS>
 __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double *__restrict__ Ub,
                                                       const double *uloc, const double *pivs, double *coefa,
                                                       const int *alive_own, const unsigned *alive_bits,
                                                       const unsigned short *live_list, int nlist,
                                                       int k, int d, int cp) {
-    // This runs once per 64 steps at most.  The thread index is made opaque here so that the address arithmetic
+    // This runs once per block of steps.  The thread index is made opaque here so that the address arithmetic
     // below is redone on entry instead of being hoisted out of the step loop, where it would hold vector
     // registers through every step.
     int tid = threadIdx.x;
@@ -317,16 +327,17 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
     const int lane = tid & 63, wave = tid >> 6;
     const int q4 = lane >> 4, cl16 = lane & 15;
     const int nks = (k + 3) / 4;
+    constexpr int bmax = BROWS, afrag = BROWS / 4 * 64;
     // with a list of the live columns a tile is sixteen consecutive entries of the list (a column's rows of the panel
     // are one 128-byte line wherever the column lies), otherwise sixteen consecutive columns
     const int ntiles = ((live_list ? nlist : d) + 15) / 16;
     for (int g0 = 0; g0 < cp; g0 += RG * FLUSH_RGC) {
         const int nrgc = min(FLUSH_RGC, (cp - g0) / RG);
-        // A fragment entry: row group e / AFRAG, k-group (e / 64) % 16, lane e % 64; zeros for row groups past the panel
-        for (int e = tid; e < (cp > RG ? FLUSH_RGC : 1) * AFRAG; e += LT) {
-            const int rgc = e / AFRAG, l = e & 63, kk = 4 * ((e >> 6) & (BMAX / 4 - 1)) + (l >> 4);
+        // A fragment entry: row group e / afrag, k-group (e / 64) % (bmax / 4), lane e % 64; zeros for row groups past the panel
+        for (int e = tid; e < (cp > RG ? FLUSH_RGC : 1) * afrag; e += LT) {
+            const int rgc = e / afrag, l = e & 63, kk = 4 * ((e >> 6) % (bmax / 4)) + (l >> 4);
             const int arow = g0 + rgc * RG + 4 * (l & 3) + ((l & 15) >> 2);
-            coefa[e] = (rgc < nrgc && kk < k && alive_own[arow]) ? -(uloc[arow * BMAX + kk] / pivs[kk]) : 0.0;
+            coefa[e] = (rgc < nrgc && kk < k && alive_own[arow]) ? -(uloc[arow * bmax + kk] / pivs[kk]) : 0.0;
         }
         __syncthreads();
         // bit x: one of this lane's four rows in row group x of the pass is alive (the three-row-group form, which the
@@ -375,7 +386,7 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
                     if (h + e < nks) {
 #pragma unroll
                         for (int x = 0; x < FLUSH_RGC; ++x)
-                            if (x == 0 || cp > RG) acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(coefa[x * AFRAG + (h + e) * 64 + lane], bv[e], acc[x], 0, 0, 0);
+                            if (x == 0 || cp > RG) acc[x] = __builtin_amdgcn_mfma_f64_16x16x4f64(coefa[x * afrag + (h + e) * 64 + lane], bv[e], acc[x], 0, 0, 0);
                     }
                 }
             }
@@ -393,7 +404,7 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
 // PACKED: several layers share the launch.  The single-layer instantiations address the one State through
 // constant offsets of the kernel argument; with the layer chosen at run time the compiler re-reads fields
 // inside the loop, which costs the single-layer loop 2.5%.
-template <bool W_IN_LDS, bool PACKED>
+template <bool W_IN_LDS, bool PACKED, int BROWS>
 __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     ZIPLM_LAZY_TIMING_LOCALS
@@ -409,7 +420,8 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
         return;
     }
     const int m = S.m, d = S.d, cpb = S.cpb, cp = S.cp;
-    const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb);
+    constexpr int bmax = BROWS;               // steps per block of deferred eliminations
+    const Lds L = lds_layout(m, d, cp, W_IN_LDS, cpb, bmax);
     double *uloc = reinterpret_cast<double *>(smem + L.uloc);
     double *cvec = reinterpret_cast<double *>(smem + L.cvec);
     double *rpivs = reinterpret_cast<double *>(smem + L.rpivs);
@@ -451,7 +463,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
     if (tid == 0) { misc[0] = 0; misc[2] = 0; *cand_key = KEY_NONE; *gkey_min = KEY_EMPTY; *gkey_max = 0; }
     for (int w = tid; w < (d + 32) / 32 + 1; w += LT) snap_bits[w] = 0;
     for (int r = tid; r < cp; r += LT) { alive_own[r] = 0; norm[r] = 0.0; diag[r] = 1.0; score[r] = 0.0; hstale[r] = 0.0; }
-    for (int e = tid; e < BMAX * cp; e += LT) uloc[e] = 0.0;
+    for (int e = tid; e < bmax * cp; e += LT) uloc[e] = 0.0;
     for (int i = tid; i < mp; i += LT) wcol[i] = 0.f;
     __syncthreads();
     for (int q = tid; q < S.n_snap; q += LT) {
@@ -541,16 +553,16 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             const int cl = col - j0;
             unsigned long long *pw = S.pay + ((size_t)par * nb + b) * S.pay_words;
             for (int i = tid; i < m; i += LT) ll_store(pw + i, __float_as_uint(WT(cl, i)), tag);
-            if (tid >= LT - BMAX && tid - (LT - BMAX) < k) {     // last wavefront: rarely busy in step 4
-                const int kk = tid - (LT - BMAX);
-                const double u = uloc[cl * BMAX + kk];
+            if (tid >= LT - bmax && tid - (LT - bmax) < k) {     // the last wavefronts: rarely busy in step 4
+                const int kk = tid - (LT - bmax);
+                const double u = uloc[cl * bmax + kk];
                 ll_store(pw + m + 2 * kk, dhi(u), tag);
                 ll_store(pw + m + 2 * kk + 1, dlo(u), tag);
             }
-            if (tid == LT - BMAX - 1) {
+            if (tid == LT - bmax - 1) {
                 const double dv = diag[cl];
-                ll_store(pw + m + 2 * BMAX, dhi(dv), tag);
-                ll_store(pw + m + 2 * BMAX + 1, dlo(dv), tag);
+                ll_store(pw + m + 2 * bmax, dhi(dv), tag);
+                ll_store(pw + m + 2 * bmax + 1, dlo(dv), tag);
             }
         };
         if (published) publish_payload(cand);
@@ -615,10 +627,13 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
             // diagonal, its entry of the stale column) before it waits for any of it.
             constexpr int N3 = 6, T3 = 64 * N3, WQ = 3;
             if (tid3 < T3) {
-                const int kk_hist = tid3 - BMAX;
+                // the first wavefront fetches the stale column, the next ones the history (one pending row per thread)
+                // and the diagonal entry behind it
+                static_assert(64 + BROWS < T3, "history and diagonal fit the wavefronts of this step");
+                const int kk_hist = tid3 - 64;
                 const bool r_hist = kk_hist >= 0 && kk_hist < k;
-                const bool r_diag = tid3 == 2 * BMAX;
-                const unsigned long long *pa = r_hist ? pw + m + 2 * kk_hist : r_diag ? pw + m + 2 * BMAX : nullptr;
+                const bool r_diag = tid3 == 64 + bmax;
+                const unsigned long long *pa = r_hist ? pw + m + 2 * kk_hist : r_diag ? pw + m + 2 * bmax : nullptr;
                 double hv = 0.0;
                 // column p of the stored matrix restricted to my rows (= my slice of row p, by symmetry)
                 if (tid3 < cp) hv = P[(size_t)p * cp + tid3];
@@ -702,7 +717,10 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                     wpre[q] = *reinterpret_cast<const floatx4 *>(&WT(jl, min(256 * q, mp - 256) + 4 * lane));
             }
             const double diag_old = diag[jl];        // asked for here, needed after the column's pass
-            double term = (lane < k) ? cvec[lane] * uloc[jl * BMAX + lane] : 0.0;
+            double term = (lane < k) ? cvec[lane] * uloc[jl * bmax + lane] : 0.0;
+#pragma unroll
+            for (int q = 1; q < BROWS / 64; ++q)
+                if (lane + 64 * q < k) term += cvec[lane + 64 * q] * uloc[jl * bmax + lane + 64 * q];
             const double u = hstale[jl] - wave_sum(term);
             const double f = u * rpiv;
             const float nf = -(float)f;
@@ -767,7 +785,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 // also waits for the stores to global memory still in flight)
                 const unsigned long long knext = __hip_atomic_load(cand_key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
                 // bookkeeping nobody waits for
-                uloc[jl * BMAX + k] = u;
+                uloc[jl * bmax + k] = u;
                 diag[jl] = dj;
                 norm[jl] = s;
                 score[jl] = sc;
@@ -776,7 +794,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                     __hip_atomic_store(S.slots + ((size_t)((t + 1) & 1) * nb + b) * SLOT_STRIDE, knext | tag4_next, __ATOMIC_RELAXED,
                                        __HIP_MEMORY_SCOPE_AGENT);
                 }
-                __hip_atomic_store(S.U + ((size_t)ublk * BMAX + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(S.U + ((size_t)ublk * bmax + k) * d + j, u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         // bookkeeping that nobody needs before the next step, after the columns (thread 0 belongs to a column wavefront)
@@ -791,7 +809,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
         TICK(4);
 
         // ---------------------------------------------------------- 5. flush the pending downdates
-        if (k == BMAX || t + 1 == S.n_remove) {
+        if (k == bmax || t + 1 == S.n_remove) {
             // all slices of the pending rows must be in memory before anyone reads them
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
@@ -845,7 +863,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
                 __syncthreads();
             }
 
-            flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2)>(P, S.U + (size_t)ublk * BMAX * d, uloc, pivs, coefa, alive_own, alive_bits,
+            flush_panel<PACKED ? 3 : (W_IN_LDS ? 1 : 2), BROWS>(P, S.U + (size_t)ublk * bmax * d, uloc, pivs, coefa, alive_own, alive_bits,
                                                          listed ? live_list : nullptr, misc[7], k, d, cp);
             k = 0;
             ublk ^= 1;
@@ -874,7 +892,7 @@ __global__ __launch_bounds__(LT) void prune_lazy_kernel(const StatePack pack) {
 }
 
 struct Plan {
-    int nb, cpb, cp, w_in_lds, pay_words;
+    int nb, cpb, cp, w_in_lds, pay_words, brows;
     size_t lds_bytes;
     bool feasible;
 };
@@ -886,10 +904,16 @@ static Plan make_plan(int d_row, int d_col, int pack = 1) {
     p.cpb = (d_col + cus - 1) / cus;
     p.cp = (p.cpb + RG - 1) / RG * RG;
     p.nb = (d_col + p.cpb - 1) / p.cpb;
-    p.pay_words = d_row + 2 * BMAX + 2;
     const size_t lds_cap = 158 * 1024;
-    p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb).total <= lds_cap ? 1 : 0;
-    p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb).total;
+    // W in LDS if it fits beside the long block where that applies, else beside the short one, else in the workspace
+    p.brows = block_rows(p.cp, d_col, true, pack);
+    p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb, p.brows).total <= lds_cap ? 1 : 0;
+    if (!p.w_in_lds && p.brows != BMAX_NARROW) {
+        p.brows = BMAX_NARROW;
+        p.w_in_lds = lds_layout(d_row, d_col, p.cp, true, p.cpb, p.brows).total <= lds_cap ? 1 : 0;
+    }
+    p.lds_bytes = lds_layout(d_row, d_col, p.cp, p.w_in_lds != 0, p.cpb, p.brows).total;
+    p.pay_words = d_row + 2 * p.brows + 2;
     p.feasible = p.lds_bytes <= lds_cap && p.cpb <= MAX_CPB && d_col <= MAX_D;
     return p;
 }
@@ -906,7 +930,7 @@ static Layout make_layout(int d_row, int d_col, int n_snap, const Plan &p, void 
     Carver c(ws);
     s.P = c.take<double>((size_t)p.nb * d_col * p.cp);
     s.Wt = c.take<float>(p.w_in_lds ? 1 : (size_t)d_col * padded_rows(d_row));
-    s.U = c.take<double>((size_t)2 * BMAX * d_col);
+    s.U = c.take<double>((size_t)2 * p.brows * d_col);
     // zero-initialised region: slots, payload, barrier epochs, status
     s.slots = c.take<unsigned long long>((size_t)2 * p.nb * SLOT_STRIDE);
     s.pay = c.take<unsigned long long>((size_t)2 * p.nb * p.pay_words);
@@ -1009,9 +1033,10 @@ int lazy_columns_launch(float *W, float *Hinv, int pack, int64_t stride_w, int64
         pk.s[q] = lay[q].st;
         status_dev_out[q] = lay[q].st.status;
     }
-    const int variant = (p.w_in_lds ? 1 : 0) + (pack > 1 ? 2 : 0);
-    void (*const kernels[4])(const StatePack) = {prune_lazy_kernel<false, false>, prune_lazy_kernel<true, false>,
-                                                 prune_lazy_kernel<false, true>, prune_lazy_kernel<true, true>};
+    const int variant = (p.brows == BMAX_WIDE) ? 4 : (p.w_in_lds ? 1 : 0) + (pack > 1 ? 2 : 0);
+    void (*const kernels[5])(const StatePack) = {prune_lazy_kernel<false, false, BMAX_NARROW>, prune_lazy_kernel<true, false, BMAX_NARROW>,
+                                                 prune_lazy_kernel<false, true, BMAX_NARROW>, prune_lazy_kernel<true, true, BMAX_NARROW>,
+                                                 prune_lazy_kernel<true, false, BMAX_WIDE>};
     const void *fn = reinterpret_cast<const void *>(kernels[variant]);
     // every time: the attribute belongs to the current device's copy of the kernel, and the call costs microseconds
     ZIPLM_HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));

@@ -32,7 +32,7 @@ def test_greedy_loop_kernel_uses_no_scratch_memory(tmp_path):
     assert out.returncode == 0, out.stderr[-2000:]
     kernels = re.split(r"remark: Function Name: ", out.stderr)[1:]
     loops = [k for k in kernels if "prune_lazy_kernel" in k.split()[0]]
-    assert len(loops) == 4, "expected W in LDS / in the workspace, each for one layer and for several per launch"
+    assert len(loops) == 5, "expected W in LDS / in the workspace, each for one layer and for several per launch, and the long-block form"
     for k in loops:
         name = k.split()[0]
         scratch = int(re.search(r"ScratchSize \[bytes/lane\]: (\d+)", k).group(1))
@@ -43,7 +43,7 @@ def test_greedy_loop_kernel_uses_no_scratch_memory(tmp_path):
 
 def test_candidate_merge_count_and_read_back_are_issued_in_program_order(tmp_path):
     """ds_min_u64 (key into the workgroup's minimum) -> ds_add_rtn_u32 (count) -> ds_read_b64 (minimum back, same
-    address as the ds_min), back to back, once in each of the four instantiations."""
+    address as the ds_min), back to back, once in each of the five instantiations."""
     from paper_2302_04089_amd import build
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     if not os.path.exists(hipcc):
@@ -56,7 +56,7 @@ def test_candidate_merge_count_and_read_back_are_issued_in_program_order(tmp_pat
     insts = [l.split(";")[0].strip() for l in asm.read_text().splitlines()]
     insts = [l for l in insts if l and not l.startswith((".", "s_nop")) and not l.endswith(":")]
     counted = [i for i, l in enumerate(insts) if l.startswith("ds_add_rtn_u32")]
-    assert len(counted) == 4, "one counting atomic per kernel instantiation expected, found %d" % len(counted)
+    assert len(counted) == 5, "one counting atomic per kernel instantiation expected, found %d" % len(counted)
     for i in counted:
         before, after = insts[i - 1], insts[i + 1]
         assert before.startswith("ds_min_u64"), "the count is not issued right behind the key merge: %r" % before
