@@ -353,11 +353,12 @@ def test_prune_random_small_shapes(z, oracle, seed):
     _run_prune_case(z, oracle, spec, k, sorted({0, k // 2, k}))
 
 
-@pytest.mark.parametrize("m", [8, 1100])
-def test_prune_more_than_sixteen_columns_per_workgroup(z, oracle, m):
-    """4352 columns = 17 per workgroup on 256 compute units: two 16-row groups per panel and the
-    synchronous flush; with 1100 rows the transposed W no longer fits LDS and lives in the workspace."""
-    d, k = 4352, 200
+@pytest.mark.parametrize("m,d,k", [(8, 4352, 200), (1100, 4352, 200), (8, 4096, 300)])
+def test_prune_wide_layers_partial_removal(z, oracle, m, d, k):
+    """4352 columns = 17 per workgroup on 256 compute units: two 16-row groups per panel, no list of live columns
+    (wider than the list holds); with 1100 rows the transposed W no longer fits LDS and lives in the workspace.
+    4096 columns = 16 per workgroup: the kernel with blocks of 256 deferred eliminations, one full block and a partial
+    one."""
     Hi32 = _spd_inverse_like(d, 16, seed=m)
     rng = np.random.default_rng(m)
     W32 = (0.05 * rng.standard_normal((m, d))).astype(np.float32)
