@@ -98,10 +98,11 @@ size_t ziplm_hessian_workspace_bytes(int d_col, int64_t n_tok);
  * waits for the stream and stores lambda and, in *info_host, 0; or 1 + the index of the first
  * non-positive pivot (-> ZIPLM_ERR_NOT_PD); or -1 when H + lambda I is too ill conditioned for
  * the fp32 factorisation to be refined (-> ZIPLM_ERR_UNSUPPORTED: use more dampening).  The
- * refinement repeats, up to three steps in all, while the residual I - (H + lambda I) X it starts
- * from has an entry above 2.5e-4 (condition numbers up to about 1e5 need one step and reach a
- * relative error below 5e-7), and is refused when the last step started above 1.5e-3 (a
- * relative error beyond about 1e-5; condition numbers of 1e7 and more).  Either failure is also
+ * refinement takes a second step when the residual I - (H + lambda I) X the first one starts from
+ * has an entry above 2.5e-4 (condition numbers up to about 1e5 need one step and reach a relative
+ * error below 5e-7), and is refused when the last step started above 1.5e-3 (a relative error
+ * beyond about 1e-5; condition numbers of a few 1e6 and more, where the rounding of an fp32 H
+ * already moves its exact inverse by tens of per cent).  Either failure is also
  * marked on the device, for callers that do not wait: every diagonal entry of Hinv is set to
  * NaN, which ziplm_structured_obs_prune reports as ZIPLM_ERR_NOT_PD at its first step.
  */

@@ -16,7 +16,7 @@
 //                  fp32 operands, fp64 sums), the correction X0 R on the fp32 ones (R is small, so its rounding is
 //                  second order).  The step squares the error of X0, which leaves the rounding of the fp32
 //                  result: the greedy loop's removal order and late-step errors then follow an fp64 inverse.
-//                  Up to two more steps follow when the residual says that one was not enough; past what they can
+//                  A second step follows when the residual says that one was not enough; past what the two can
 //                  repair the result is refused (poison_on_failure_kernel).
 #include "common.h"
 #include "mfma_gemm.h"
@@ -29,7 +29,7 @@ int device_cu_count();
 constexpr int NB = 64;  // Cholesky panel width
 
 // Newton steps enqueued per call (all but the first gated on the device, see poison_on_failure_kernel)
-constexpr int kNewtonSteps = 3;
+constexpr int kNewtonSteps = 2;
 
 // lambda = damp_rel * mean(diag H), accumulated in fp64 by one workgroup.
 __global__ __launch_bounds__(256) void damp_lambda_kernel(const float *__restrict__ H, int d, float damp_rel,
@@ -385,10 +385,12 @@ __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, 
 // 1.2e-3 -> 6e-6, 8e-3 -> 1.3e-4.  So:
 //   * a step whose residual stays below kRepeatAbove is the last one (error below 5e-7; conditioning up to about 1e5
 //     gets there with the first step);
-//   * above it another step follows, up to kNewtonSteps in all, each enqueued by the host and gated on the device by
-//     the residual of the one before (a closed gate costs a few empty launches);
+//   * above it a second step follows, enqueued by the host every time and gated on the device by the residual of the
+//     first (a closed gate costs five empty launches, 25 us);
 //   * the result is refused when the residual the LAST executed step started from is above kResidualLimit (error up
 //     to about 1e-5), NaN included: the matrix is too ill conditioned for the fp32 factorisation to be refined.
+//     That is the case from a condition number of a few 1e6 on -- where the rounding of the fp32 Hessian itself
+//     (2e-7 per entry) already moves the exact inverse by tens of per cent, so a third step would refine noise.
 constexpr float kRepeatAbove = 2.5e-4f;
 constexpr float kResidualLimit = 1.5e-3f;
 constexpr int kInfoWords = 2 + kNewtonSteps;      // status, departure counter, one residual maximum per step
