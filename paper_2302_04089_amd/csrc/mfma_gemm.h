@@ -313,8 +313,11 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
         // Workgroups are dealt to the 8 XCDs round-robin by blockIdx.x.  Neighbouring entries of the tile
         // list share their row slab of A, so each XCD takes a contiguous eighth of the list and finds
         // that slab in its own L2.
+        // (Not when the k range shrinks with the tile row: an eighth of the list would then be an eighth of the tiles
+        // and far from an eighth of the work.  Dealt one by one, every XCD gets long and short tiles alike, and the
+        // longest go out first.)
         const int n = gridDim.x, x = blockIdx.x % 8;
-        tile_linear = x * (n / 8) + min(x, n % 8) + blockIdx.x / 8;
+        tile_linear = (g.flags & F_KSTART_MAXMN) ? (int)blockIdx.x : x * (n / 8) + min(x, n % 8) + blockIdx.x / 8;
         tri_decode(tile_linear, tm, tn);
     } else {
         tile_linear = blockIdx.x;
