@@ -430,14 +430,17 @@ __global__ __launch_bounds__(64) void trtri_diag_kernel(const float *__restrict_
     for (int i = 0; i < NB; ++i) dinv[i * NB + lane] = t[i];          // t[i] = T[i][lane], zero above the diagonal
 }
 
-// T (dp x dp) = block diagonal of the inverted 64 x 64 factors, zero elsewhere.
+// The diagonal 128 x 128 tiles of T: the two inverted 64 x 64 factors on their diagonal, zeros beside them.  Tiles
+// below the diagonal are written by the merges; tiles above it are never read (every product that reads T clips its
+// k range to the lower triangle at tile granularity).  One workgroup per tile.
 __global__ __launch_bounds__(256) void place_diag_kernel(float *__restrict__ T, int dp, const float *__restrict__ dinv) {
-    const int64_t total = (int64_t)dp * dp;
-    for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < total; idx += (int64_t)gridDim.x * 256) {
-        const int i = (int)(idx / dp), j = (int)(idx % dp);
-        float v = 0.f;
-        if (i / NB == j / NB) v = dinv[(int64_t)(i / NB) * NB * NB + (i % NB) * NB + (j % NB)];
-        T[idx] = v;
+    const int t0 = blockIdx.x * PW;
+    for (int e = threadIdx.x; e < PW * PW / 4; e += 256) {
+        const int i = e / (PW / 4), j = 4 * (e % (PW / 4));
+        gemm::floatx4 v = {0.f, 0.f, 0.f, 0.f};
+        if (i / NB == j / NB)
+            v = *reinterpret_cast<const gemm::floatx4 *>(dinv + (int64_t)((t0 + i) / NB) * NB * NB + (i % NB) * NB + (j % NB));
+        *reinterpret_cast<gemm::floatx4 *>(T + (int64_t)(t0 + i) * dp + t0 + j) = v;
     }
 }
 
@@ -562,7 +565,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
 
     // ---- T = L^-1: leaves (all diagonal blocks in one launch), then pairwise merges -------------------
     hipLaunchKernelGGL(trtri_diag_kernel, dim3(dp / NB), dim3(64), 0, st, l.ldiag, l.dinv);
-    hipLaunchKernelGGL(place_diag_kernel, dim3(fill_blocks), dim3(256), 0, st, l.T, dp, l.dinv);
+    hipLaunchKernelGGL(place_diag_kernel, dim3(dp / PW), dim3(256), 0, st, l.T, dp, l.dinv);
     ZIPLM_HIP_TRY(hipGetLastError());
     for (int s = NB; s < dp; s *= 2) {
         const int nfull = dp / (2 * s);
@@ -622,8 +625,12 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     // and of X is the identity, so the padded block of R stays apart from the d_col x d_col one.  From here on the
     // caller's H is not read again (Hinv may be the same memory).  The first step starts from X0 in A; a later one
     // (gated: it runs only if the step before left a residual above kRepeatAbove) copies Hinv back into A first.
-    hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp,
-                       static_cast<const double *>(nullptr), static_cast<const unsigned *>(nullptr), 0u);
+    // (A caller's H that is a whole number of tiles already, and is not also the output, is read in place.)
+    const bool h_in_place = (d_col == dp) && (static_cast<const void *>(H) != static_cast<const void *>(Hinv)) &&
+                            (reinterpret_cast<uintptr_t>(H) % 16 == 0);          // 128-bit loads
+    if (!h_in_place)
+        hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.S, dp,
+                           static_cast<const double *>(nullptr), static_cast<const unsigned *>(nullptr), 0u);
     for (int step = 0; step < kNewtonSteps; ++step) {
         const unsigned *gate = step ? reinterpret_cast<const unsigned *>(l.info + 2 + step - 1) : nullptr;
         const unsigned above = __builtin_bit_cast(unsigned, kRepeatAbove);
@@ -633,7 +640,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         ZIPLM_HIP_TRY(hipGetLastError());
         {
             dgemm::ResidualArgs r = {};
-            r.A = l.S; r.lda = dp;
+            r.A = h_in_place ? H : l.S; r.lda = dp;
             r.X = l.A; r.ldx = dp;
             r.R = l.T; r.ldr = dp;
             r.lambda = l.lambda;
