@@ -87,13 +87,14 @@ __device__ __forceinline__ float lane_bcast(float v, int lane) {
 // only the entry the next pivot waits for (column j + 1) travels through a register broadcast, so that the chain
 // pivot -> reciprocal root -> scaled column -> next pivot never waits for LDS.  (Sixty-three register broadcasts
 // per column, the earlier form, cost two thirds of the routine's time.)
-__device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
-    first_bad = -1;
-    my_rdiag = 1.f;
+// Columns J0 .. J1 - 1 of that factorisation; only columns below J1 are updated (the block of columns from J1 on gets
+// the whole rank-(J1 - J0) update from the matrix cores afterwards, see potrf64_in_registers).
+template <int J0, int J1>
+__device__ __forceinline__ void potrf_columns(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
     gemm::floatx4 lprev[NB / 4], lcur[NB / 4];      // column j - 1 and column j of the factor, as read back from LDS
     float aprev = 0.f;                              // this lane's entry of column j - 1
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
+    for (int j = J0; j < J1; ++j) {
         // the chain: pivot, reciprocal root, scaled column, and the one update the next pivot waits for
         float piv = lane_bcast(a[j], j);
         const bool bad = !(piv > 0.f);                    // uniform
@@ -103,16 +104,16 @@ __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, f
         my_rdiag = (lane == j) ? r : my_rdiag;            // 1 / l_jj
         a[j] = a[j] * r;                                  // column j of L; lane j: piv / sqrt(piv) = l_jj
         Lt[j][lane] = a[j];
-        if (j + 1 < NB) a[j + 1] -= a[j] * lane_bcast(a[j], j + 1);
+        if (j + 1 < J1) a[j + 1] -= a[j] * lane_bcast(a[j], j + 1);
         // column j back from LDS (in flight during the multiply-adds below) ...
 #pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4)
+        for (int c4 = 0; c4 < J1 / 4; ++c4)
             if (4 * c4 + 3 > j + 1) lcur[c4] = *reinterpret_cast<const gemm::floatx4 *>(&Lt[j][4 * c4]);
         __builtin_amdgcn_sched_barrier(0);
         // ... while column j - 1, asked for one step ago, updates the columns from j + 1 on
-        if (j > 0) {
+        if (j > J0) {
 #pragma unroll
-            for (int c4 = 0; c4 < NB / 4; ++c4)
+            for (int c4 = 0; c4 < J1 / 4; ++c4)
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
                     if (4 * c4 + e > j) a[4 * c4 + e] -= aprev * lprev[c4][e];
@@ -120,9 +121,46 @@ __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, f
         __builtin_amdgcn_sched_barrier(0);
         aprev = a[j];
 #pragma unroll
-        for (int c4 = 0; c4 < NB / 4; ++c4) lprev[c4] = lcur[c4];
+        for (int c4 = 0; c4 < J1 / 4; ++c4) lprev[c4] = lcur[c4];
     }
-    // (column NB - 1 has nothing left to update)
+    // (column J1 - 1 has nothing left to update)
+}
+
+// The 64 x 64 factorisation in two halves of 32 columns.  After the first half the rows 32 .. 63 hold L21 in their
+// first 32 entries (and Lt[k][32 + r] = L21[r][k] in LDS); their remaining 32 x 32 block takes the whole update
+// L21 L21^T from the matrix cores at once -- sixteen instructions instead of a thousand multiply-adds spread over the
+// column steps -- and goes back to the rows' registers through the part of Lt that the second half has not written
+// yet (skewed by the row, so that neither the scatter nor the gather meets a bank conflict).
+__device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
+    first_bad = -1;
+    my_rdiag = 1.f;
+    constexpr int HB = NB / 2;
+    potrf_columns<0, HB>(a, lane, Lt, my_rdiag, first_bad);
+    {
+        const int r = lane & 31, half = lane >> 5;
+        gemm::floatx16 acc;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        // lane l supplies A[row l % 32][k l / 32] and B[k l / 32][col l % 32]: the same entry of L21 for both
+#pragma unroll
+        for (int kk = 0; kk < HB; kk += 2) {
+            const float f = Lt[kk + half][HB + r];
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(f, f, acc, 0, 0, 0);
+        }
+        // accumulator v: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32
+        float *scratch = &Lt[HB][0];              // 32 rows of 64 floats, free until the second half writes them
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = 8 * (v >> 2) + 4 * half + (v & 3);
+            scratch[row * NB + ((r + row) & 31)] = acc[v];
+        }
+        // the same wavefront reads what it wrote: LDS keeps a wavefront's operations in order
+        if (lane >= HB) {
+#pragma unroll
+            for (int c = 0; c < HB; ++c) a[HB + c] -= scratch[r * NB + ((c + r) & 31)];
+        }
+    }
+    potrf_columns<HB, NB>(a, lane, Lt, my_rdiag, first_bad);
 }
 
 // x L^T = a for one row held in registers, column by column: x_j = a_j / L[j][j], then a_c -= x_j L[c][j] for
