@@ -4,8 +4,9 @@
 // A symmetric rank-n_tok update on the fp32 matrix cores: only the lower-triangular list of
 // 128 x 128 output tiles is computed; every strictly-lower tile is also written transposed, so both
 // triangles of H are valid.  When the triangular tile list alone cannot fill the chip the token
-// range is split; the splits write raw accumulators to the workspace and a second kernel adds them in
-// split order (fixed summation order: results do not change from run to run).
+// range is split; the splits write raw accumulators to the workspace and count themselves at their tile, and the
+// one that counts last adds all sets in split order (fixed summation order whoever is last: results do not change
+// from run to run) and applies the epilogue.
 #include "common.h"
 #include "mfma_gemm.h"
 
@@ -33,7 +34,7 @@ struct HessianPlan {
     int tiles;        // lower-triangular tile count
     int nsplit;       // token splits
     int64_t k_chunk;  // tokens per split (multiple of 32)
-    size_t ws_bytes;
+    size_t ws_bytes, partial_bytes;
 };
 
 static HessianPlan plan_hessian(int d_col, int64_t n_tok) {
@@ -60,7 +61,9 @@ static HessianPlan plan_hessian(int d_col, int64_t n_tok) {
     p.k_chunk = chunk > 0 ? chunk : gemm::BK;
     p.nsplit = (int)((n_tok + p.k_chunk - 1) / p.k_chunk);
     if (p.nsplit < 1) p.nsplit = 1;
-    p.ws_bytes = p.nsplit > 1 ? align_up((size_t)p.nsplit * p.tiles * 64 * gemm::THREADS * sizeof(float)) : 0;
+    // accumulator sets of the splits, then one arrival counter per tile
+    p.partial_bytes = p.nsplit > 1 ? align_up((size_t)p.nsplit * p.tiles * 64 * gemm::THREADS * sizeof(float)) : 0;
+    p.ws_bytes = p.nsplit > 1 ? p.partial_bytes + align_up(sizeof(int) * (size_t)p.tiles) : 0;
     return p;
 }
 
@@ -73,13 +76,11 @@ static int run_hessian(const gemm::Args &base, const HessianPlan &plan, hipStrea
         ZIPLM_HIP_TRY(hipGetLastError());
         return ZIPLM_OK;
     }
+    // the splits count themselves at their tile; the one that counts last adds all sets in split order (one launch)
     g.flags |= gemm::F_PARTIAL;
-    hipLaunchKernelGGL((gemm::gemm_kernel<MODE, MODE, VEC, true, false, HESSIAN_CHUNK>), dim3(plan.tiles, plan.nsplit, 1),
+    if (zero_fill(g.tile_counters, plan.ws_bytes - plan.partial_bytes, stream) != ZIPLM_OK) return ZIPLM_ERR_DEVICE;
+    hipLaunchKernelGGL((gemm::gemm_kernel<MODE, MODE, VEC, true, false, HESSIAN_CHUNK, true>), dim3(plan.tiles, plan.nsplit, 1),
                        dim3(gemm::THREADS), 0, stream, g);
-    ZIPLM_HIP_TRY(hipGetLastError());
-    g.flags &= ~gemm::F_PARTIAL;
-    hipLaunchKernelGGL(gemm::splitk_reduce_kernel, dim3(plan.tiles, 4), dim3(gemm::THREADS), 0, stream, g,
-                       plan.nsplit, plan.tiles);
     ZIPLM_HIP_TRY(hipGetLastError());
     return ZIPLM_OK;
 }
@@ -111,6 +112,7 @@ extern "C" int ziplm_hessian_accumulate(float *H, const float *X, int d_col, int
     g.flags = gemm::F_TRI_GRID | gemm::F_MIRROR;
     g.k_chunk = plan.k_chunk;
     g.partial = static_cast<float *>(workspace);
+    g.tile_counters = plan.nsplit > 1 ? reinterpret_cast<int *>(static_cast<char *>(workspace) + plan.partial_bytes) : nullptr;
     g.tiles_n = (d_col + gemm::BN - 1) / gemm::BN;
     const bool vec = (ldx % 4 == 0) && (reinterpret_cast<uintptr_t>(X) % 16 == 0);
     hipStream_t st = static_cast<hipStream_t>(stream);

@@ -33,7 +33,10 @@ constexpr int kNewtonSteps = 2;
 
 // lambda = damp_rel * mean(diag H), accumulated in fp64 by one workgroup.
 __global__ __launch_bounds__(256) void damp_lambda_kernel(const float *__restrict__ H, int d, float damp_rel,
-                                                          double *__restrict__ lambda_out, int *__restrict__ info) {
+                                                          double *__restrict__ lambda_out, int *__restrict__ info,
+                                                          int *__restrict__ counters, int ncounters) {
+    // arrival counters of the split products: zero before the first of them (each leaves them zero again)
+    for (int i = threadIdx.x; i < ncounters; i += 256) counters[i] = 0;
     __shared__ double part[256];
     double s = 0.0;
     for (int i = threadIdx.x; i < d; i += 256) s += (double)H[(int64_t)i * d + i];
@@ -527,6 +530,8 @@ static int merge_splits(int M, int N, int64_t K, int batch) {
 struct HinvLayout {
     int dp;
     float *A, *T, *S, *dinv, *ldiag, *loff, *partial;
+    int *counters;       // one per (batch, tile) of a split product
+    int ncounters;
     double *lambda;
     int *info;
     // Newton step: partial sums of the tiles two workgroups share
@@ -549,6 +554,11 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.ldiag = c.take<float>((size_t)(l.dp / NB) * NB * NB);   // factored 64 x 64 diagonal blocks
     l.loff = c.take<float>((size_t)(l.dp / PW) * NB * NB);    // the block below the first one in every 128 x 128
     l.lambda = c.take<double>(1);
+    {
+        const int tm = l.dp / gemm::BM;
+        l.ncounters = tm * (tm + 1) / 2 + 256;       // the lower tiles of a full-size product, or the 256 tiles at most of a split merge
+        l.counters = c.take<int>((size_t)l.ncounters);
+    }
     l.info = c.take<int>(kInfoWords);
     l.resid_workgroups = dgemm::residual_workgroups(l.dp, 2 * device_cu_count());     // two workgroups fit a compute unit
     if (l.resid_workgroups > dgemm::RESIDUAL_MAX_WORKGROUPS) l.resid_workgroups = dgemm::RESIDUAL_MAX_WORKGROUPS;
@@ -576,7 +586,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
     const int dp = l.dp;
     const int fill_blocks = 1024;
 
-    hipLaunchKernelGGL(damp_lambda_kernel, dim3(1), dim3(256), 0, st, H, d_col, damp_rel, l.lambda, l.info);
+    hipLaunchKernelGGL(damp_lambda_kernel, dim3(1), dim3(256), 0, st, H, d_col, damp_rel, l.lambda, l.info, l.counters, l.ncounters);
     hipLaunchKernelGGL(embed_kernel, dim3(fill_blocks), dim3(256), 0, st, H, d_col, l.A, dp, l.lambda,
                        static_cast<const unsigned *>(nullptr), 0u);
     ZIPLM_HIP_TRY(hipGetLastError());
@@ -623,6 +633,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
             m1.alpha = 1.f; m1.beta = 0.f; m1.flags = F_KSTART_N;
             m1.strideA = m1.strideB = m1.strideC = stride;
             m1.partial = l.partial;
+            m1.tile_counters = l.counters;
             ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(m1, batch, merge_splits(m1.M, m1.N, m1.K, batch), st)));
             // T21 = -T22 S21     (T22 lower triangular: k ends with the tile row)
             Args m2 = {};
@@ -633,6 +644,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
             m2.alpha = -1.f; m2.beta = 0.f; m2.flags = F_KEND_M;
             m2.strideA = m2.strideB = m2.strideC = stride;
             m2.partial = l.partial;
+            m2.tile_counters = l.counters;
             ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(m2, batch, merge_splits(m2.M, m2.N, m2.K, batch), st)));
         }
     }
@@ -655,6 +667,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         if (nsplit > 4) nsplit = 4;
         if (dp < 1024) nsplit = 1;
         f.partial = l.S;
+        f.tile_counters = l.counters;
         ZIPLM_HIP_TRY((launch_splitk<R_CONTIG, R_CONTIG, true, false>(f, 1, nsplit < 1 ? 1 : nsplit, st)));
     }
 
@@ -706,6 +719,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
         if (nsplit > 3) nsplit = 3;
         if (dp < 1024 || tiles >= 2 * 2 * device_cu_count()) nsplit = 1;
         c.partial = reinterpret_cast<float *>(l.resid_scratch);
+        c.tile_counters = l.counters;
         ZIPLM_HIP_TRY((launch_splitk<K_CONTIG, R_CONTIG, true, false>(c, 1, nsplit < 1 ? 1 : nsplit, st)));
     }
     hipLaunchKernelGGL(poison_on_failure_kernel, dim3((d_col + 255) / 256 < 64 ? (d_col + 255) / 256 : 64), dim3(256), 0, st, Hinv, d_col, l.info);

@@ -82,6 +82,8 @@ struct Args {
     // kernel on the stream), so that the host can enqueue work whose need only the device knows
     const unsigned *gate;
     unsigned gate_above;
+    // FUSED split-K: one arrival counter per (batch, tile), zero before the launch and zero again after it
+    int *tile_counters;
 };
 
 __device__ __forceinline__ bool gate_closed(const unsigned *gate, unsigned above) {
@@ -299,7 +301,10 @@ __device__ __forceinline__ void epilogue(const floatx16 (&acc)[2][2], float *__r
 // about (sqrt(16 CHUNK / chunks) + sqrt(chunks)) * 2^-25 of the sum -- 1e-7 for a dozen chunks of 256.  A
 // second set in fp64 does not fit the register file at two workgroups per compute unit; callers bound the
 // number of chunks per launch through the k range they give a workgroup.  The products are unchanged.
-template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false, int CHUNK = 0>
+// FUSED (the instantiation that F_PARTIAL launches use): no second launch for the sum over the splits.  Every workgroup
+// writes its accumulators through to memory and counts itself at its tile; the one that counts last reads all the sets
+// back, adds them in split order (the same order, hence the same bits, whoever is last) and applies the epilogue.
+template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false, int CHUNK = 0, bool FUSED = false>
 __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
     __shared__ __attribute__((aligned(16))) float lds[2][2][SLAB];
     if (gate_closed(g.gate, g.gate_above)) return;
@@ -419,15 +424,46 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = acc2[(i * 2 + j) * 16 + v];
     }
 
-    if (g.flags & F_PARTIAL) {
-        float *dst = g.partial + (((int64_t)blockIdx.z * gridDim.y + split) * gridDim.x + tile_linear) * (64 * THREADS);
+    if (FUSED && (g.flags & F_PARTIAL)) {
+        const int nsplit = gridDim.y;
+        float *sets = g.partial + ((int64_t)blockIdx.z * nsplit * gridDim.x + tile_linear) * (64 * THREADS);
+        const int64_t set_stride = (int64_t)gridDim.x * (64 * THREADS);
+        float *dst = sets + split * set_stride;
+        // written through to memory (the reader may sit on another XCD) ...
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) dst[((i * 2 + j) * 16 + v) * THREADS + tid] = acc[i][j][v];
-        return;
+                for (int v = 0; v < 16; ++v)
+                    __hip_atomic_store(dst + ((i * 2 + j) * 16 + v) * THREADS + tid, acc[i][j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // ... and acknowledged, for every thread of the workgroup, before the workgroup counts itself
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        int *ticket = reinterpret_cast<int *>(&lds[0][0][0]);      // every wavefront is past the last slice's barrier
+        if (tid == 0)
+            *ticket = __hip_atomic_fetch_add(g.tile_counters + (int64_t)blockIdx.z * gridDim.x + tile_linear, 1, __ATOMIC_RELAXED,
+                                             __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (*ticket != nsplit - 1) return;                          // uniform
+        if (tid == 0)
+            __hip_atomic_store(g.tile_counters + (int64_t)blockIdx.z * gridDim.x + tile_linear, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // the last one: all sets in split order, its own included (read back, so that the sum does not depend on who is last)
+        for (int s2 = 0; s2 < nsplit; ++s2) {
+            const float *src = sets + s2 * set_stride;
+            float part[64];
+#pragma unroll
+            for (int e = 0; e < 64; ++e) part[e] = __hip_atomic_load(src + e * THREADS + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float pv = part[(i * 2 + j) * 16 + v];
+                        acc[i][j][v] = (s2 == 0) ? (0.f + pv) : acc[i][j][v] + pv;
+                    }
+        }
     }
     if (DOT) {
         // every thread sums its 64 products in fp64, then the 256 partial sums are added in thread order
@@ -462,67 +498,6 @@ __global__ __launch_bounds__(THREADS, 2) void gemm_kernel(Args g) {
              g.D ? g.D + (int64_t)blockIdx.z * g.strideC : nullptr, g.ldd, (g.flags & F_MIRROR) && tm == tn);
 }
 
-template <int Q>
-__device__ __forceinline__ void reduce_epilogue(const float (&sum)[16], const Args &g, int tm, int tn, bool mirror,
-                                                int wm, int wn, int lane) {
-    floatx16 acc[2][2];
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[e >> 3][(e >> 2) & 1][4 * Q + (e & 3)] = sum[e];
-    epilogue<4 * Q, 4 * Q + 4>(acc, g.C, g.ldc, g.M, g.N, tm, tn, g.alpha, g.beta, mirror, wm, wn, lane, g.D, g.ldd,
-                               (g.flags & F_MIRROR) && tm == tn);
-}
-
-// Second pass of a split-K product: sums the raw accumulators of all splits in split order and
-// applies the epilogue.  Same thread <-> element mapping as gemm_kernel; blockIdx.y selects one of the
-// four groups of four accumulator registers (rows 8q..8q+7 of each 32-row block), so that a tile's
-// reduction is spread over four workgroups.
-static __global__ __launch_bounds__(THREADS) void splitk_reduce_kernel(Args g, int nsplit, int ntiles) {
-    if (gate_closed(g.gate, g.gate_above)) return;
-    const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int tile_linear = blockIdx.x;
-    const int q = blockIdx.y;
-    int tm, tn;
-    if (g.flags & F_TRI_GRID) {
-        tri_decode(tile_linear, tm, tn);
-    } else {
-        tm = tile_linear / g.tiles_n;
-        tn = tile_linear % g.tiles_n;
-        if ((g.flags & F_LOWER_ONLY) && tn > tm) return;
-    }
-    float sum[16];       // this workgroup's quarter of the thread's accumulators: [i][j][4 q + v] at e = 8 i + 4 j + v
-#pragma unroll
-    for (int e = 0; e < 16; ++e) sum[e] = 0.f;
-    // Splits are added in index order (fixed summation order); the loads of SU splits are issued together, since
-    // with few workgroups per tile list this kernel is a chain of memory round trips, not a bandwidth problem.
-    constexpr int SU = 6;
-    for (int s0 = 0; s0 < nsplit; s0 += SU) {
-        float part[SU][16];
-#pragma unroll
-        for (int u = 0; u < SU; ++u) {
-            const float *src = g.partial + (((int64_t)blockIdx.z * nsplit + s0 + u) * ntiles + tile_linear) * (64 * THREADS);
-#pragma unroll
-            for (int e = 0; e < 16; ++e)
-                part[u][e] = (s0 + u < nsplit) ? src[((e >> 2) * 16 + 4 * q + (e & 3)) * THREADS + tid] : 0.f;
-        }
-#pragma unroll
-        for (int u = 0; u < SU; ++u) {
-            if (s0 + u >= nsplit) break;          // uniform; adding the zeros would turn -0 sums into +0
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sum[e] += part[u][e];
-        }
-    }
-    const bool mirror = (g.flags & F_MIRROR) && (tm != tn);
-    g.C += (int64_t)blockIdx.z * g.strideC;
-    switch (q) {
-        case 0: reduce_epilogue<0>(sum, g, tm, tn, mirror, wm, wn, lane); break;
-        case 1: reduce_epilogue<1>(sum, g, tm, tn, mirror, wm, wn, lane); break;
-        case 2: reduce_epilogue<2>(sum, g, tm, tn, mirror, wm, wn, lane); break;
-        default: reduce_epilogue<3>(sum, g, tm, tn, mirror, wm, wn, lane); break;
-    }
-}
-
 // Host-side launch of a full (non split-K) product.  `batch` >= 1.
 template <int AMODE, int BMODE, bool VEC, bool KGUARD, bool DOT = false>
 inline hipError_t launch(Args g, int batch, hipStream_t stream) {
@@ -536,20 +511,19 @@ inline hipError_t launch(Args g, int batch, hipStream_t stream) {
     return hipGetLastError();
 }
 
-// A product whose tile list alone cannot fill the chip: `nsplit` workgroups share every tile's k range, a
-// second launch adds their accumulators in split order and applies the epilogue.  `partial` must hold
-// nsplit * tiles * batch accumulator sets of 64 * THREADS floats.
+// A product whose tile list alone cannot fill the chip: `nsplit` workgroups share every tile's k range and the last of
+// them to finish adds their accumulators in split order and applies the epilogue (FUSED above).  `partial` must hold
+// nsplit * tiles * batch accumulator sets of 64 * THREADS floats, `tile_counters` tiles * batch zeros.
 template <int AMODE, int BMODE, bool VEC, bool KGUARD>
 inline hipError_t launch_splitk(Args g, int batch, int nsplit, hipStream_t stream) {
     if (nsplit <= 1) return launch<AMODE, BMODE, VEC, KGUARD>(g, batch, stream);
     if (g.M <= 0 || g.N <= 0 || batch <= 0) return hipSuccess;
+    if (!g.partial || !g.tile_counters) return hipErrorInvalidValue;
     const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     g.tiles_n = tiles_n;
     const int tiles = (g.flags & F_TRI_GRID) ? tiles_m * (tiles_m + 1) / 2 : tiles_m * tiles_n;
     g.flags |= F_PARTIAL | F_SPLIT_TILE_RANGE;
-    hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD>), dim3(tiles, nsplit, batch), dim3(THREADS), 0, stream, g);
-    g.flags &= ~(F_PARTIAL | F_SPLIT_TILE_RANGE);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3(tiles, 4, batch), dim3(THREADS), 0, stream, g, nsplit, tiles);
+    hipLaunchKernelGGL((gemm_kernel<AMODE, BMODE, VEC, KGUARD, false, 0, true>), dim3(tiles, nsplit, batch), dim3(THREADS), 0, stream, g);
     return hipGetLastError();
 }
 
