@@ -350,6 +350,38 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
                 if (alive_own[r0] | alive_own[r0 + 1] | alive_own[r0 + 2] | alive_own[r0 + 3]) rows_live |= 1u << x;
             }
         }
+        if (FLUSH_RGC == 1 && live_list && k == bmax) {
+            // The common case (a full block, one row group, a list of live columns) as straight-line code: nothing
+            // about a request depends on the lane any more -- a lane past the end of the list asks for the list's
+            // last column and keeps the result to itself, a lane whose four rows are dead asks anyway -- so the
+            // requests of a tile go out back to back, the A fragments are read from LDS in batches ahead of the
+            // matrix instructions that use them, and those follow one another with five requests in flight ahead of
+            // them.  (The general form below compiles to a test around every request and a full wait in front of every
+            // matrix instruction.)
+            const bool rows_ok = (rows_live & 1u) != 0;
+            for (int ct = wave; ct < ntiles; ct += NW) {
+                const int li = ct * 16 + cl16;
+                const bool col_ok = li < nlist;
+                const int c = (int)live_list[col_ok ? li : nlist - 1];
+                double *pc = P + (size_t)c * cp + g0 + 4 * q4;
+                doublex4 acc = *reinterpret_cast<const doublex4 *>(pc);
+                const unsigned voff = ((unsigned)q4 * (unsigned)d + (unsigned)c) * (unsigned)sizeof(double);
+#pragma unroll
+                for (int h = 0; h < BROWS / 4; h += FLUSH_KB) {
+                    double bv[FLUSH_KB], av[FLUSH_KB];
+#pragma unroll
+                    for (int e = 0; e < FLUSH_KB; ++e) {
+                        const char *base = reinterpret_cast<const char *>(Ub + (size_t)(h + e) * 4 * d);
+                        bv[e] = __hip_atomic_load(reinterpret_cast<const double *>(base + voff), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+#pragma unroll
+                    for (int e = 0; e < FLUSH_KB; ++e) av[e] = coefa[(h + e) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < FLUSH_KB; ++e) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av[e], bv[e], acc, 0, 0, 0);
+                }
+                if (col_ok && rows_ok) *reinterpret_cast<doublex4 *>(pc) = acc;
+            }
+        } else
         for (int ct = wave; ct < ntiles; ct += NW) {
             int c = ct * 16 + cl16;
             bool col_ok;
