@@ -359,13 +359,34 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
             // them.  (The general form below compiles to a test around every request and a full wait in front of every
             // matrix instruction.)
             const bool rows_ok = (rows_live & 1u) != 0;
-            for (int ct = wave; ct < ntiles; ct += NW) {
+            // the panel entries of the next tile are asked for before this tile's pending rows: two tiles of the panel
+            // in flight per wavefront (the flush is bound by the panel's read-modify-write)
+            int ct = wave, c_next = 0;
+            bool ok_next = false;
+            doublex4 acc_next = {0.0, 0.0, 0.0, 0.0};
+            if (ct < ntiles) {
                 const int li = ct * 16 + cl16;
-                const bool col_ok = li < nlist;
-                const int c = (int)live_list[col_ok ? li : nlist - 1];
+                ok_next = li < nlist;
+                c_next = (int)live_list[ok_next ? li : nlist - 1];
+                acc_next = *reinterpret_cast<const doublex4 *>(P + (size_t)c_next * cp + g0 + 4 * q4);
+            }
+            while (ct < ntiles) {
+                const int c = c_next;
+                const bool col_ok = ok_next;
+                doublex4 acc = acc_next;
                 double *pc = P + (size_t)c * cp + g0 + 4 * q4;
-                doublex4 acc = *reinterpret_cast<const doublex4 *>(pc);
+                const int ctn = ct + NW;
+                if (ctn < ntiles) {
+                    const int li = ctn * 16 + cl16;
+                    ok_next = li < nlist;
+                    c_next = (int)live_list[ok_next ? li : nlist - 1];
+                    acc_next = *reinterpret_cast<const doublex4 *>(P + (size_t)c_next * cp + g0 + 4 * q4);
+                }
                 const unsigned voff = ((unsigned)q4 * (unsigned)d + (unsigned)c) * (unsigned)sizeof(double);
+                // the A fragments are read again for every tile (an opaque lane index keeps them from being held in
+                // thirty-two registers across the whole loop, which the second tile in flight needs)
+                int alane = lane;
+                asm volatile("" : "+v"(alane));
 #pragma unroll
                 for (int h = 0; h < BROWS / 4; h += FLUSH_KB) {
                     double bv[FLUSH_KB], av[FLUSH_KB];
@@ -375,11 +396,12 @@ __device__ __forceinline__ void flush_panel(double *__restrict__ P, const double
                         bv[e] = __hip_atomic_load(reinterpret_cast<const double *>(base + voff), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
 #pragma unroll
-                    for (int e = 0; e < FLUSH_KB; ++e) av[e] = coefa[(h + e) * 64 + lane];
+                    for (int e = 0; e < FLUSH_KB; ++e) av[e] = coefa[(h + e) * 64 + alane];
 #pragma unroll
                     for (int e = 0; e < FLUSH_KB; ++e) acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av[e], bv[e], acc, 0, 0, 0);
                 }
                 if (col_ok && rows_ok) *reinterpret_cast<doublex4 *>(pc) = acc;
+                ct = ctn;
             }
         } else
         for (int ct = wave; ct < ntiles; ct += NW) {
