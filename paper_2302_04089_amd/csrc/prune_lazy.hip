@@ -67,11 +67,13 @@ constexpr int IDX_NONE = -1;             // workgroup has no live column
 constexpr int IDX_ERROR = -2;            // workgroup met a non-positive diagonal entry
 constexpr int MAX_CPB = 250;             // the local column index travels in 8 bits
 constexpr int MAX_D = 65535;             // the global column index travels in 16 bits of the comparison key
-// 64-bit words between the candidate slots of two workgroups: every slot has a 128-byte line of its own.  Packed
-// eight to a line, the sixteen writers of a line and the 256 x 8 readers polling it delay one another (an
-// all-to-all exchange of 256 workgroups: 2.5 us per round packed, 2.1 us with a line per slot).
+// 64-bit words between the candidate slots of two workgroups: every slot has a 32-byte sector of its own, four slots
+// share a 128-byte line.  Every workgroup polls every slot, and the polls load the fabric: with a line per slot a
+// wavefront's poll is 64 line requests, with four slots per line 16; closer than a sector the writers of neighbouring
+// slots and the readers polling them delay one another.  Loop at 768 x 3072 by words per slot: 16 -> 12.69 ms,
+// 8 -> 12.55, 4 -> 12.34, 2 -> 12.45, 1 -> 13.15.
 #ifndef ZIPLM_SLOT_STRIDE
-#define ZIPLM_SLOT_STRIDE 16
+#define ZIPLM_SLOT_STRIDE 4
 #endif
 constexpr int SLOT_STRIDE = ZIPLM_SLOT_STRIDE;
 
