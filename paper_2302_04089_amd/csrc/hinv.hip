@@ -134,10 +134,12 @@ __device__ __forceinline__ void potrf_columns(float (&a)[NB], int lane, float (*
 // L21 L21^T from the matrix cores at once -- sixteen instructions instead of a thousand multiply-adds spread over the
 // column steps -- and goes back to the rows' registers through the part of Lt that the second half has not written
 // yet (skewed by the row, so that neither the scatter nor the gather meets a bank conflict).
-__device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
+constexpr int HB = NB / 2;
+// First half: afterwards columns 0 .. 31 of the factor are final for all 64 rows (in a[], in Lt[0 .. 31][*], and
+// *my_rdiag for lanes below 32), so whoever solves rows against this block can start on those columns.
+__device__ __forceinline__ void potrf64_first_half(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
     first_bad = -1;
     my_rdiag = 1.f;
-    constexpr int HB = NB / 2;
     potrf_columns<0, HB>(a, lane, Lt, my_rdiag, first_bad);
     {
         const int r = lane & 31, half = lane >> 5;
@@ -163,6 +165,8 @@ __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, f
             for (int c = 0; c < HB; ++c) a[HB + c] -= scratch[r * NB + ((c + r) & 31)];
         }
     }
+}
+__device__ __forceinline__ void potrf64_second_half(float (&a)[NB], int lane, float (*Lt)[NB], float &my_rdiag, int &first_bad) {
     potrf_columns<HB, NB>(a, lane, Lt, my_rdiag, first_bad);
 }
 
@@ -171,14 +175,19 @@ __device__ __forceinline__ void potrf64_in_registers(float (&a)[NB], int lane, f
 // rows of Lt are read with 128-bit broadcast reads, and the whole row j + 1 is asked for before row j is used:
 // with one read in flight at a time (what the compiler makes of the plain loop) every read's latency is exposed,
 // five hundred times per row.
-__device__ __forceinline__ void solve_row_in_registers(float (&x)[NB], const float (*Lt)[NB], const float *rdiag) {
+// Columns J0 .. J1 - 1 of the substitution (every later entry of the row is updated): the two halves of a block run
+// one after the other give the same operations in the same order as one pass, and the first can start as soon as the
+// first half of the block's factor exists.
+template <int J0, int J1>
+__device__ __forceinline__ void solve_row_columns(float (&x)[NB], const float (*Lt)[NB], const float *rdiag) {
     gemm::floatx4 lcur[NB / 4], lnext[NB / 4];
-    float rcur = rdiag[0], rnext = 0.f;
+    float rcur = rdiag[J0], rnext = 0.f;
 #pragma unroll
-    for (int c4 = 0; c4 < NB / 4; ++c4) lcur[c4] = *reinterpret_cast<const gemm::floatx4 *>(&Lt[0][4 * c4]);
+    for (int c4 = 0; c4 < NB / 4; ++c4)
+        if (4 * c4 + 3 > J0) lcur[c4] = *reinterpret_cast<const gemm::floatx4 *>(&Lt[J0][4 * c4]);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        if (j + 1 < NB) {
+    for (int j = J0; j < J1; ++j) {
+        if (j + 1 < J1) {
             rnext = rdiag[j + 1];
 #pragma unroll
             for (int c4 = 0; c4 < NB / 4; ++c4)
@@ -255,26 +264,23 @@ __global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1
     float *Xg = A + (int64_t)(k0 + PW + row0) * ld + k0;          // this workgroup's rows of the panel
     int bad1 = -1, bad2 = -1;
 
-    // ---- first diagonal block in registers || everything else staged in LDS
+    // Every 64-column factorisation runs in two halves with a workgroup barrier between them: once the first 32
+    // columns of a block's factor exist, the wavefronts that solve rows against the block start on those columns
+    // while wavefront 0 factors the other 32, and only the second half of the substitution is left behind the
+    // factorisation (same operations in the same order as one pass: the results do not change).
+    float a[NB];            // wavefront 0: the diagonal block being factored, one row per lane
+    float x[NB];            // wavefronts 1-3: the row being solved
+    float my_rdiag = 1.f;
+
+    // ---- stage 0: first half of L11 || everything else staged in LDS
     if (wave == 0) {
-        float a[NB];
 #pragma unroll
         for (int c = 0; c < NB; c += 4) {
             const gemm::floatx4 v = *reinterpret_cast<const gemm::floatx4 *>(Ab + (int64_t)lane * ld + c);
             a[c] = v[0]; a[c + 1] = v[1]; a[c + 2] = v[2]; a[c + 3] = v[3];
         }
-        float my_rdiag;
-        potrf64_in_registers(a, lane, S.Lt1, my_rdiag, bad1);
-        S.rd1[lane] = my_rdiag;
-        if (blockIdx.x == 0) {
-#pragma unroll
-            for (int c = 0; c < NB; c += 4) {
-                gemm::floatx4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) v[e] = (c + e <= lane) ? a[c + e] : 0.f;
-                *reinterpret_cast<gemm::floatx4 *>(Ldiag + lane * NB + c) = v;
-            }
-        }
+        potrf64_first_half(a, lane, S.Lt1, my_rdiag, bad1);
+        S.rd1[lane] = my_rdiag;                 // final for lanes below 32
     } else {
         const int t = tid - 64, nt = PANEL_THREADS - 64;
         // A21 and A22 of the diagonal block: 64 rows x 16 pieces of four floats each
@@ -296,21 +302,39 @@ __global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1
     }
     __syncthreads();
 
-    // ---- against L11: the block below it (wavefront 1) and the first half of the workgroup's rows (wavefronts 2, 3)
+    // ---- stage 1: second half of L11 || against its first 32 columns: the block below it (wavefront 1) and the first
+    // half of the workgroup's rows (wavefronts 2, 3)
+    float *rowp1 = (wave == 1) ? &S.Lm[lane][0] : &S.Xs[(tid - 128) & (PANEL_ROWS - 1)][0];
+    if (wave == 0) {
+        potrf64_second_half(a, lane, S.Lt1, my_rdiag, bad1);
+        S.rd1[lane] = my_rdiag;
+        if (blockIdx.x == 0) {
+#pragma unroll
+            for (int c = 0; c < NB; c += 4) {
+                gemm::floatx4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = (c + e <= lane) ? a[c + e] : 0.f;
+                *reinterpret_cast<gemm::floatx4 *>(Ldiag + lane * NB + c) = v;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) x[c] = rowp1[c];
+        solve_row_columns<0, HB>(x, S.Lt1, S.rd1);
+    }
+    __syncthreads();
+
+    // ---- stage 2: against the other 32 columns of L11
     if (wave >= 1) {
-        float *rowp = (wave == 1) ? &S.Lm[lane][0] : &S.Xs[tid - 128][0];
-        float x[NB];
+        solve_row_columns<HB, NB>(x, S.Lt1, S.rd1);
 #pragma unroll
-        for (int c = 0; c < NB; ++c) x[c] = rowp[c];
-        solve_row_in_registers(x, S.Lt1, S.rd1);
-#pragma unroll
-        for (int c = 0; c < NB; ++c) rowp[c] = x[c];
+        for (int c = 0; c < NB; ++c) rowp1[c] = x[c];
     }
     __syncthreads();
 
     // ---- matrix cores: D22 -= L21 L21^T (lower 32 x 32 tiles 0-2) and Xs[:, 64:128] -= Xs[:, 0:64] L21^T (tiles 3-10).
     // Only the first three are needed by the factorisation of D22 that follows: they and one more go first, the other
-    // seven are done by wavefronts 1-3 while wavefront 0 factors.
+    // seven are done by wavefronts 1-3 while wavefront 0 factors the first half.
     auto downdate_tile = [&](int tile) {
         if (tile < 3) {
             const int ti = (tile == 0) ? 0 : 1, tj = (tile == 2) ? 1 : 0;
@@ -323,15 +347,22 @@ __global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1
     downdate_tile(wave);
     __syncthreads();
 
-    // ---- second diagonal block in registers || the remaining coupling tiles
+    // ---- stage 4: first half of L22 || the remaining coupling tiles
     if (wave != 0) {
         for (int tile = 3 + wave; tile < 11; tile += 3) downdate_tile(tile);
     } else {
-        float a[NB];
 #pragma unroll
         for (int c = 0; c < NB; ++c) a[c] = S.D22[lane][c];
-        float my_rdiag;
-        potrf64_in_registers(a, lane, S.Lt2, my_rdiag, bad2);
+        potrf64_first_half(a, lane, S.Lt2, my_rdiag, bad2);
+        S.rd2[lane] = my_rdiag;
+    }
+    __syncthreads();
+
+    // ---- stage 5: second half of L22 || the second half of the workgroup's rows against its first 32 columns
+    // (wavefronts 2, 3); workgroup 0 meanwhile stores the block below L11
+    float *rowp2 = &S.Xs[(tid - 128) & (PANEL_ROWS - 1)][NB];
+    if (wave == 0) {
+        potrf64_second_half(a, lane, S.Lt2, my_rdiag, bad2);
         S.rd2[lane] = my_rdiag;
         if (blockIdx.x == 0) {
 #pragma unroll
@@ -346,22 +377,20 @@ __global__ __launch_bounds__(PANEL_THREADS) __attribute__((amdgpu_waves_per_eu(1
             if (bad1 >= 0) *info = 1 + k0 + bad1;
             else if (bad2 >= 0) *info = 1 + k0 + NB + bad2;
         }
+    } else if (wave >= 2) {
+#pragma unroll
+        for (int c = 0; c < NB; ++c) x[c] = rowp2[c];
+        solve_row_columns<0, HB>(x, S.Lt2, S.rd2);
+    } else if (blockIdx.x == 0) {
+        for (int e = lane; e < NB * NB; e += 64) Loff[e] = S.Lm[e >> 6][e & 63];
     }
     __syncthreads();
 
-    // ---- against L22: second half of the workgroup's rows; workgroup 0 meanwhile stores the diagonal factor
-    if (tid < PANEL_ROWS) {
-        float *rowp = &S.Xs[tid][NB];
-        float x[NB];
+    // ---- stage 6: against the other 32 columns of L22
+    if (wave >= 2) {
+        solve_row_columns<HB, NB>(x, S.Lt2, S.rd2);
 #pragma unroll
-        for (int c = 0; c < NB; ++c) x[c] = rowp[c];
-        solve_row_in_registers(x, S.Lt2, S.rd2);
-#pragma unroll
-        for (int c = 0; c < NB; ++c) rowp[c] = x[c];
-    } else if (blockIdx.x == 0) {
-        for (int e = tid - PANEL_ROWS; e < NB * NB; e += PANEL_THREADS - PANEL_ROWS) {
-            Loff[e] = S.Lm[e >> 6][e & 63];
-        }
+        for (int c = 0; c < NB; ++c) rowp2[c] = x[c];
     }
     __syncthreads();
     for (int e = tid; e < PANEL_ROWS * (PW / 4); e += PANEL_THREADS) {
