@@ -585,7 +585,8 @@ static HinvLayout hinv_layout(int d_col, void *ws) {
     l.lambda = c.take<double>(1);
     {
         const int tm = l.dp / gemm::BM;
-        l.ncounters = tm * (tm + 1) / 2 + 256;       // the lower tiles of a full-size product, or the 256 tiles at most of a split merge
+        // the lower tiles of a full-size product, the 256 tiles at most of a split merge, the range boundaries of the residual
+        l.ncounters = tm * (tm + 1) / 2 + dgemm::RESIDUAL_MAX_WORKGROUPS;
         l.counters = c.take<int>((size_t)l.ncounters);
     }
     l.info = c.take<int>(kInfoWords);
@@ -729,6 +730,7 @@ extern "C" int ziplm_hinv(const float *H, float *Hinv, int d_col, float damp_rel
             r.rmax_bits = reinterpret_cast<unsigned *>(l.info + 2 + step);
             r.n_valid = d_col;
             r.gate = gate; r.gate_above = above;
+            r.counters = l.counters;
             ZIPLM_HIP_TRY(dgemm::launch_residual(r, l.resid_workgroups, st));
         }
         Args c = {};

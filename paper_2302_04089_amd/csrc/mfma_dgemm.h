@@ -37,7 +37,7 @@ struct ResidualArgs {
     // A range that starts or ends inside a tile leaves its part of that tile as partial sums in `scratch` (two sets
     // of accumulators per workgroup: [2 w] for the tail of the tile its range starts in, [2 w + 1] for the head of
     // the tile it ends in).  The launch uses at most one workgroup per tile, so a tile is shared by two workgroups
-    // at most: a second launch adds head and tail, always in that order, and writes those tiles.
+    // at most: the one of the two that finishes second adds head and tail, always in that order, and writes the tile.
     double *scratch;       // [2 * workgroups][64 accumulators][256 threads]
     // Largest |R_ij| over the n_valid x n_valid block that holds the caller's matrix (the rest is padding), as the
     // bit pattern of a non-negative float, raised with an unsigned atomic maximum; NaN counts as infinity.  One
@@ -47,6 +47,8 @@ struct ResidualArgs {
     // optional gate, as in gemm::Args: nothing happens unless *gate > gate_above
     const unsigned *gate;
     unsigned gate_above;
+    // one arrival counter per boundary between two ranges, zero before the launch and zero again after it
+    int *counters;
 };
 
 __device__ __forceinline__ void residual_note_max(float local, unsigned *rmax_bits) {
@@ -136,20 +138,61 @@ __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs
         }
 
         if (k0 > 0 || k1 < nslices) {
-            // part of a tile: leave the partial sums for the second launch.  One running pointer, advanced behind an
-            // opaque step: sixty-four addresses computed ahead of the stores (their offsets exceed what an instruction
-            // can encode) would need more registers than are left.
-            double *dst = g.scratch + ((size_t)2 * w + (k0 > 0 ? 0 : 1)) * (64 * gemm::THREADS) + tid;
+            // Part of a tile, which this range shares with a neighbour (a tail continues the tile that range w - 1
+            // began, a head begins the tile that range w + 1 continues).  The partial sums are written through to memory
+            // and the workgroup counts itself at the boundary; of the two, the one that counts second reads both sets
+            // back and finishes the tile: head + tail, in that order whoever is second.  One running pointer, advanced
+            // behind an opaque step: sixty-four addresses computed ahead of the stores (their offsets exceed what an
+            // instruction can encode) would need more registers than are left.
+            const bool is_tail = k0 > 0;
+            const int boundary = is_tail ? w - 1 : w;
+            double *dst = g.scratch + ((size_t)2 * w + (is_tail ? 0 : 1)) * (64 * gemm::THREADS) + tid;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
-                        *dst = acc[i][j][v];
+                        __hip_atomic_store(dst, acc[i][j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         dst += gemm::THREADS;
                         asm volatile("" : "+v"(dst));
                     }
+            __builtin_amdgcn_s_waitcnt(0);          // acknowledged, for every thread, before the workgroup counts itself
+            __syncthreads();
+            int *ticket = reinterpret_cast<int *>(&lds[0][0][0]);
+            if (tid == 0) *ticket = __hip_atomic_fetch_add(g.counters + boundary, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            if (*ticket != 1) continue;             // uniform: the neighbour will finish the tile
+            if (tid == 0) __hip_atomic_store(g.counters + boundary, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const double *head = g.scratch + ((size_t)2 * boundary + 1) * (64 * gemm::THREADS) + tid;
+            const double *tail = g.scratch + ((size_t)2 * (boundary + 1)) * (64 * gemm::THREADS) + tid;
+            float rmax2 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int col = tn * gemm::BN + wn * 64 + j * 16 + cl16;
+                    double sum[4];
+                    float xv[4];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
+                        sum[v] = __hip_atomic_load(head, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
+                                 __hip_atomic_load(tail, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        head += gemm::THREADS;
+                        tail += gemm::THREADS;
+                        asm volatile("" : "+v"(head), "+v"(tail));
+                        xv[v] = g.X[(int64_t)row * g.ldx + col];
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
+                        const double r = ((row == col) ? 1.0 : 0.0) - sum[v] - lam * (double)xv[v];
+                        g.R[(int64_t)row * g.ldr + col] = (float)r;
+                        if (row < g.n_valid && col < g.n_valid) rmax2 = fmaxf(rmax2, residual_magnitude(r));
+                    }
+                }
+            residual_note_max(rmax2, g.rmax_bits);
             continue;
         }
 
@@ -177,50 +220,6 @@ __global__ __launch_bounds__(gemm::THREADS, 2) void residual_kernel(ResidualArgs
     }
 }
 
-// Second launch: workgroup w < G - 1 looks at the boundary between ranges w and w + 1; if it falls inside a tile, the
-// tile is the sum of the head left by w and the tail left by w + 1.  Same thread <-> element mapping as above.
-__global__ __launch_bounds__(gemm::THREADS) void residual_fixup_kernel(ResidualArgs g, int G) {
-    if (gemm::gate_closed(g.gate, g.gate_above)) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int cl16 = lane & 15, q4 = lane >> 4;
-    const int tiles_n = g.n / gemm::BN;
-    const int nslices = g.n / gemm::BK;
-    const int w = blockIdx.x;
-    const long long total = (long long)tiles_n * tiles_n * nslices;
-    const long long u1 = residual_range_begin(total, w + 1, G);
-    if (u1 % nslices == 0) return;
-    const int tile = (int)(u1 / nslices);
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
-    const double lam = *g.lambda;
-    const double *head = g.scratch + ((size_t)2 * w + 1) * (64 * gemm::THREADS) + tid;
-    const double *tail = g.scratch + ((size_t)2 * (w + 1)) * (64 * gemm::THREADS) + tid;
-    float rmax = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int col = tn * gemm::BN + wn * 64 + j * 16 + cl16;
-            double sum[4];
-            float xv[4];
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
-                const size_t e = (size_t)((i * 4 + j) * 4 + v) * gemm::THREADS;
-                sum[v] = head[e] + tail[e];
-                xv[v] = g.X[(int64_t)row * g.ldx + col];
-            }
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int row = tm * gemm::BM + wm * 64 + i * 16 + 4 * v + q4;
-                const double r = ((row == col) ? 1.0 : 0.0) - sum[v] - lam * (double)xv[v];
-                g.R[(int64_t)row * g.ldr + col] = (float)r;
-                if (row < g.n_valid && col < g.n_valid) rmax = fmaxf(rmax, residual_magnitude(r));
-            }
-        }
-    residual_note_max(rmax, g.rmax_bits);
-}
-
 // Workgroups of the first launch: at most one per tile (a tile is then shared by two workgroups at most), at most
 // `slots` (what the device runs at once).
 inline int residual_workgroups(int n, int slots) {
@@ -231,11 +230,8 @@ constexpr int RESIDUAL_MAX_WORKGROUPS = 1024;
 inline size_t residual_scratch_doubles(int workgroups) { return (size_t)2 * workgroups * 64 * gemm::THREADS; }
 
 inline hipError_t launch_residual(const ResidualArgs &g, int workgroups, hipStream_t stream) {
+    if (!g.counters) return hipErrorInvalidValue;
     hipLaunchKernelGGL(residual_kernel, dim3(workgroups), dim3(gemm::THREADS), 0, stream, g);
-    // whole tiles per workgroup: every range ends on a tile boundary and nothing is left to add
-    const int tiles = (g.n / gemm::BM) * (g.n / gemm::BN);
-    if (tiles % workgroups != 0)
-        hipLaunchKernelGGL(residual_fixup_kernel, dim3(workgroups - 1), dim3(gemm::THREADS), 0, stream, g, workgroups);
     return hipGetLastError();
 }
 
